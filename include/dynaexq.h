@@ -1,0 +1,232 @@
+/*
+ * dynaexq.h -- C ABI of the MI355X (gfx950) hot path of DynaExq
+ * (arXiv 2511.15015): the routed MoE expert forward over a per-(layer,
+ * expert) table of stable handles, each expert either a resident bf16
+ * version or a group-quantized int4 version, plus the control pieces around
+ * it (hotness counting, budget-feasible top-n selection, the demotion
+ * quantizer, publication of new versions between forward passes).
+ *
+ * Conventions for every call
+ *   - "dev" pointers are HIP device pointers on the context's GPU, "host"
+ *     pointers are ordinary host memory, "pinned" is page-locked host memory.
+ *   - Tensors are caller-allocated and caller-owned; the library keeps no
+ *     reference past the call, except for the targets of published handles,
+ *     which must stay valid while they are published.
+ *   - Device work is enqueued on the compute stream given to dx_create and is
+ *     asynchronous to the host unless the call returns host data.
+ *   - Errors are return codes; a failing call has no side effect.  The text of
+ *     the last error of a context is available from dx_last_error.
+ *   - bf16 is the 16-bit truncated-fp32 format; tensors are row-major.
+ */
+#ifndef DYNAEXQ_H
+#define DYNAEXQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dx_ctx dx_ctx; /* opaque, owned by the library */
+
+typedef enum {
+    DX_OK = 0,
+    DX_ERR_INVALID = 1, /* bad argument: null pointer, id/shape out of range, K % group != 0 ... */
+    DX_ERR_BUDGET = 2,  /* the byte budget / high-precision capacity does not admit the request */
+    DX_ERR_BUSY = 3,    /* the expert is in transition, or the producer of a version has not finished */
+    DX_ERR_NOMEM = 4,   /* host or device allocation failed, or a pool has no free block */
+    DX_ERR_HIP = 5      /* a HIP runtime call failed */
+} dx_status;
+
+/* numeric format of one stored expert version (Sec. 3.2: "multiple weight
+ * versions that implement the same operator in different numeric formats") */
+typedef enum { DX_FMT_BF16 = 0, DX_FMT_INT4G = 1 } dx_fmt;
+
+/* residency state of an expert entry (Sec. 3.2, "Residency states") */
+typedef enum {
+    DX_STATE_EMPTY = 0,      /* no version published yet */
+    DX_STATE_RESIDENT_HI = 1,
+    DX_STATE_RESIDENT_LO = 2,
+    DX_STATE_PROMOTING = 3,  /* hi version being materialised; handle still resolves to the old one */
+    DX_STATE_DEMOTING = 4    /* lo version being materialised; handle still resolves to the old one */
+} dx_state;
+
+typedef struct {
+    int32_t L;            /* MoE layers */
+    int32_t E;            /* routed experts per layer */
+    int32_t d;            /* hidden size (multiple of 32) */
+    int32_t f;            /* expert intermediate size (multiple of 32) */
+    int32_t top_k;        /* experts per token, 1..min(E,64) */
+    int32_t group;        /* int4 group size along K: 32, 64 or 128; d and f are multiples of it */
+    int32_t shared_f;     /* intermediate size of the always-bf16 shared expert, 0 = none */
+    int32_t max_tokens;   /* largest T a call will pass; sizes the scratch buffers */
+    int32_t window_steps; /* informational: forward passes per hotness window */
+    uint32_t alpha_q16;   /* EMA factor alpha * 65536, 0 <= alpha_q16 < 65536 (Sec. 3.5) */
+    uint64_t budget_bytes;    /* expert-weight budget of the whole stack, steady state */
+    uint64_t transient_bytes; /* extra bytes in-flight transitions may hold on top of it */
+} dx_config;
+
+/* Device-visible expert handle (Sec. 3.2, "Expert entries and stable
+ * handles").  The table entry's address is the handle's identity and never
+ * changes; its contents are the "active pointer" plus quantization
+ * parameters and are replaced as a whole by dx_swap_handle.
+ *   bf16:  w_gate, w_up [f,d] bf16, w_down [d,f] bf16, s_* = NULL
+ *   int4:  w_gate, w_up [f,d/2] u8, w_down [d,f/2] u8 (element 2i in the low
+ *          nibble of byte i, two's complement), s_gate, s_up [f,d/group]
+ *          bf16, s_down [d,f/group] bf16.
+ * All pointers 16-byte aligned. */
+typedef struct {
+    const void *w_gate, *w_up, *w_down;
+    const void *s_gate, *s_up, *s_down;
+    uint32_t fmt;     /* dx_fmt */
+    uint32_t version; /* increases with every publication */
+    uint64_t reserved;
+} dx_handle; /* 64 bytes */
+
+typedef struct {
+    uint64_t promotions_issued, promotions_published;
+    uint64_t demotions_issued, demotions_published;
+    uint64_t h2d_bytes;            /* bytes copied from pinned host memory by promotions */
+    uint64_t quantize_read_bytes;  /* bf16 bytes read by demotion quantize kernels */
+    uint64_t quantize_write_bytes; /* int4 + scale bytes they wrote */
+    uint64_t reserved_bytes;       /* budget tracker: bytes currently reserved */
+    uint64_t peak_reserved_bytes;
+    uint64_t deferred;             /* transitions refused by admission control */
+} dx_stats;
+
+/* ------------------------------------------------------------------ context */
+/* Creates a context on the current HIP device.  `hip_compute_stream` is a
+ * hipStream_t (NULL = the null stream).  Allocates the handle tables
+ * (L*E routed + L shared entries), the window counters, the routing and
+ * forward scratch for max_tokens, and a migration stream. */
+dx_status dx_create(const dx_config *cfg, void *hip_compute_stream, dx_ctx **out);
+void dx_destroy(dx_ctx *ctx);
+const char *dx_last_error(const dx_ctx *ctx);
+const char *dx_status_str(dx_status s);
+
+/* ----------------------------------------------------------- the hot path */
+/* Router top-k and token permutation (Sec. 3.1: "each request invokes the
+ * router to obtain top-k expert IDs, which are used to index a handle
+ * table").  logits: dev fp32 [T,E].  Outputs, all dev:
+ *   topk_ids int32 [T,k]  the k largest logits, largest first, ties to the lower index
+ *   topk_w   fp32  [T,k]  softmax over those k logits
+ *   counts   int32 [E]    pairs routed to each expert
+ *   offsets  int32 [E+1]  exclusive prefix sum of counts
+ *   perm     int32 [T*k]  pair indices p = t*k + j grouped by expert, increasing inside a segment
+ * 0 <= T <= max_tokens.  Logits must be finite. */
+dx_status dx_route(dx_ctx *ctx, int layer, const float *logits, int T,
+                   int32_t *topk_ids, float *topk_w,
+                   int32_t *counts, int32_t *offsets, int32_t *perm);
+
+/* Mixed-precision expert execution (Sec. 3.2: "The compute path resolves
+ * the handle to obtain the active pointer and the associated quantization
+ * parameters, then invokes the corresponding kernel").
+ *   y[t] = sum_j topk_w[t,j] * W_down( silu(W_gate x[t]) * (W_up x[t]) )  of expert topk_ids[t,j]
+ *          (+ the layer's shared expert, weight 1, when shared_f > 0)
+ * handle_table: dev, E entries of this layer; NULL = the context's own table
+ * for `layer`.  x_bf16 dev [T,d]; y_bf16 dev [T,d]; routing arrays as written
+ * by dx_route for the same T.  Weights are read through the handles as they
+ * are when the kernels run on the compute stream. */
+dx_status dx_moe_forward(dx_ctx *ctx, int layer, const dx_handle *handle_table,
+                         const void *x_bf16, int T,
+                         const int32_t *topk_ids, const float *topk_w,
+                         const int32_t *offsets, const int32_t *perm, void *y_bf16);
+
+/* Hotness counters (Sec. 3.5, "Hotness Estimation"): c[layer,e] += counts[e].
+ * counts: dev int32 [E]. */
+dx_status dx_hotness_update(dx_ctx *ctx, int layer, const int32_t *counts);
+
+/* End of an update interval (Sec. 3.5): S <- alpha*S + (1-alpha)*c for every
+ * (layer, expert), then c <- 0.  S is kept on the host in units of 2^-16
+ * counts: S <- floor((alpha_q16*S + (65536-alpha_q16)*c*65536) / 65536).
+ * Synchronises the compute stream.  scores_out: host uint64 [L*E] or NULL. */
+dx_status dx_window_end(dx_ctx *ctx, uint64_t *scores_out);
+
+/* Budget-feasible selection (Sec. 3.5, "Budget-feasible Selection"):
+ * n = the largest count with n*b_hi + (E-n)*b_lo <= budget_bytes (this
+ * layer's share), H = the n experts with the largest score S, ties to the
+ * lower index, written to out_ids (host, capacity E) in rank order.
+ * DX_ERR_BUDGET and *out_n = 0 when even the all-int4 layer does not fit. */
+dx_status dx_select_resident(dx_ctx *ctx, int layer, uint64_t budget_bytes,
+                             int32_t *out_ids, int32_t *out_n);
+
+/* The same rule as two pure host functions (no context, no device). */
+uint64_t dx_expert_bytes(int d, int f, int group, int fmt);
+int dx_budget_capacity(uint64_t budget_bytes, int E, uint64_t b_hi, uint64_t b_lo); /* -1: infeasible */
+dx_status dx_select_topn(const uint64_t *scores, int E, int n, int32_t *out_ids);
+
+/* Candidates for residency change (Sec. 3.5): promote = H \ H_cur,
+ * demote = H_cur \ H, where H_cur is the set of experts of `layer` that are
+ * Resident-Hi or Promoting.  Outputs host int32, capacity E each, ascending. */
+dx_status dx_plan_transitions(dx_ctx *ctx, int layer, const int32_t *target_ids, int n_target,
+                              int32_t *promote, int32_t *n_promote,
+                              int32_t *demote, int32_t *n_demote);
+
+/* Demotion quantizer: one matrix bf16 [rows,K] (dev) -> packed int4 u8
+ * [rows,K/2] + bf16 scales [rows,K/group] (dev).  Per group of `group`
+ * consecutive elements along K: scale = bf16_rne(absmax/7) in fp32,
+ * q = clamp(rint(w/scale), -8, 7) (IEEE divide, half to even), 0 when the
+ * scale is 0.  The paper prepares both versions offline (Sec. 4
+ * Implementation); this kernel produces the low-precision version on device.
+ * hip_stream: hipStream_t to run on, NULL = the compute stream. */
+dx_status dx_quantize_expert(dx_ctx *ctx, const void *w_bf16, int rows, int K, int group,
+                             void *q_out, void *s_out, void *hip_stream);
+
+/* Publication (Sec. 3.2, "Non-blocking switching semantics"): replaces the
+ * handle of (layer, expert) with *new_version (host pointer to a struct
+ * holding dev pointers).  The write is ordered on the compute stream, so it
+ * lands between forward passes.  producer_event: hipEvent_t recorded after
+ * the work that fills the new version, or NULL when it is already complete;
+ * DX_ERR_BUSY if that event has not completed.  expert == E addresses the
+ * layer's shared expert. */
+dx_status dx_swap_handle(dx_ctx *ctx, int layer, int expert, const dx_handle *new_version,
+                         void *producer_event);
+
+/* ------------------------------------------------------- table inspection */
+const dx_handle *dx_handle_table(dx_ctx *ctx, int layer); /* dev pointer, E entries */
+dx_status dx_get_handle(dx_ctx *ctx, int layer, int expert, dx_handle *out); /* host copy */
+dx_status dx_get_formats(dx_ctx *ctx, uint8_t *fmt_out /* host [L*E], dx_fmt; 255 = empty */);
+dx_status dx_get_states(dx_ctx *ctx, uint8_t *state_out /* host [L*E], dx_state */);
+dx_status dx_get_counters(dx_ctx *ctx, int64_t *counters_out /* host [L*E] */); /* syncs the compute stream */
+dx_status dx_get_stats(dx_ctx *ctx, dx_stats *out);
+
+/* ------------------------------------------- pools and transitions (Sec. 3.3, 3.4) */
+/* One-time carve-out of the two weight pools: hi_blocks blocks of b_hi bytes
+ * and lo_blocks blocks of b_lo bytes (each rounded up to 256), with
+ * constant-time free lists, plus one bf16-sized staging block. */
+dx_status dx_pools_create(dx_ctx *ctx, int hi_blocks, int lo_blocks);
+
+/* Synchronous set-up: materialise (layer, expert) in `fmt` from bf16 master
+ * matrices gate [f,d], up [f,d], down [d,f] (`src_on_device` != 0: dev
+ * pointers, else host) into a pool block and publish it.  For int4 the
+ * masters are quantized on device.  expert == E installs the shared expert
+ * (bf16 only, intermediate size shared_f). */
+dx_status dx_expert_install(dx_ctx *ctx, int layer, int expert, int fmt,
+                            const void *gate, const void *up, const void *down, int src_on_device);
+
+/* Promotion (Sec. 3.4, "Update/Evict procedure"): reserve b_hi from the
+ * budget tracker, take a block of pool_hi, copy the bf16 masters from pinned
+ * host memory on the migration stream, record a completion event.  The
+ * handle keeps resolving to the int4 version until dx_migrate_poll publishes.
+ * DX_ERR_BUDGET: reservation refused (nothing started); DX_ERR_BUSY: the
+ * expert is not Resident-Lo; DX_ERR_NOMEM: pool_hi has no free block. */
+dx_status dx_promote_async(dx_ctx *ctx, int layer, int expert,
+                           const void *pinned_gate, const void *pinned_up, const void *pinned_down);
+
+/* Demotion: take a block of pool_lo and run the quantizer on the migration
+ * stream over the resident bf16 version; the handle keeps resolving to bf16
+ * until published.  DX_ERR_BUSY: the expert is not Resident-Hi. */
+dx_status dx_demote_async(dx_ctx *ctx, int layer, int expert);
+
+/* Publish every transition whose completion event has fired, in issue order
+ * (wait != 0: block until all in-flight transitions have completed).  The
+ * handle is swapped on the compute stream; the old version's block returns
+ * to its pool and is reused only after the compute stream has passed the
+ * swap.  Call between forward passes. */
+dx_status dx_migrate_poll(dx_ctx *ctx, int wait, int *n_published);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNAEXQ_H */

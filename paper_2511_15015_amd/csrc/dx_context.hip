@@ -1,0 +1,730 @@
+// Host side of libdynaexq.so: context, handle table (Versioned Expert
+// Residency, Sec. 3.2), hotness window and selection (Sec. 3.5), weight pools
+// and budget tracker (Sec. 3.3), and the transition pipeline on a migration
+// stream (Sec. 3.4).  All device arithmetic lives in the kernel files.
+#include "dx_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+namespace {
+
+thread_local std::string g_create_err;
+
+bool valid_layer(const dx_ctx *c, int layer) { return layer >= 0 && layer < c->cfg.L; }
+
+// index of an entry: routed (layer, e<E) or shared (layer, e==E)
+int entry_index(const dx_ctx *c, int layer, int expert)
+{
+    if (expert == c->cfg.E) return c->cfg.L * c->cfg.E + layer;
+    return layer * c->cfg.E + expert;
+}
+
+bool valid_expert(const dx_ctx *c, int expert, bool allow_shared)
+{
+    if (expert >= 0 && expert < c->cfg.E) return true;
+    return allow_shared && c->cfg.shared_f > 0 && expert == c->cfg.E;
+}
+
+size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+dx_status get_event(dx_ctx *c, hipEvent_t *ev)
+{
+    if (!c->event_pool.empty()) {
+        *ev = c->event_pool.back();
+        c->event_pool.pop_back();
+        return DX_OK;
+    }
+    DX_HIP(c, hipEventCreateWithFlags(ev, hipEventDisableTiming));
+    return DX_OK;
+}
+
+// carve a handle out of a pool block; layouts: hi = [gate|up|down] bf16,
+// lo = [q_gate|q_up|q_down|s_gate|s_up|s_down]
+dx_handle handle_in_block(const dx_ctx *c, void *block, int fmt, int f)
+{
+    const size_t d = c->cfg.d, g = c->cfg.group, ff = f;
+    char *p = static_cast<char *>(block);
+    dx_handle h{};
+    h.fmt = fmt;
+    if (fmt == DX_FMT_BF16) {
+        h.w_gate = p;
+        h.w_up = p + ff * d * 2;
+        h.w_down = p + 2 * ff * d * 2;
+    } else {
+        const size_t qm = ff * d / 2, sm = ff * d / g * 2;
+        h.w_gate = p;
+        h.w_up = p + qm;
+        h.w_down = p + 2 * qm;
+        h.s_gate = p + 3 * qm;
+        h.s_up = p + 3 * qm + sm;
+        h.s_down = p + 3 * qm + 2 * sm;
+    }
+    return h;
+}
+
+dx_status pool_take(dx_ctx *c, dx_block_pool &pool, hipStream_t user, int *block)
+{
+    if (pool.free_list.empty()) DX_FAIL(c, DX_ERR_NOMEM, "weight pool has no free block");
+    const int b = pool.free_list.back();
+    pool.free_list.pop_back();
+    if (pool.reuse_after[b]) {
+        // the block was released by a publication; the stream that will write it
+        // must first pass the point where the compute stream stopped reading it
+        hipError_t e = hipStreamWaitEvent(user, pool.reuse_after[b], 0);
+        if (e != hipSuccess) {
+            pool.free_list.push_back(b);
+            DX_FAIL(c, DX_ERR_HIP, "hipStreamWaitEvent: %s", hipGetErrorString(e));
+        }
+        c->event_pool.push_back(pool.reuse_after[b]);
+        pool.reuse_after[b] = nullptr;
+    }
+    *block = b;
+    return DX_OK;
+}
+
+void pool_give(dx_block_pool &pool, int block, hipEvent_t after)
+{
+    pool.reuse_after[block] = after;
+    pool.free_list.push_back(block);
+}
+
+void track_reserve(dx_ctx *c, uint64_t bytes)
+{
+    c->reserved += bytes;
+    c->stats.reserved_bytes = c->reserved;
+    c->stats.peak_reserved_bytes = std::max(c->stats.peak_reserved_bytes, c->reserved);
+}
+
+void track_release(dx_ctx *c, uint64_t bytes)
+{
+    c->reserved -= std::min(bytes, c->reserved);
+    c->stats.reserved_bytes = c->reserved;
+}
+
+// write the entry's handle to the device table, ordered on the compute stream
+dx_status publish(dx_ctx *c, int idx, const dx_handle &h)
+{
+    dx_entry &en = c->entries[idx];
+    dx_handle nh = h;
+    nh.version = en.h.version + 1;
+    nh.reserved = 0;
+    DX_HIP(c, dxk_store_handle(c->d_table + idx, nh, c->compute));
+    en.h = nh;
+    return DX_OK;
+}
+
+} // namespace
+
+// ------------------------------------------------------------- pure host rule
+extern "C" uint64_t dx_expert_bytes(int d, int f, int group, int fmt)
+{
+    if (d <= 0 || f <= 0 || group <= 0) return 0;
+    const uint64_t params = 3ull * (uint64_t)d * (uint64_t)f;
+    if (fmt == DX_FMT_BF16) return params * 2ull;
+    return params / 2ull + (params / (uint64_t)group) * 2ull;
+}
+
+extern "C" int dx_budget_capacity(uint64_t budget, int E, uint64_t b_hi, uint64_t b_lo)
+{
+    if (E <= 0 || b_hi <= b_lo) return -1;
+    const uint64_t floor_bytes = (uint64_t)E * b_lo;
+    if (budget < floor_bytes) return -1;
+    const uint64_t n = (budget - floor_bytes) / (b_hi - b_lo);
+    return n > (uint64_t)E ? E : (int)n;
+}
+
+extern "C" dx_status dx_select_topn(const uint64_t *scores, int E, int n, int32_t *out_ids)
+{
+    if (!scores || E <= 0 || n < 0 || n > E || (n > 0 && !out_ids)) return DX_ERR_INVALID;
+    std::vector<int32_t> order(E);
+    for (int e = 0; e < E; ++e) order[e] = e;
+    std::partial_sort(order.begin(), order.begin() + n, order.end(), [&](int32_t a, int32_t b) {
+        return scores[a] != scores[b] ? scores[a] > scores[b] : a < b;
+    });
+    for (int i = 0; i < n; ++i) out_ids[i] = order[i];
+    return DX_OK;
+}
+
+extern "C" const char *dx_status_str(dx_status s)
+{
+    switch (s) {
+    case DX_OK: return "DX_OK";
+    case DX_ERR_INVALID: return "DX_ERR_INVALID";
+    case DX_ERR_BUDGET: return "DX_ERR_BUDGET";
+    case DX_ERR_BUSY: return "DX_ERR_BUSY";
+    case DX_ERR_NOMEM: return "DX_ERR_NOMEM";
+    case DX_ERR_HIP: return "DX_ERR_HIP";
+    }
+    return "DX_ERR_?";
+}
+
+// -------------------------------------------------------------------- context
+extern "C" dx_status dx_create(const dx_config *cfg, void *stream, dx_ctx **out)
+{
+    if (!cfg || !out) return DX_ERR_INVALID;
+    *out = nullptr;
+    const dx_config &g = *cfg;
+    const bool group_ok = g.group == 32 || g.group == 64 || g.group == 128;
+    if (g.L <= 0 || g.E <= 0 || g.E > 1024 || g.d <= 0 || g.f <= 0 || g.top_k <= 0 || g.top_k > g.E ||
+        g.top_k > 64 || !group_ok || g.d % g.group || g.f % g.group || g.d % 32 || g.f % 32 ||
+        g.shared_f < 0 || g.shared_f % 32 || (g.shared_f && g.shared_f % g.group) || g.max_tokens <= 0 ||
+        g.alpha_q16 >= 65536u || (uint64_t)g.max_tokens * (uint64_t)(g.top_k + 1) > 0x7FFFFFFFull) {
+        g_create_err = "dx_create: invalid configuration";
+        return DX_ERR_INVALID;
+    }
+    dx_ctx *c = new (std::nothrow) dx_ctx;
+    if (!c) return DX_ERR_NOMEM;
+    c->cfg = g;
+    c->compute = static_cast<hipStream_t>(stream);
+    c->b_hi = dx_expert_bytes(g.d, g.f, g.group, DX_FMT_BF16);
+    c->b_lo = dx_expert_bytes(g.d, g.f, g.group, DX_FMT_INT4G);
+    c->b_shared = g.shared_f ? dx_expert_bytes(g.d, g.shared_f, g.group, DX_FMT_BF16) : 0;
+    c->fmax = std::max(g.f, g.shared_f);
+    c->n_chunks_max = (g.max_tokens + 63) / 64;
+    const size_t n_entries = (size_t)g.L * g.E + g.L;
+    const size_t n_rows = (size_t)g.max_tokens * (g.top_k + (g.shared_f ? 1 : 0));
+
+    auto fail = [&](hipError_t e, const char *what) {
+        g_create_err = std::string("dx_create: ") + what + ": " + hipGetErrorString(e);
+        dx_destroy(c);
+        return e == hipErrorOutOfMemory ? DX_ERR_NOMEM : DX_ERR_HIP;
+    };
+    hipError_t e;
+    if ((e = hipGetDevice(&c->device)) != hipSuccess) return fail(e, "hipGetDevice");
+    if ((e = hipStreamCreateWithFlags(&c->mig, hipStreamNonBlocking)) != hipSuccess) return fail(e, "migration stream");
+    if ((e = hipMalloc(&c->d_table, n_entries * sizeof(dx_handle))) != hipSuccess) return fail(e, "handle table");
+    if ((e = hipMalloc(&c->d_counters, (size_t)g.L * g.E * 8)) != hipSuccess) return fail(e, "counters");
+    if ((e = hipHostMalloc(&c->h_counters, (size_t)g.L * g.E * 8, hipHostMallocDefault)) != hipSuccess)
+        return fail(e, "pinned counters");
+    if ((e = hipMalloc(&c->d_mask, (size_t)c->n_chunks_max * g.E * 8)) != hipSuccess) return fail(e, "route masks");
+    if ((e = hipMalloc(&c->d_chunk_base, (size_t)c->n_chunks_max * g.E * 4)) != hipSuccess) return fail(e, "route bases");
+    if ((e = hipMalloc(&c->d_h, n_rows * c->fmax * sizeof(dx_bf16))) != hipSuccess) return fail(e, "H scratch");
+    if ((e = hipMalloc(&c->d_o, n_rows * (size_t)g.d * sizeof(float))) != hipSuccess) return fail(e, "O scratch");
+    // zero the table and the counters with fill kernels on the compute stream
+    if ((e = dxk_fill_u64(reinterpret_cast<unsigned long long *>(c->d_table), n_entries * sizeof(dx_handle) / 8, 0ull,
+                          c->compute)) != hipSuccess)
+        return fail(e, "table fill");
+    if ((e = dxk_fill_u64(c->d_counters, (size_t)g.L * g.E, 0ull, c->compute)) != hipSuccess) return fail(e, "counter fill");
+    if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return fail(e, "sync");
+    c->entries.assign(n_entries, dx_entry{});
+    c->scores.assign((size_t)g.L * g.E, 0);
+    c->hi_count.assign(g.L, 0);
+    // per-layer high-precision capacity from the stack budget (shared experts are fixed cost)
+    if (g.budget_bytes) {
+        const uint64_t fixed = (uint64_t)g.L * c->b_shared;
+        const uint64_t per_layer = g.budget_bytes > fixed ? (g.budget_bytes - fixed) / (uint64_t)g.L : 0;
+        const int n = dx_budget_capacity(per_layer, g.E, c->b_hi, c->b_lo);
+        c->n_hi_cap = n < 0 ? 0 : n;
+    } else {
+        c->n_hi_cap = g.E;
+    }
+    *out = c;
+    return DX_OK;
+}
+
+extern "C" void dx_destroy(dx_ctx *c)
+{
+    if (!c) return;
+    if (c->compute || true) (void)hipStreamSynchronize(c->compute);
+    if (c->mig) {
+        (void)hipStreamSynchronize(c->mig);
+        (void)hipStreamDestroy(c->mig);
+    }
+    for (auto &t : c->inflight) (void)hipEventDestroy(t.done);
+    for (auto ev : c->event_pool) (void)hipEventDestroy(ev);
+    for (dx_block_pool *p : {&c->pool_hi, &c->pool_lo}) {
+        for (auto ev : p->reuse_after)
+            if (ev) (void)hipEventDestroy(ev);
+        if (p->base) (void)hipFree(p->base);
+    }
+    if (c->staging) (void)hipFree(c->staging);
+    if (c->d_table) (void)hipFree(c->d_table);
+    if (c->d_counters) (void)hipFree(c->d_counters);
+    if (c->h_counters) (void)hipHostFree(c->h_counters);
+    if (c->d_mask) (void)hipFree(c->d_mask);
+    if (c->d_chunk_base) (void)hipFree(c->d_chunk_base);
+    if (c->d_h) (void)hipFree(c->d_h);
+    if (c->d_o) (void)hipFree(c->d_o);
+    delete c;
+}
+
+extern "C" const char *dx_last_error(const dx_ctx *c) { return c ? c->err.c_str() : g_create_err.c_str(); }
+
+// ------------------------------------------------------------------- hot path
+extern "C" dx_status dx_route(dx_ctx *c, int layer, const float *logits, int T, int32_t *ids, float *w,
+                              int32_t *counts, int32_t *offsets, int32_t *perm)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_route: layer %d out of range", layer);
+    if (T < 0 || T > c->cfg.max_tokens) DX_FAIL(c, DX_ERR_INVALID, "dx_route: T=%d outside [0,%d]", T, c->cfg.max_tokens);
+    if (!counts || !offsets || (T > 0 && (!logits || !ids || !w || !perm)))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_route: null pointer");
+    DX_HIP(c, dxk_route(logits, T, c->cfg.E, c->cfg.top_k, ids, w, counts, offsets, perm, c->d_mask, c->d_chunk_base,
+                        c->compute));
+    return DX_OK;
+}
+
+extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table, const void *x, int T,
+                                    const int32_t *ids, const float *w, const int32_t *offsets,
+                                    const int32_t *perm, void *y)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: layer %d out of range", layer);
+    if (T < 0 || T > c->cfg.max_tokens)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: T=%d outside [0,%d]", T, c->cfg.max_tokens);
+    if (T == 0) return DX_OK;
+    if (!x || !y || !ids || !w || !offsets || !perm) DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: null pointer");
+    const dx_config &g = c->cfg;
+    if (!table) {
+        // the context's own table: every expert of the layer must have a published version
+        for (int e = 0; e < g.E; ++e)
+            if (c->entries[entry_index(c, layer, e)].state == DX_STATE_EMPTY)
+                DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: expert (%d,%d) has no published version", layer, e);
+        table = c->d_table + (size_t)layer * g.E;
+    }
+    dx_fwd_args a{};
+    a.table = table;
+    a.shared = nullptr;
+    if (g.shared_f) {
+        if (c->entries[entry_index(c, layer, g.E)].state == DX_STATE_EMPTY)
+            DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: shared expert of layer %d not installed", layer);
+        a.shared = c->d_table + entry_index(c, layer, g.E);
+    }
+    a.x = static_cast<const dx_bf16 *>(x);
+    a.y = static_cast<dx_bf16 *>(y);
+    a.ids = ids;
+    a.w = w;
+    a.offsets = offsets;
+    a.perm = perm;
+    a.h = c->d_h;
+    a.o = c->d_o;
+    a.T = T;
+    a.E = g.E;
+    a.k = g.top_k;
+    a.d = g.d;
+    a.f = g.f;
+    a.group = g.group;
+    a.shared_f = g.shared_f;
+    a.fmax = c->fmax;
+    DX_HIP(c, dxk_moe_forward(a, c->compute));
+    return DX_OK;
+}
+
+extern "C" dx_status dx_hotness_update(dx_ctx *c, int layer, const int32_t *counts)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_hotness_update: layer %d out of range", layer);
+    if (!counts) DX_FAIL(c, DX_ERR_INVALID, "dx_hotness_update: null counts");
+    DX_HIP(c, dxk_hotness_add(c->d_counters + (size_t)layer * c->cfg.E, counts, c->cfg.E, c->compute));
+    return DX_OK;
+}
+
+extern "C" dx_status dx_get_counters(dx_ctx *c, int64_t *out)
+{
+    if (!c || !out) return DX_ERR_INVALID;
+    const size_t n = (size_t)c->cfg.L * c->cfg.E;
+    DX_HIP(c, hipMemcpyAsync(c->h_counters, c->d_counters, n * 8, hipMemcpyDeviceToHost, c->compute));
+    DX_HIP(c, hipStreamSynchronize(c->compute));
+    std::memcpy(out, c->h_counters, n * 8);
+    return DX_OK;
+}
+
+extern "C" dx_status dx_window_end(dx_ctx *c, uint64_t *scores_out)
+{
+    if (!c) return DX_ERR_INVALID;
+    const size_t n = (size_t)c->cfg.L * c->cfg.E;
+    DX_HIP(c, hipMemcpyAsync(c->h_counters, c->d_counters, n * 8, hipMemcpyDeviceToHost, c->compute));
+    DX_HIP(c, dxk_fill_u64(c->d_counters, n, 0ull, c->compute));
+    DX_HIP(c, hipStreamSynchronize(c->compute));
+    const uint64_t a = c->cfg.alpha_q16;
+    for (size_t i = 0; i < n; ++i) {
+        const uint64_t cur = (uint64_t)c->h_counters[i] << 16;
+        c->scores[i] = (a * c->scores[i] + (65536ull - a) * cur) >> 16;
+    }
+    if (scores_out) std::memcpy(scores_out, c->scores.data(), n * 8);
+    return DX_OK;
+}
+
+extern "C" dx_status dx_select_resident(dx_ctx *c, int layer, uint64_t budget_bytes, int32_t *out_ids, int32_t *out_n)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!out_n) DX_FAIL(c, DX_ERR_INVALID, "dx_select_resident: null out_n");
+    *out_n = 0;
+    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_select_resident: layer %d out of range", layer);
+    if (!out_ids) DX_FAIL(c, DX_ERR_INVALID, "dx_select_resident: null out_ids");
+    const int n = dx_budget_capacity(budget_bytes, c->cfg.E, c->b_hi, c->b_lo);
+    if (n < 0)
+        DX_FAIL(c, DX_ERR_BUDGET, "dx_select_resident: budget %llu B is below the all-int4 layer (%llu B)",
+                (unsigned long long)budget_bytes, (unsigned long long)(c->cfg.E * c->b_lo));
+    dx_status s = dx_select_topn(c->scores.data() + (size_t)layer * c->cfg.E, c->cfg.E, n, out_ids);
+    if (s != DX_OK) DX_FAIL(c, s, "dx_select_resident: selection failed");
+    *out_n = n;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_plan_transitions(dx_ctx *c, int layer, const int32_t *target, int n_target, int32_t *promote,
+                                         int32_t *n_promote, int32_t *demote, int32_t *n_demote)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || n_target < 0 || n_target > c->cfg.E || (n_target && !target) || !promote ||
+        !n_promote || !demote || !n_demote)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_plan_transitions: bad argument");
+    const int E = c->cfg.E;
+    std::vector<uint8_t> want(E, 0);
+    for (int i = 0; i < n_target; ++i) {
+        if (target[i] < 0 || target[i] >= E) DX_FAIL(c, DX_ERR_INVALID, "dx_plan_transitions: id %d out of range", target[i]);
+        want[target[i]] = 1;
+    }
+    int np = 0, nd = 0;
+    for (int e = 0; e < E; ++e) {
+        const uint8_t st = c->entries[entry_index(c, layer, e)].state;
+        const bool cur = st == DX_STATE_RESIDENT_HI || st == DX_STATE_PROMOTING;
+        if (want[e] && !cur) promote[np++] = e;
+        if (cur && !want[e]) demote[nd++] = e;
+    }
+    *n_promote = np;
+    *n_demote = nd;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_quantize_expert(dx_ctx *c, const void *w, int rows, int K, int group, void *q, void *s,
+                                        void *stream)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (rows < 0 || K <= 0 || (group != 32 && group != 64 && group != 128) || K % group)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_quantize_expert: rows=%d K=%d group=%d not supported", rows, K, group);
+    if (rows == 0) return DX_OK;
+    if (!w || !q || !s) DX_FAIL(c, DX_ERR_INVALID, "dx_quantize_expert: null pointer");
+    if (((uintptr_t)w & 15) || ((uintptr_t)q & 3) || ((uintptr_t)s & 1))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_quantize_expert: misaligned pointer");
+    hipStream_t st = stream ? static_cast<hipStream_t>(stream) : c->compute;
+    DX_HIP(c, dxk_quantize(static_cast<const dx_bf16 *>(w), rows, K, group, static_cast<uint8_t *>(q),
+                           static_cast<dx_bf16 *>(s), st));
+    return DX_OK;
+}
+
+extern "C" dx_status dx_swap_handle(dx_ctx *c, int layer, int expert, const dx_handle *nv, void *producer_event)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, true) || !nv)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: bad (layer, expert) = (%d, %d) or null handle", layer, expert);
+    const bool int4 = nv->fmt == DX_FMT_INT4G;
+    if (nv->fmt != DX_FMT_BF16 && !int4) DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: unknown format %u", nv->fmt);
+    if (expert == c->cfg.E && int4) DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: the shared expert is bf16 only");
+    if (!nv->w_gate || !nv->w_up || !nv->w_down || (int4 && (!nv->s_gate || !nv->s_up || !nv->s_down)))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: null weight or scale pointer");
+    const uintptr_t all = (uintptr_t)nv->w_gate | (uintptr_t)nv->w_up | (uintptr_t)nv->w_down |
+                          (uintptr_t)nv->s_gate | (uintptr_t)nv->s_up | (uintptr_t)nv->s_down;
+    if (all & 15) DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: pointers must be 16-byte aligned");
+    const int idx = entry_index(c, layer, expert);
+    dx_entry &en = c->entries[idx];
+    if (en.state == DX_STATE_PROMOTING || en.state == DX_STATE_DEMOTING)
+        DX_FAIL(c, DX_ERR_BUSY, "dx_swap_handle: expert (%d,%d) is in transition", layer, expert);
+    if (producer_event) {
+        hipError_t q = hipEventQuery(static_cast<hipEvent_t>(producer_event));
+        if (q == hipErrorNotReady) DX_FAIL(c, DX_ERR_BUSY, "dx_swap_handle: the new version is not complete yet");
+        if (q != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q));
+    }
+    if (en.pool >= 0) DX_FAIL(c, DX_ERR_BUSY, "dx_swap_handle: expert (%d,%d) is pool-managed; use the transition calls", layer, expert);
+    dx_status s = publish(c, idx, *nv);
+    if (s != DX_OK) return s;
+    if (expert < c->cfg.E) {
+        if (en.state == DX_STATE_RESIDENT_HI) c->hi_count[layer]--;
+        if (!int4) c->hi_count[layer]++;
+    }
+    en.state = int4 ? DX_STATE_RESIDENT_LO : DX_STATE_RESIDENT_HI;
+    return DX_OK;
+}
+
+// ------------------------------------------------------------ table inspection
+extern "C" const dx_handle *dx_handle_table(dx_ctx *c, int layer)
+{
+    if (!c || !valid_layer(c, layer)) return nullptr;
+    return c->d_table + (size_t)layer * c->cfg.E;
+}
+
+extern "C" dx_status dx_get_handle(dx_ctx *c, int layer, int expert, dx_handle *out)
+{
+    if (!c || !out) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, true)) DX_FAIL(c, DX_ERR_INVALID, "dx_get_handle: out of range");
+    *out = c->entries[entry_index(c, layer, expert)].h;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_get_formats(dx_ctx *c, uint8_t *out)
+{
+    if (!c || !out) return DX_ERR_INVALID;
+    const size_t n = (size_t)c->cfg.L * c->cfg.E;
+    for (size_t i = 0; i < n; ++i) out[i] = c->entries[i].state == DX_STATE_EMPTY ? 255 : (uint8_t)c->entries[i].h.fmt;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_get_states(dx_ctx *c, uint8_t *out)
+{
+    if (!c || !out) return DX_ERR_INVALID;
+    const size_t n = (size_t)c->cfg.L * c->cfg.E;
+    for (size_t i = 0; i < n; ++i) out[i] = c->entries[i].state;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_get_stats(dx_ctx *c, dx_stats *out)
+{
+    if (!c || !out) return DX_ERR_INVALID;
+    *out = c->stats;
+    return DX_OK;
+}
+
+// ------------------------------------------------------ pools and transitions
+extern "C" dx_status dx_pools_create(dx_ctx *c, int hi_blocks, int lo_blocks)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (hi_blocks < 0 || lo_blocks < 0) DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: negative block count");
+    if (c->pool_hi.base || c->pool_lo.base || c->staging) DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: pools already exist");
+    const size_t hi_b = round256(std::max(c->b_hi, c->b_shared)), lo_b = round256(c->b_lo);
+    auto make = [&](dx_block_pool &p, size_t bytes, int n) -> hipError_t {
+        p.block_bytes = bytes;
+        p.n_blocks = n;
+        p.reuse_after.assign(n, nullptr);
+        p.free_list.resize(n);
+        for (int i = 0; i < n; ++i) p.free_list[i] = n - 1 - i; // block 0 is handed out first
+        if (n == 0) return hipSuccess;
+        return hipMalloc(reinterpret_cast<void **>(&p.base), bytes * (size_t)n);
+    };
+    hipError_t e;
+    if ((e = make(c->pool_hi, hi_b, hi_blocks)) != hipSuccess ||
+        (e = make(c->pool_lo, lo_b, lo_blocks)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void **>(&c->staging), hi_b)) != hipSuccess) {
+        for (dx_block_pool *p : {&c->pool_hi, &c->pool_lo}) {
+            if (p->base) (void)hipFree(p->base);
+            *p = dx_block_pool{};
+        }
+        if (c->staging) (void)hipFree(c->staging);
+        c->staging = nullptr;
+        DX_FAIL(c, e == hipErrorOutOfMemory ? DX_ERR_NOMEM : DX_ERR_HIP, "dx_pools_create: %s", hipGetErrorString(e));
+    }
+    return DX_OK;
+}
+
+extern "C" dx_status dx_expert_install(dx_ctx *c, int layer, int expert, int fmt, const void *gate, const void *up,
+                                       const void *down, int src_on_device)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, true) || !gate || !up || !down ||
+        (fmt != DX_FMT_BF16 && fmt != DX_FMT_INT4G))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_expert_install: bad argument");
+    const bool shared = expert == c->cfg.E;
+    if (shared && fmt != DX_FMT_BF16) DX_FAIL(c, DX_ERR_INVALID, "dx_expert_install: the shared expert is bf16 only");
+    if (!c->staging) DX_FAIL(c, DX_ERR_INVALID, "dx_expert_install: call dx_pools_create first");
+    const int idx = entry_index(c, layer, expert);
+    dx_entry &en = c->entries[idx];
+    if (en.state != DX_STATE_EMPTY) DX_FAIL(c, DX_ERR_BUSY, "dx_expert_install: expert (%d,%d) already installed", layer, expert);
+    const dx_config &g = c->cfg;
+    const int f = shared ? g.shared_f : g.f;
+    const uint64_t bytes = shared ? c->b_shared : (fmt == DX_FMT_BF16 ? c->b_hi : c->b_lo);
+    const uint64_t cap = g.budget_bytes ? g.budget_bytes + g.transient_bytes : ~0ull;
+    if (c->reserved + bytes > cap) {
+        c->stats.deferred++;
+        DX_FAIL(c, DX_ERR_BUDGET, "dx_expert_install: %llu B reserved + %llu B exceeds the budget", (unsigned long long)c->reserved,
+                (unsigned long long)bytes);
+    }
+    if (!shared && fmt == DX_FMT_BF16 && g.budget_bytes && c->hi_count[layer] >= c->n_hi_cap) {
+        c->stats.deferred++;
+        DX_FAIL(c, DX_ERR_BUDGET, "dx_expert_install: layer %d already holds its %d high-precision experts", layer, c->n_hi_cap);
+    }
+    dx_block_pool &pool = fmt == DX_FMT_BF16 ? c->pool_hi : c->pool_lo;
+    int block;
+    dx_status s = pool_take(c, pool, c->compute, &block);
+    if (s != DX_OK) return s;
+    const size_t mat = (size_t)f * g.d * 2; // bytes of one bf16 matrix
+    const hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    dx_handle h = handle_in_block(c, pool.block_ptr(block), fmt, f);
+    hipError_t e = hipSuccess;
+    if (fmt == DX_FMT_BF16) {
+        if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_gate), gate, mat, kind, c->compute);
+        if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_up), up, mat, kind, c->compute);
+        if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_down), down, mat, kind, c->compute);
+    } else {
+        const void *src[3] = {gate, up, down};
+        void *qd[3] = {const_cast<void *>(h.w_gate), const_cast<void *>(h.w_up), const_cast<void *>(h.w_down)};
+        void *sd[3] = {const_cast<void *>(h.s_gate), const_cast<void *>(h.s_up), const_cast<void *>(h.s_down)};
+        const int rows[3] = {f, f, g.d}, Ks[3] = {g.d, g.d, f};
+        for (int i = 0; i < 3 && e == hipSuccess; ++i) {
+            const void *dev_src = src[i];
+            if (!src_on_device) {
+                dev_src = c->staging + (size_t)i * mat;
+                e = hipMemcpyAsync(c->staging + (size_t)i * mat, src[i], mat, hipMemcpyHostToDevice, c->compute);
+            }
+            if (e == hipSuccess)
+                e = dxk_quantize(static_cast<const dx_bf16 *>(dev_src), rows[i], Ks[i], g.group,
+                                 static_cast<uint8_t *>(qd[i]), static_cast<dx_bf16 *>(sd[i]), c->compute);
+        }
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
+    if (e != hipSuccess) {
+        pool_give(pool, block, nullptr);
+        DX_FAIL(c, DX_ERR_HIP, "dx_expert_install: %s", hipGetErrorString(e));
+    }
+    s = publish(c, idx, h);
+    if (s != DX_OK) {
+        pool_give(pool, block, nullptr);
+        return s;
+    }
+    track_reserve(c, bytes);
+    en.pool = fmt == DX_FMT_BF16 ? 0 : 1;
+    en.block = block;
+    en.state = fmt == DX_FMT_BF16 ? DX_STATE_RESIDENT_HI : DX_STATE_RESIDENT_LO;
+    if (!shared && fmt == DX_FMT_BF16) c->hi_count[layer]++;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_promote_async(dx_ctx *c, int layer, int expert, const void *pg, const void *pu, const void *pd)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, false) || !pg || !pu || !pd)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_promote_async: bad argument");
+    const int idx = entry_index(c, layer, expert);
+    dx_entry &en = c->entries[idx];
+    if (en.state != DX_STATE_RESIDENT_LO || en.pool != 1)
+        DX_FAIL(c, DX_ERR_BUSY, "dx_promote_async: expert (%d,%d) is not a pool-resident int4 expert", layer, expert);
+    const dx_config &g = c->cfg;
+    // admission: per-layer capacity and the byte budget (try_reserve)
+    const uint64_t cap = g.budget_bytes ? g.budget_bytes + g.transient_bytes : ~0ull;
+    if ((g.budget_bytes && c->hi_count[layer] >= c->n_hi_cap) || c->reserved + c->b_hi > cap) {
+        c->stats.deferred++;
+        DX_FAIL(c, DX_ERR_BUDGET, "dx_promote_async: no high-precision capacity for (%d,%d): %d/%d resident, %llu B reserved",
+                layer, expert, c->hi_count[layer], c->n_hi_cap, (unsigned long long)c->reserved);
+    }
+    hipEvent_t done;
+    dx_status s = get_event(c, &done);
+    if (s != DX_OK) return s;
+    int block;
+    s = pool_take(c, c->pool_hi, c->mig, &block);
+    if (s != DX_OK) {
+        c->event_pool.push_back(done);
+        if (s == DX_ERR_NOMEM) c->stats.deferred++;
+        return s;
+    }
+    const size_t mat = (size_t)g.f * g.d * 2;
+    dx_handle h = handle_in_block(c, c->pool_hi.block_ptr(block), DX_FMT_BF16, g.f);
+    hipError_t e = hipMemcpyAsync(const_cast<void *>(h.w_gate), pg, mat, hipMemcpyHostToDevice, c->mig);
+    if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_up), pu, mat, hipMemcpyHostToDevice, c->mig);
+    if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_down), pd, mat, hipMemcpyHostToDevice, c->mig);
+    if (e == hipSuccess) e = hipEventRecord(done, c->mig);
+    if (e != hipSuccess) {
+        (void)hipStreamSynchronize(c->mig);
+        pool_give(c->pool_hi, block, nullptr);
+        c->event_pool.push_back(done);
+        DX_FAIL(c, DX_ERR_HIP, "dx_promote_async: %s", hipGetErrorString(e));
+    }
+    track_reserve(c, c->b_hi);
+    en.state = DX_STATE_PROMOTING;
+    en.next_block = block;
+    c->hi_count[layer]++;
+    c->inflight.push_back({layer, expert, true, done});
+    c->stats.promotions_issued++;
+    c->stats.h2d_bytes += 3 * mat;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_demote_async(dx_ctx *c, int layer, int expert)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, false)) DX_FAIL(c, DX_ERR_INVALID, "dx_demote_async: bad argument");
+    const int idx = entry_index(c, layer, expert);
+    dx_entry &en = c->entries[idx];
+    if (en.state != DX_STATE_RESIDENT_HI || en.pool != 0)
+        DX_FAIL(c, DX_ERR_BUSY, "dx_demote_async: expert (%d,%d) is not a pool-resident bf16 expert", layer, expert);
+    const dx_config &g = c->cfg;
+    const uint64_t cap = g.budget_bytes ? g.budget_bytes + g.transient_bytes : ~0ull;
+    if (c->reserved + c->b_lo > cap) {
+        c->stats.deferred++;
+        DX_FAIL(c, DX_ERR_BUDGET, "dx_demote_async: no transient room for the int4 version (%llu B reserved)", (unsigned long long)c->reserved);
+    }
+    hipEvent_t done;
+    dx_status s = get_event(c, &done);
+    if (s != DX_OK) return s;
+    int block;
+    s = pool_take(c, c->pool_lo, c->mig, &block);
+    if (s != DX_OK) {
+        c->event_pool.push_back(done);
+        if (s == DX_ERR_NOMEM) c->stats.deferred++;
+        return s;
+    }
+    dx_handle lo = handle_in_block(c, c->pool_lo.block_ptr(block), DX_FMT_INT4G, g.f);
+    const dx_handle &hi = en.h;
+    hipError_t e = dxk_quantize(static_cast<const dx_bf16 *>(hi.w_gate), g.f, g.d, g.group,
+                                static_cast<uint8_t *>(const_cast<void *>(lo.w_gate)),
+                                static_cast<dx_bf16 *>(const_cast<void *>(lo.s_gate)), c->mig);
+    if (e == hipSuccess)
+        e = dxk_quantize(static_cast<const dx_bf16 *>(hi.w_up), g.f, g.d, g.group,
+                         static_cast<uint8_t *>(const_cast<void *>(lo.w_up)),
+                         static_cast<dx_bf16 *>(const_cast<void *>(lo.s_up)), c->mig);
+    if (e == hipSuccess)
+        e = dxk_quantize(static_cast<const dx_bf16 *>(hi.w_down), g.d, g.f, g.group,
+                         static_cast<uint8_t *>(const_cast<void *>(lo.w_down)),
+                         static_cast<dx_bf16 *>(const_cast<void *>(lo.s_down)), c->mig);
+    if (e == hipSuccess) e = hipEventRecord(done, c->mig);
+    if (e != hipSuccess) {
+        (void)hipStreamSynchronize(c->mig);
+        pool_give(c->pool_lo, block, nullptr);
+        c->event_pool.push_back(done);
+        DX_FAIL(c, DX_ERR_HIP, "dx_demote_async: %s", hipGetErrorString(e));
+    }
+    track_reserve(c, c->b_lo);
+    en.state = DX_STATE_DEMOTING;
+    en.next_block = block;
+    c->inflight.push_back({layer, expert, false, done});
+    c->stats.demotions_issued++;
+    c->stats.quantize_read_bytes += c->b_hi;
+    c->stats.quantize_write_bytes += c->b_lo;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_migrate_poll(dx_ctx *c, int wait, int *n_published)
+{
+    if (!c) return DX_ERR_INVALID;
+    int n = 0;
+    if (n_published) *n_published = 0;
+    while (!c->inflight.empty()) {
+        dx_transition t = c->inflight.front();
+        hipError_t q = wait ? hipEventSynchronize(t.done) : hipEventQuery(t.done);
+        if (q == hipErrorNotReady) break; // publish strictly in issue order
+        if (q != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_migrate_poll: %s", hipGetErrorString(q));
+        const int idx = entry_index(c, t.layer, t.expert);
+        dx_entry &en = c->entries[idx];
+        dx_block_pool &new_pool = t.promote ? c->pool_hi : c->pool_lo;
+        dx_block_pool &old_pool = t.promote ? c->pool_lo : c->pool_hi;
+        const int old_block = en.block;
+        dx_handle h = handle_in_block(c, new_pool.block_ptr(en.next_block), t.promote ? DX_FMT_BF16 : DX_FMT_INT4G, c->cfg.f);
+        // an event on the compute stream right after the swap: once it has fired, no
+        // forward pass can still read the old version, so its block may be rewritten
+        hipEvent_t after;
+        dx_status s = get_event(c, &after);
+        if (s != DX_OK) return s;
+        s = publish(c, idx, h);
+        if (s != DX_OK) {
+            c->event_pool.push_back(after);
+            return s;
+        }
+        hipError_t e = hipEventRecord(after, c->compute);
+        if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_migrate_poll: hipEventRecord: %s", hipGetErrorString(e));
+        pool_give(old_pool, old_block, after);
+        track_release(c, t.promote ? c->b_lo : c->b_hi);
+        en.block = en.next_block;
+        en.next_block = -1;
+        en.pool = t.promote ? 0 : 1;
+        en.state = t.promote ? DX_STATE_RESIDENT_HI : DX_STATE_RESIDENT_LO;
+        if (t.promote) c->stats.promotions_published++;
+        else {
+            c->stats.demotions_published++;
+            c->hi_count[t.layer]--;
+        }
+        c->event_pool.push_back(t.done);
+        c->inflight.pop_front();
+        ++n;
+    }
+    if (n_published) *n_published = n;
+    return DX_OK;
+}

@@ -1,0 +1,119 @@
+// Internal declarations shared by the translation units of libdynaexq.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <deque>
+#include <string>
+#include <vector>
+
+#include "dynaexq.h"
+
+typedef uint16_t dx_bf16; // bit pattern
+
+struct dx_block_pool {
+    char *base = nullptr;
+    size_t block_bytes = 0;
+    int n_blocks = 0;
+    std::vector<int> free_list;           // LIFO of free block indices
+    std::vector<hipEvent_t> reuse_after;  // per block: compute-stream event to pass before reuse (or null)
+    void *block_ptr(int i) const { return base + (size_t)i * block_bytes; }
+};
+
+struct dx_entry {
+    uint8_t state = DX_STATE_EMPTY;
+    int8_t pool = -1;        // -1: caller-owned memory, 0: pool_hi, 1: pool_lo
+    int32_t block = -1;      // block index of the published version
+    int32_t next_block = -1; // block being filled by an in-flight transition
+    dx_handle h{};           // host mirror of the published handle
+};
+
+struct dx_transition {
+    int layer, expert;
+    bool promote;
+    hipEvent_t done;
+};
+
+struct dx_ctx {
+    dx_config cfg{};
+    int device = 0;
+    hipStream_t compute = nullptr;
+    hipStream_t mig = nullptr;
+    std::string err;
+
+    // handle tables: routed [L*E] then shared [L]
+    dx_handle *d_table = nullptr;
+    std::vector<dx_entry> entries; // L*E routed + L shared
+
+    // hotness
+    unsigned long long *d_counters = nullptr; // [L*E]
+    long long *h_counters = nullptr;          // pinned [L*E]
+    std::vector<uint64_t> scores;             // host S, Q16
+
+    // routing scratch (chunks of 64 tokens)
+    int n_chunks_max = 0;
+    unsigned long long *d_mask = nullptr; // [n_chunks_max, E]
+    int32_t *d_chunk_base = nullptr;      // [n_chunks_max, E]
+
+    // forward scratch
+    dx_bf16 *d_h = nullptr; // [max_tokens*(k+1), fmax]
+    float *d_o = nullptr;   // [max_tokens*(k+1), d]
+    int fmax = 0;
+
+    // pools / budget tracker / transitions
+    dx_block_pool pool_hi, pool_lo;
+    char *staging = nullptr;
+    uint64_t b_hi = 0, b_lo = 0, b_shared = 0;
+    uint64_t reserved = 0;
+    std::vector<int> hi_count; // per layer: Resident-Hi + Promoting
+    int n_hi_cap = 0;          // per-layer capacity from the budget rule
+    std::deque<dx_transition> inflight;
+    std::vector<hipEvent_t> event_pool;
+    dx_stats stats{};
+};
+
+#define DX_FAIL(ctx, code, ...)                                   \
+    do {                                                          \
+        char _buf[512];                                           \
+        snprintf(_buf, sizeof _buf, __VA_ARGS__);                 \
+        if (ctx) (ctx)->err = _buf;                               \
+        return (code);                                            \
+    } while (0)
+
+#define DX_HIP(ctx, call)                                                                  \
+    do {                                                                                   \
+        hipError_t _e = (call);                                                            \
+        if (_e != hipSuccess)                                                              \
+            DX_FAIL(ctx, DX_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(_e), \
+                    __FILE__, __LINE__);                                                   \
+    } while (0)
+
+// ---- kernel launchers (each validates nothing; callers validate) ----------
+// dx_route.hip
+hipError_t dxk_route(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
+                     int32_t *offsets, int32_t *perm, unsigned long long *mask, int32_t *chunk_base,
+                     hipStream_t s);
+hipError_t dxk_hotness_add(unsigned long long *counters, const int32_t *counts, int E, hipStream_t s);
+hipError_t dxk_fill_u64(unsigned long long *p, size_t n, unsigned long long v, hipStream_t s);
+hipError_t dxk_store_handle(dx_handle *slot, const dx_handle &h, hipStream_t s);
+
+// dx_quantize.hip
+hipError_t dxk_quantize(const dx_bf16 *w, int rows, int K, int group, uint8_t *q, dx_bf16 *sc, hipStream_t s);
+
+// dx_moe_decode.hip / dx_moe_prefill.hip
+struct dx_fwd_args {
+    const dx_handle *table;  // E routed entries of the layer
+    const dx_handle *shared; // one entry or null
+    const dx_bf16 *x;
+    dx_bf16 *y;
+    const int32_t *ids;
+    const float *w;
+    const int32_t *offsets;
+    const int32_t *perm;
+    dx_bf16 *h;  // scratch [T*k (+T), fmax]
+    float *o;    // scratch [T*k (+T), d]
+    int T, E, k, d, f, group, shared_f, fmax;
+};
+hipError_t dxk_moe_forward(const dx_fwd_args &a, hipStream_t s);

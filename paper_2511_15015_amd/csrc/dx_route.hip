@@ -1,0 +1,242 @@
+// Router top-k, routing weights and the stable permutation of (token, slot)
+// pairs into per-expert segments, plus the small table/counter kernels.
+//
+// Paper: Sec. 3.1 (the worker obtains top-k expert ids from the router and
+// indexes the handle table with them); Sec. 3.5 (per-expert selection counts).
+//
+// Determinism: the order inside an expert segment is by increasing pair
+// index p = t*k + j.  Because the k ids of one token are distinct, the rank of
+// pair (t, j) inside the segment of expert e equals the number of tokens
+// t' < t that selected e.  Tokens are handled in chunks of 64: each chunk
+// builds, per expert, a 64-bit mask of the tokens that selected it; ranks are
+// population counts of mask prefixes.  No atomics decide any position.
+#include "dx_internal.h"
+
+#include <cfloat>
+
+namespace {
+
+constexpr int kChunk = 64;      // tokens per chunk = bits per mask word
+constexpr int kRouteThreads = 1024;
+constexpr int kWaves = kRouteThreads / 64;
+
+__device__ __forceinline__ bool better(float av, int ai, float bv, int bi)
+{
+    return av > bv || (av == bv && ai < bi);
+}
+
+// exclusive scan of one int per thread across a 1024-thread block
+__device__ int block_exclusive_scan(int v, int *lds_wave_tot /*[kWaves]*/, int *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
+    }
+    if (lane == 63) lds_wave_tot[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        int t = lds_wave_tot[w];
+        if (w < wave) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+// One chunk of 64 tokens per block.  NV = logits held per lane (E <= 64*NV).
+template <int NV>
+__global__ __launch_bounds__(kRouteThreads) void k_route_topk(
+    const float *__restrict__ logits, int T, int E, int k, int32_t *__restrict__ ids,
+    float *__restrict__ w, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
+    int32_t *__restrict__ perm, unsigned long long *__restrict__ mask_out, int fused)
+{
+    extern __shared__ unsigned long long lds_mask[]; // [E], then int ids [64*k], then wave totals
+    int *lds_ids = reinterpret_cast<int *>(lds_mask + E);
+    int *lds_tot = lds_ids + kChunk * k;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x;
+    for (int e = threadIdx.x; e < E; e += kRouteThreads) lds_mask[e] = 0ull;
+    __syncthreads();
+
+    for (int tt = wave; tt < kChunk; tt += kWaves) {
+        const int t = chunk * kChunk + tt;
+        if (t >= T) break; // wave-uniform
+        const float *row = logits + (size_t)t * E;
+        float v[NV];
+#pragma unroll
+        for (int s = 0; s < NV; ++s) {
+            int e = lane + 64 * s;
+            v[s] = e < E ? row[e] : -INFINITY;
+        }
+        int my_id = 0;
+        float my_logit = 0.f;
+        for (int j = 0; j < k; ++j) {
+            float bv = v[0];
+            int bi = lane;
+#pragma unroll
+            for (int s = 1; s < NV; ++s) {
+                if (v[s] > bv) { bv = v[s]; bi = lane + 64 * s; } // strict: lower index wins
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                float ov = __shfl_xor(bv, off, 64);
+                int oi = __shfl_xor(bi, off, 64);
+                if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            }
+#pragma unroll
+            for (int s = 0; s < NV; ++s)
+                if (bi == lane + 64 * s) v[s] = -INFINITY;
+            if (lane == j) { my_id = bi; my_logit = bv; }
+        }
+        const float top = __shfl(my_logit, 0, 64);
+        float ex = lane < k ? expf(my_logit - top) : 0.f;
+        float sum = ex;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if (lane < k) {
+            ids[(size_t)t * k + lane] = my_id;
+            w[(size_t)t * k + lane] = ex / sum;
+            lds_ids[tt * k + lane] = my_id;
+            atomicOr(&lds_mask[my_id], 1ull << tt);
+        }
+    }
+    __syncthreads();
+
+    if (!fused) {
+        for (int e = threadIdx.x; e < E; e += kRouteThreads) mask_out[(size_t)chunk * E + e] = lds_mask[e];
+        return;
+    }
+    // single chunk: finish counts, offsets and the permutation here (E <= 1024)
+    const int e = threadIdx.x;
+    const int c = e < E ? __popcll(lds_mask[e]) : 0;
+    int total;
+    const int off = block_exclusive_scan(c, lds_tot, &total);
+    if (e < E) {
+        counts[e] = c;
+        offsets[e] = off;
+        lds_ids[kChunk * k + kWaves + e] = off; // offsets kept in LDS after the wave totals
+    }
+    if (e == 0) offsets[E] = total;
+    __syncthreads();
+    const int *lds_off = lds_ids + kChunk * k + kWaves;
+    const int P = T * k;
+    for (int p = threadIdx.x; p < P; p += kRouteThreads) {
+        const int tt = p / k;
+        const int ex_id = lds_ids[p];
+        const unsigned long long below = lds_mask[ex_id] & ((1ull << tt) - 1ull);
+        perm[lds_off[ex_id] + __popcll(below)] = p;
+    }
+}
+
+// counts/offsets and per-chunk bases from the chunk masks (one block)
+__global__ __launch_bounds__(kRouteThreads) void k_route_scan(
+    const unsigned long long *__restrict__ mask, int n_chunks, int E, int32_t *__restrict__ chunk_base,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets)
+{
+    __shared__ int lds_tot[kWaves];
+    const int e = threadIdx.x;
+    int run = 0;
+    if (e < E) {
+        for (int c = 0; c < n_chunks; ++c) {
+            chunk_base[(size_t)c * E + e] = run;
+            run += __popcll(mask[(size_t)c * E + e]);
+        }
+    }
+    int total;
+    const int off = block_exclusive_scan(run, lds_tot, &total);
+    if (e < E) {
+        counts[e] = run;
+        offsets[e] = off;
+    }
+    if (e == 0) offsets[E] = total;
+}
+
+__global__ __launch_bounds__(256) void k_route_place(
+    const int32_t *__restrict__ ids, int P, int E, int k, const unsigned long long *__restrict__ mask,
+    const int32_t *__restrict__ chunk_base, const int32_t *__restrict__ offsets, int32_t *__restrict__ perm)
+{
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= P) return;
+    const int t = p / k;
+    const int c = t / kChunk, bit = t % kChunk;
+    const int e = ids[p];
+    const unsigned long long below = mask[(size_t)c * E + e] & ((1ull << bit) - 1ull);
+    perm[offsets[e] + chunk_base[(size_t)c * E + e] + __popcll(below)] = p;
+}
+
+__global__ void k_hotness_add(unsigned long long *__restrict__ counters, const int32_t *__restrict__ counts, int E)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < E) counters[e] += (unsigned long long)counts[e];
+}
+
+__global__ void k_fill_u64(unsigned long long *p, size_t n, unsigned long long v)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void k_store_handle(dx_handle *slot, dx_handle h)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *slot = h;
+}
+
+template <int NV>
+hipError_t launch_topk(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
+                       int32_t *offsets, int32_t *perm, unsigned long long *mask, int n_chunks, hipStream_t s)
+{
+    const int fused = n_chunks == 1;
+    size_t lds = (size_t)E * 8 + (size_t)(kChunk * k + kWaves + E) * 4;
+    hipLaunchKernelGGL(k_route_topk<NV>, dim3(n_chunks), dim3(kRouteThreads), lds, s, logits, T, E, k, ids, w,
+                       counts, offsets, perm, mask, fused);
+    return hipGetLastError();
+}
+
+} // namespace
+
+hipError_t dxk_route(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
+                     int32_t *offsets, int32_t *perm, unsigned long long *mask, int32_t *chunk_base,
+                     hipStream_t s)
+{
+    // T == 0 still runs one (empty) chunk so that counts and offsets are written.
+    const int n_chunks = T > 0 ? (T + kChunk - 1) / kChunk : 1;
+    hipError_t e;
+    if (E <= 64) e = launch_topk<1>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
+    else if (E <= 128) e = launch_topk<2>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
+    else if (E <= 256) e = launch_topk<4>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
+    else if (E <= 512) e = launch_topk<8>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
+    else e = launch_topk<16>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
+    if (e != hipSuccess || n_chunks == 1) return e;
+    hipLaunchKernelGGL(k_route_scan, dim3(1), dim3(kRouteThreads), 0, s, mask, n_chunks, E, chunk_base, counts,
+                       offsets);
+    const int P = T * k;
+    hipLaunchKernelGGL(k_route_place, dim3((P + 255) / 256), dim3(256), 0, s, ids, P, E, k, mask, chunk_base,
+                       offsets, perm);
+    return hipGetLastError();
+}
+
+hipError_t dxk_hotness_add(unsigned long long *counters, const int32_t *counts, int E, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_hotness_add, dim3((E + 255) / 256), dim3(256), 0, s, counters, counts, E);
+    return hipGetLastError();
+}
+
+hipError_t dxk_fill_u64(unsigned long long *p, size_t n, unsigned long long v, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t dxk_store_handle(dx_handle *slot, const dx_handle &h, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_store_handle, dim3(1), dim3(64), 0, s, slot, h);
+    return hipGetLastError();
+}

@@ -1,0 +1,352 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle
+on the same seeded inputs.  Integer stages bit-exact; layer outputs within
+rel-L2 1e-2 (the bar the build's target states); routing weights within 1e-5."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_15015_amd import workloads as W
+from paper_2511_15015_amd.workloads import WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+REL_L2_TOL = 1e-2
+W_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2511_15015_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def LY():
+    from paper_2511_15015_amd import layer
+    return layer
+
+
+def rel_l2(y_gpu_bits, y_ref):
+    y = bf16_bits_to_f32(y_gpu_bits).astype(np.float64)
+    return float(np.linalg.norm(y - y_ref) / max(np.linalg.norm(y_ref), 1e-300))
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ quantizer
+@pytest.mark.parametrize("rows,K,group", [(128, 256, 64), (768, 2048, 128), (2048, 768, 128), (37, 96, 32),
+                                          (1, 128, 128), (5, 64, 64)])
+def test_quantize_bit_exact(B, LY, dxo, rows, K, group):
+    print(f"quantize rows={rows} K={K} group={group}", flush=True)
+    g = np.random.default_rng(rows * 7 + K)
+    w = 0.02 * g.standard_normal((rows, K)).astype(np.float32)
+    w[0, :group] = 0.0                       # an all-zero group
+    if rows > 2:
+        w[1] *= 1e3
+        w[2] *= 1e-4
+    # exact .5 ties: scale 1 (absmax 7), values k + 0.5
+    w[-1, :group] = 0.0
+    w[-1, 0] = 7.0
+    w[-1, 1:9] = [0.5, 1.5, 2.5, 3.5, -0.5, -1.5, -2.5, -6.5]
+    bits = f32_to_bf16_bits(w)
+    q_ref, s_ref = dxo.quantize(bits, group)
+    ctx = B.Context(L=1, E=4, d=128, f=128, top_k=2, group=group, max_tokens=4)
+    wd = LY.bits_to_device(bits)
+    q = torch.empty((rows, K // 2), dtype=torch.uint8, device="cuda")
+    s = torch.empty((rows, K // group), dtype=torch.bfloat16, device="cuda")
+    ctx.dx_quantize_expert(wd, rows, K, group, q, s)
+    sync()
+    assert np.array_equal(LY.device_to_bits(s), s_ref)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    ctx.close()
+
+
+def test_quantize_rejects_bad_arguments(B):
+    ctx = B.Context(L=1, E=4, d=128, f=128, top_k=2, group=64, max_tokens=4)
+    buf = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_quantize_expert(buf, 2, 96, 64, buf, buf)          # K % group != 0
+    assert ei.value.status == B.DX_ERR_INVALID
+    with pytest.raises(B.DxError):
+        ctx.dx_quantize_expert(buf, 2, 128, 48, buf, buf)         # unsupported group
+    with pytest.raises(B.DxError):
+        ctx.dx_quantize_expert(None, 2, 128, 64, buf, buf)        # null pointer
+    ctx.dx_quantize_expert(buf, 0, 128, 64, buf, buf)             # empty is fine
+    ctx.close()
+
+
+# -------------------------------------------------------------------- routing
+def _check_route(B, LY, dxo, logits, k, max_tokens=None):
+    T, E = logits.shape
+    ctx = B.Context(L=1, E=E, d=64, f=64, top_k=k, group=32, max_tokens=max(max_tokens or T, 1))
+    rb = LY.RoutingBuffers(max(T, 1), E, k)
+    dl = torch.from_numpy(logits).cuda() if T else torch.empty((1, E), dtype=torch.float32, device="cuda")
+    rb.route(ctx, 0, dl, T)
+    sync()
+    ids_r, w_r, counts_r, offsets_r, perm_r = dxo.route(logits, k)
+    assert np.array_equal(rb.counts.cpu().numpy(), counts_r)
+    assert np.array_equal(rb.offsets.cpu().numpy(), offsets_r)
+    if T:
+        assert np.array_equal(rb.ids.cpu().numpy()[:T], ids_r)
+        assert np.array_equal(rb.perm.cpu().numpy()[:T * k], perm_r)
+        wg = rb.w.cpu().numpy()[:T].astype(np.float64)
+        assert np.max(np.abs(wg - w_r) / np.maximum(w_r, 1e-30)) < W_TOL or np.max(np.abs(wg - w_r)) < 1e-7
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4"])
+def test_route_workloads_bit_exact(B, LY, dxo, name):
+    wl = WORKLOADS[name]
+    print(f"route {name} T={wl.T} E={wl.E} k={wl.k}", flush=True)
+    _, logits = W.layer_inputs(wl, seed=0)
+    _check_route(B, LY, dxo, logits, wl.k)
+
+
+@pytest.mark.parametrize("T,E,k", [(0, 8, 2), (1, 8, 2), (63, 16, 4), (64, 16, 4), (65, 16, 4), (130, 200, 6),
+                                   (1000, 1024, 3), (5, 8, 8), (3, 1, 1), (257, 64, 64)])
+def test_route_edge_shapes_and_ties(B, LY, dxo, T, E, k):
+    print(f"route T={T} E={E} k={k}", flush=True)
+    g = np.random.default_rng(T * 31 + E)
+    # logits on a coarse grid: many exact ties, both signs of zero
+    logits = np.round(g.standard_normal((T, E)) * 2).astype(np.float32) / 2
+    logits[logits == 0] *= np.where(g.random(np.count_nonzero(logits == 0)) < 0.5, -1.0, 1.0).astype(np.float32)
+    _check_route(B, LY, dxo, logits, k)
+
+
+def test_route_rejects_bad_arguments(B, LY):
+    ctx = B.Context(L=2, E=8, d=64, f=64, top_k=2, group=32, max_tokens=16)
+    rb = LY.RoutingBuffers(16, 8, 2)
+    lg = torch.zeros((16, 8), dtype=torch.float32, device="cuda")
+    for layer, T in [(2, 4), (-1, 4), (0, 17), (0, -1)]:
+        with pytest.raises(B.DxError) as ei:
+            ctx.dx_route(layer, lg, T, rb.ids, rb.w, rb.counts, rb.offsets, rb.perm)
+        assert ei.value.status == B.DX_ERR_INVALID
+    with pytest.raises(B.DxError):
+        ctx.dx_route(0, None, 4, rb.ids, rb.w, rb.counts, rb.offsets, rb.perm)
+    for bad in [dict(E=0), dict(top_k=9), dict(group=48), dict(d=100), dict(max_tokens=0), dict(alpha_q16=65536)]:
+        kw = dict(L=1, E=8, d=64, f=64, top_k=2, group=32, max_tokens=4)
+        kw.update(bad)
+        with pytest.raises(B.DxError):
+            B.Context(**kw)
+    ctx.close()
+
+
+# ------------------------------------------------------------------ the layer
+class Layer:
+    """One layer set up on both sides from the same master bits."""
+
+    def __init__(self, B, LY, dxo, wl, resident, seed=0, layer=0, masters=None, T=None, shared=None):
+        self.wl, self.B = wl, B
+        T = wl.T if T is None else T
+        self.T = T
+        self.masters = masters if masters is not None else W.layer_masters(wl, seed, layer)
+        wg, wu, wd = self.masters
+        self.ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=max(T, 1),
+                             shared_f=wl.shared_f if shared is not None else 0)
+        self.dev = [LY.bits_to_device(m) for m in self.masters]
+        self.lw = LY.LayerWeights(self.ctx, 0, *self.dev, resident, wl.group)
+        self.rb = LY.RoutingBuffers(max(T, 1), wl.E, wl.k)
+        self.resident = set(int(e) for e in resident)
+        self.versions = [dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if e in self.resident
+                         else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group)
+                         for e in range(wl.E)]
+        self.shared = None
+        if shared is not None:
+            self.shared_dev = [LY.bits_to_device(m) for m in shared]
+            self.ctx.dx_swap_handle(0, wl.E, B.make_handle(B.DX_FMT_BF16, *self.shared_dev))
+            self.shared = dxo.ExpertVersion.bf16(*shared)
+        self.LY, self.dxo = LY, dxo
+
+    def run(self, x_bits, logits, tokens=None):
+        T = x_bits.shape[0]
+        xd = self.LY.bits_to_device(x_bits)
+        ld = torch.from_numpy(logits).cuda()
+        y = torch.empty((T, self.wl.d), dtype=torch.bfloat16, device="cuda")
+        self.rb.route(self.ctx, 0, ld, T)
+        self.rb.forward(self.ctx, 0, xd, y, None, T)
+        sync()
+        ids, w, counts, offsets, perm = self.dxo.route(logits, self.wl.k)
+        assert np.array_equal(self.rb.ids.cpu().numpy()[:T], ids)
+        y_ref = self.dxo.moe_forward(self.versions, self.wl.d, self.wl.f, self.wl.group, x_bits, ids, w,
+                                     shared=self.shared, shared_f=self.wl.shared_f if self.shared else 0,
+                                     tokens=tokens)
+        y_gpu = self.LY.device_to_bits(y)
+        if tokens is not None:
+            y_gpu = y_gpu[np.asarray(tokens)]
+        return y_gpu, y_ref
+
+
+def test_forward_c1_mixed_all_hi_all_lo(B, LY, dxo):
+    wl = WORKLOADS["C1"]
+    x, logits = W.layer_inputs(wl, seed=0)
+    masters = W.layer_masters(wl, 0, 0)
+    for resident in ([1, 6], list(range(wl.E)), []):
+        print(f"forward C1 resident={resident}", flush=True)
+        ly = Layer(B, LY, dxo, wl, resident, masters=masters)
+        y_gpu, y_ref = ly.run(x, logits)
+        err = rel_l2(y_gpu, y_ref)
+        print("  rel-L2", err, flush=True)
+        assert err <= REL_L2_TOL
+        ly.ctx.close()
+
+
+@pytest.mark.parametrize("T", [1, 7, 16, 17, 33, 40])
+def test_forward_ragged_token_counts(B, LY, dxo, T):
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=4, k=2)   # few experts: segments longer than one 16-row tile
+    print(f"forward ragged T={T}", flush=True)
+    x, logits = W.layer_inputs(wl, seed=3)
+    ly = Layer(B, LY, dxo, wl, [0, 2], seed=3)
+    y_gpu, y_ref = ly.run(x, logits)
+    assert rel_l2(y_gpu, y_ref) <= REL_L2_TOL
+    # per-token check as well: no token may be far off
+    yg = bf16_bits_to_f32(y_gpu).astype(np.float64)
+    tok = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
+    assert tok.max() <= 2 * REL_L2_TOL
+    ly.ctx.close()
+
+
+def test_forward_group32(B, LY, dxo):
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], group=32, T=9)
+    x, logits = W.layer_inputs(wl, seed=4)
+    ly = Layer(B, LY, dxo, wl, [3], seed=4)
+    y_gpu, y_ref = ly.run(x, logits)
+    assert rel_l2(y_gpu, y_ref) <= REL_L2_TOL
+    ly.ctx.close()
+
+
+def test_forward_c2_decode_full(B, LY, dxo):
+    """The 30B-shaped decode layer at full size; resident set = top-32 by the oracle's window counts."""
+    wl = WORKLOADS["C2"]
+    print("forward C2: drawing masters", flush=True)
+    masters = W.layer_masters(wl, 0, 0)
+    x, logits = W.layer_inputs(wl, seed=0)
+    # hotness from a warm-up window of routing only (oracle side decides the set for both)
+    c = np.zeros(wl.E, np.int64)
+    for step in range(1, 9):
+        _, lg = W.layer_inputs(wl, seed=0, step=step)
+        _, _, counts, _, _ = dxo.route(lg, wl.k)
+        dxo.hotness_update(c, counts)
+    S = np.zeros(wl.E, np.uint64)
+    dxo.window_end(S, c, 0)
+    resident = dxo.select_topn(S, wl.n_hi)
+    print("forward C2: running", flush=True)
+    ly = Layer(B, LY, dxo, wl, resident, masters=masters)
+    y_gpu, y_ref = ly.run(x, logits)
+    err = rel_l2(y_gpu, y_ref)
+    print("  C2 rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    ly.ctx.close()
+
+
+def test_forward_with_shared_expert(B, LY, dxo):
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C4"], L=1, E=16, k=4, T=19, d=256, f=128, shared_f=256, group=128)
+    x, logits = W.layer_inputs(wl, seed=5)
+    shared = W.shared_master(wl, 5, 0)
+    ly = Layer(B, LY, dxo, wl, [0, 5, 9], seed=5, shared=shared)
+    y_gpu, y_ref = ly.run(x, logits)
+    err = rel_l2(y_gpu, y_ref)
+    print("  shared rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    ly.ctx.close()
+
+
+def test_forward_empty_batch_and_bad_arguments(B, LY, dxo):
+    wl = WORKLOADS["C1"]
+    ly = Layer(B, LY, dxo, wl, [0])
+    y = torch.zeros((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+    x = torch.zeros((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+    ly.rb.forward(ly.ctx, 0, x, y, None, 0)                      # T = 0: nothing to do
+    with pytest.raises(B.DxError):
+        ly.rb.forward(ly.ctx, 0, None, y, None, 4)
+    with pytest.raises(B.DxError):
+        ly.rb.forward(ly.ctx, 1, x, y, None, 4)
+    with pytest.raises(B.DxError):
+        ly.rb.forward(ly.ctx, 0, x, y, None, wl.T + 1)
+    ly.ctx.close()
+    # a context whose experts were never published refuses to run
+    ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T)
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    with pytest.raises(B.DxError):
+        rb.forward(ctx, 0, x, y, None, 4)
+    ctx.close()
+
+
+# ---------------------------------------------------------- swap / publication
+def test_swap_handle_takes_effect_between_forward_passes(B, LY, dxo):
+    wl = WORKLOADS["C1"]
+    x, logits = W.layer_inputs(wl, seed=0)
+    masters = W.layer_masters(wl, 0, 0)
+    ly = Layer(B, LY, dxo, wl, [], masters=masters)              # all int4
+    y_gpu0, y_ref0 = ly.run(x, logits)
+    assert rel_l2(y_gpu0, y_ref0) <= REL_L2_TOL
+    fm = ly.ctx.dx_get_formats()
+    assert np.all(fm == B.DX_FMT_INT4G)
+    # publish bf16 versions of every expert, straight from the master tensors
+    v0 = ly.ctx.dx_get_handle(0, 3).version
+    for e in range(wl.E):
+        ly.ctx.dx_swap_handle(0, e, B.make_handle(B.DX_FMT_BF16, ly.dev[0][e], ly.dev[1][e], ly.dev[2][e]))
+    assert ly.ctx.dx_get_handle(0, 3).version == v0 + 1
+    assert np.all(ly.ctx.dx_get_formats() == B.DX_FMT_BF16)
+    ly.versions = [dxo.ExpertVersion.bf16(masters[0][e], masters[1][e], masters[2][e]) for e in range(wl.E)]
+    y_gpu1, y_ref1 = ly.run(x, logits)
+    assert rel_l2(y_gpu1, y_ref1) <= REL_L2_TOL
+    assert rel_l2(y_gpu1, y_ref0) > rel_l2(y_gpu1, y_ref1)       # it really switched versions
+    # a version whose producer has not finished is refused
+    ev = torch.cuda.Event()
+    side = torch.cuda.Stream()
+    big = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    with torch.cuda.stream(side):
+        for _ in range(20):
+            big.add_(1.0)
+        ev.record(side)
+    with pytest.raises(B.DxError) as ei:
+        ly.ctx.dx_swap_handle(0, 0, ly.lw.handle(0, B.DX_FMT_INT4G), producer_event=ev.cuda_event)
+    assert ei.value.status == B.DX_ERR_BUSY
+    ev.synchronize()
+    ly.ctx.dx_swap_handle(0, 0, ly.lw.handle(0, B.DX_FMT_INT4G), producer_event=ev.cuda_event)
+    assert ly.ctx.dx_get_formats()[0, 0] == B.DX_FMT_INT4G
+    with pytest.raises(B.DxError):
+        ly.ctx.dx_swap_handle(0, wl.E, ly.lw.handle(0, B.DX_FMT_INT4G))   # no shared expert configured
+    ly.ctx.close()
+
+
+# ------------------------------------------------------- hotness and selection
+def test_hotness_window_and_selection_match_oracle(B, LY, dxo):
+    wl = WORKLOADS["C2"]
+    L = 3
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, 0), dxo.expert_bytes(wl.d, wl.f, wl.group, 1)
+    ctx = B.Context(L=L, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T, alpha_q16=16384)
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    c = np.zeros((L, wl.E), np.int64)
+    S = np.zeros((L, wl.E), np.uint64)
+    for window in range(3):
+        for step in range(6):
+            for layer in range(L):
+                _, lg = W.layer_inputs(wl, seed=1, layer=layer, step=window * 6 + step)
+                rb.route(ctx, layer, torch.from_numpy(lg).cuda())
+                ctx.dx_hotness_update(layer, rb.counts)
+                _, _, counts, _, _ = dxo.route(lg, wl.k)
+                dxo.hotness_update(c[layer], counts)
+        assert np.array_equal(ctx.dx_get_counters(), c)
+        S_gpu = ctx.dx_window_end()
+        for layer in range(L):
+            dxo.window_end(S[layer], c[layer], 16384)
+        assert np.array_equal(S_gpu, S)
+        assert not ctx.dx_get_counters().any()
+        for layer in range(L):
+            budget = 535560192
+            ids = ctx.dx_select_resident(layer, budget)
+            n = dxo.budget_capacity(budget, wl.E, b_hi, b_lo)
+            assert n == 32 and np.array_equal(ids, dxo.select_topn(S[layer], n))
+            assert len(ids) * b_hi + (wl.E - len(ids)) * b_lo <= budget
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_select_resident(0, wl.E * b_lo - 1)
+    assert ei.value.status == B.DX_ERR_BUDGET
+    ctx.close()

@@ -1,0 +1,71 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its pure host rules agree with the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2511_15015_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_15015_amd import build
+        build.build(verbose=False)
+    binding.load()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    text = open(os.path.join(ROOT, "include", "dynaexq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(dx_[a-z_0-9]+)\s*\(", text)))
+    assert len(declared) >= 20
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in dynaexq.h but not exported"
+    assert sorted(B.EXPORTS) == declared
+
+
+def test_struct_sizes_match_the_header(B):
+    assert C.sizeof(B.DxHandle) == 64
+    assert C.sizeof(B.DxConfig) == 56
+    assert C.sizeof(B.DxStats) == 80
+
+
+def test_host_rules_agree_with_oracle(B, dxo):
+    g = np.random.default_rng(0)
+    for d, f, grp in [(256, 128, 64), (2048, 768, 128), (2048, 512, 128), (64, 32, 32)]:
+        for fmt in (0, 1):
+            assert B.dx_expert_bytes(d, f, grp, fmt) == dxo.expert_bytes(d, f, grp, fmt)
+    b_hi, b_lo = B.dx_expert_bytes(2048, 768, 128, 0), B.dx_expert_bytes(2048, 768, 128, 1)
+    for _ in range(300):
+        E = int(g.integers(1, 600))
+        budget = int(g.integers(0, int(E * b_hi * 1.2)))
+        assert B.dx_budget_capacity(budget, E, b_hi, b_lo) == dxo.budget_capacity(budget, E, b_hi, b_lo)
+    for E, n in [(8, 2), (128, 32), (512, 12), (7, 7), (7, 0)]:
+        S = g.integers(0, 30, E).astype(np.uint64) << np.uint64(16)
+        assert np.array_equal(B.dx_select_topn(S, n), dxo.select_topn(S, n))
+    with pytest.raises(B.DxError):
+        B.dx_select_topn(np.zeros(4, np.uint64), 5)
+
+
+def test_no_fallback_when_library_is_missing(B, monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libdynaexq.so")
+    with pytest.raises(ImportError):
+        B.load()
+
+
+def test_product_path_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2511_15015_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in src.replace("the CPU oracle", "").replace("CPU oracle", ""), fn
+                assert "dxo" not in src, fn
