@@ -69,6 +69,10 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(or paper_2511_15015_amd/build.py) first; there is no CPU fallback")
+    # PyTorch ships its own HIP runtime (same soname as the system one).  Import it
+    # first so that this library binds to the runtime that owns torch's memory and
+    # streams instead of bringing a second runtime into the process.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, u64 = C.c_void_p, C.c_int, C.c_uint64
     L.dx_create.argtypes = [C.POINTER(DxConfig), vp, C.POINTER(vp)]
