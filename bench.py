@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-precision MoE layer on one MI355X.
+
+A step is one pass of the whole hot path over one batch: dx_route ->
+dx_hotness_update -> dx_moe_forward for one 30B-shaped MoE layer at decode
+batch 32 (workload C2).  Steps rotate over `--layers` independent layers'
+weights (default 48, the model's depth, ~26 GB) so that no step finds its
+expert weights in the 256 MB last-level cache.  Each layer's bf16 resident set
+is what the budget rule selects from a warm-up window of router traces.
+
+Prints one JSON line: MoE-layer tokens/s, the roofline record of the dominant
+kernel (gate/up + SwiGLU, timed with HIP events on the compute stream in a
+second pass over the same steps), and the CPU oracle timed on one layer call.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+C2_LAYER_BUDGET = 535560192   # bytes: 32 bf16 + 96 int4 experts of the 30B shape
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=960)
+    ap.add_argument("--warmup", type=int, default=96)
+    ap.add_argument("--workload", default="C2", choices=["C2", "C3"])
+    ap.add_argument("--layers", type=int, default=48, help="independent weight sets to rotate over")
+    ap.add_argument("--window", type=int, default=64, help="routing-only warm-up steps per layer for hotness")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one process, one MI355X); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2511_15015_amd import binding as B
+    from paper_2511_15015_amd import layer as LY
+    from paper_2511_15015_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    wl = W.WORKLOADS[args.workload]
+    L, T, E, k, d, f = args.layers, wl.T, wl.E, wl.k, wl.d, wl.f
+    seed = args.seed
+    b_hi = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_BF16)
+    b_lo = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_INT4G)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = B.Context(L=L, E=E, d=d, f=f, top_k=k, group=wl.group, max_tokens=T,
+                        window_steps=args.window, budget_bytes=L * C2_LAYER_BUDGET, stream=stream.cuda_stream)
+        rb = LY.RoutingBuffers(T, E, k)
+        # inputs of every layer: the measured batch plus the warm-up window's router traces
+        xs, lgs = [], []
+        for layer in range(L):
+            x, lg = W.layer_inputs(wl, seed, layer, step=0)
+            xs.append(LY.bits_to_device(x))
+            lgs.append(torch.from_numpy(lg).cuda())
+        wr = [W.router_matrix(wl, seed, layer) for layer in range(L)]
+        for step in range(1, args.window + 1):
+            for layer in range(L):
+                xw = W.activations(wl, seed, layer, step)
+                lg = torch.from_numpy(W.router_logits(wl, xw, wr[layer], seed, layer)).cuda()
+                rb.route(ctx, layer, lg)
+                ctx.dx_hotness_update(layer, rb.counts)
+        ctx.dx_window_end()
+        resident = [ctx.dx_select_resident(layer, C2_LAYER_BUDGET) for layer in range(L)]
+        assert all(len(r) == wl.n_hi for r in resident), [len(r) for r in resident]
+        # weights: draw each layer's masters on the device, keep bf16 for the resident set, int4 for the rest
+        layers = []
+        for layer in range(L):
+            wg, wu, wd = W.device_masters(wl, seed, layer)
+            layers.append(LY.LayerWeights(ctx, layer, wg, wu, wd, resident[layer], wl.group, keep_masters=False))
+            del wg, wu, wd
+        y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+        stream.synchronize()
+
+        # argument tuples resolved once: the timed loop is three C calls per step
+        lib, h = ctx.lib, ctx.h
+        p_ids, p_w, p_counts, p_off, p_perm = (t.data_ptr() for t in (rb.ids, rb.w, rb.counts, rb.offsets, rb.perm))
+        route_args = [(h, layer, lgs[layer].data_ptr(), T, p_ids, p_w, p_counts, p_off, p_perm) for layer in range(L)]
+        fwd_args = [(h, layer, None, xs[layer].data_ptr(), T, p_ids, p_w, p_off, p_perm, y.data_ptr())
+                    for layer in range(L)]
+
+        def step_fn(i):
+            layer = i % L
+            if lib.dx_route(*route_args[layer]) or lib.dx_hotness_update(h, layer, p_counts) \
+                    or lib.dx_moe_forward(*fwd_args[layer]):
+                raise RuntimeError(lib.dx_last_error(h).decode())
+
+        for i in range(args.warmup):
+            step_fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step_fn(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+        # second pass over the same steps with HIP events around each forward kernel
+        ctx.dx_set_profiling(True)
+        alg_bytes = 0.0
+        for i in range(args.steps):
+            step_fn(i)
+            if i < L:   # algorithmic bytes of the gate/up launch for this layer's batch
+                counts = rb.counts.cpu().numpy()
+                act = counts > 0
+                hi = layers[i % L].is_hi
+                alg = (act & hi).sum() * (2 * b_hi // 3) + (act & ~hi).sum() * (2 * b_lo // 3) + T * d * 2
+                alg_bytes += float(alg)
+        prof = ctx.dx_get_profile()
+        ctx.dx_set_profiling(False)
+        n_alg = min(args.steps, L)
+        alg_per_launch = alg_bytes / n_alg
+        gate_up_us = prof["gate_up_ms"] * 1e3 / prof["calls"]
+        achieved = alg_per_launch / (gate_up_us * 1e-6) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"k_gate_up_{args.workload}_decode_pmc.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+
+    out = {
+        "metric": "MoE-layer tokens/s (decode B=32) + achieved HBM GB/s",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: 30B-A3B-shaped MoE layer, decode T={T}, d={d}, f={f}, E={E}, top-{k}, "
+                               f"Zipf(s={wl.zipf_s}) routing, {wl.n_hi} bf16 + {E - wl.n_hi} int4-g{wl.group} experts "
+                               f"per layer, rotating over {L} layers' weights",
+                   "step": "dx_route + dx_hotness_update + dx_moe_forward of one layer"},
+        "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
+                      "combine": prof["combine_ms"] * 1e3 / prof["calls"]},
+        "roofline": {"bound": "hbm", "kernel": "k_gate_up", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us},
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle, as it stands, on one full layer call (layer 0, all T tokens) on the host cores
+        from oracle import dxo
+        x0, lg0 = W.layer_inputs(wl, seed, 0, step=0)
+        wg, wu, wd = (LY.device_to_bits(m) for m in W.device_masters(wl, seed, 0))
+        ids, w, counts, offsets, perm = dxo.route(lg0, k)
+        res0 = set(int(e) for e in resident[0])
+        versions = [None] * E
+        for e in np.flatnonzero(counts > 0):
+            versions[e] = (dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if int(e) in res0
+                           else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group))
+        filler = next(v for v in versions if v is not None)
+        versions = [v if v is not None else filler for v in versions]     # never routed to
+        t0 = time.perf_counter()
+        ids, w, counts, offsets, perm = dxo.route(lg0, k)
+        y_ref = dxo.moe_forward(versions, d, f, wl.group, x0, ids, w)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": T / dt, "unit": "tokens/s", "cores": dxo.threads(), "kind": "oracle",
+                               "sample": f"one full layer call (layer 0, all {T} tokens, route + forward), {dt:.2f} s"}
+        # the same call on the GPU, as a sanity check of the benchmarked path
+        with torch.cuda.stream(stream):
+            rb.route(ctx, 0, lgs[0])
+            rb.forward(ctx, 0, xs[0], y)
+            stream.synchronize()
+        yg = W.bf16_bits_to_f32(LY.device_to_bits(y)).astype(np.float64)
+        out["parity_rel_l2_layer0"] = float(np.linalg.norm(yg - y_ref) / np.linalg.norm(y_ref))
+        out["parity_ids_exact_layer0"] = bool(np.array_equal(rb.ids.cpu().numpy(), ids))
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

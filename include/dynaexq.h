@@ -191,6 +191,20 @@ dx_status dx_get_states(dx_ctx *ctx, uint8_t *state_out /* host [L*E], dx_state 
 dx_status dx_get_counters(dx_ctx *ctx, int64_t *counters_out /* host [L*E] */); /* syncs the compute stream */
 dx_status dx_get_stats(dx_ctx *ctx, dx_stats *out);
 
+/* Per-kernel timing of dx_moe_forward with HIP events on the compute stream
+ * (measurement aid, off by default).  While enabled, every forward call
+ * records events around its kernels; dx_get_profile synchronises the compute
+ * stream, adds the elapsed times of all calls since the last read and clears
+ * them. */
+typedef struct {
+    uint64_t calls;     /* forward calls accumulated */
+    double gate_up_ms;  /* summed duration of the gate/up + SwiGLU kernel */
+    double down_ms;     /* summed duration of the down-projection kernel */
+    double combine_ms;  /* summed duration of the combine kernel (0 when fused away) */
+} dx_profile;
+dx_status dx_set_profiling(dx_ctx *ctx, int enable);
+dx_status dx_get_profile(dx_ctx *ctx, dx_profile *out);
+
 /* ------------------------------------------- pools and transitions (Sec. 3.3, 3.4) */
 /* One-time carve-out of the two weight pools: hi_blocks blocks of b_hi bytes
  * and lo_blocks blocks of b_lo bytes (each rounded up to 256), with

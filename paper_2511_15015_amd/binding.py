@@ -13,7 +13,7 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libdynaexq.so")
+LIB_PATH = os.environ.get("DYNAEXQ_LIB", os.path.join(_PKG, "libdynaexq.so"))
 
 DX_OK, DX_ERR_INVALID, DX_ERR_BUDGET, DX_ERR_BUSY, DX_ERR_NOMEM, DX_ERR_HIP = range(6)
 DX_FMT_BF16, DX_FMT_INT4G = 0, 1
@@ -25,6 +25,7 @@ EXPORTS = [
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
     "dx_quantize_expert", "dx_swap_handle",
     "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats",
+    "dx_set_profiling", "dx_get_profile",
     "dx_pools_create", "dx_expert_install", "dx_promote_async", "dx_demote_async", "dx_migrate_poll",
 ]
 
@@ -50,6 +51,11 @@ class DxStats(C.Structure):
 
     def asdict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class DxProfile(C.Structure):
+    _fields_ = [("calls", C.c_uint64), ("gate_up_ms", C.c_double), ("down_ms", C.c_double),
+                ("combine_ms", C.c_double)]
 
 
 class DxError(RuntimeError):
@@ -102,6 +108,8 @@ def load():
     L.dx_get_states.argtypes = [vp, vp]
     L.dx_get_counters.argtypes = [vp, vp]
     L.dx_get_stats.argtypes = [vp, C.POINTER(DxStats)]
+    L.dx_set_profiling.argtypes = [vp, i32]
+    L.dx_get_profile.argtypes = [vp, C.POINTER(DxProfile)]
     L.dx_pools_create.argtypes = [vp, i32, i32]
     L.dx_expert_install.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32]
     L.dx_promote_async.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -248,6 +256,14 @@ class Context:
         st = DxStats()
         self._chk(self.lib.dx_get_stats(self.h, C.byref(st)), "dx_get_stats")
         return st.asdict()
+
+    def dx_set_profiling(self, enable: bool):
+        self._chk(self.lib.dx_set_profiling(self.h, 1 if enable else 0), "dx_set_profiling")
+
+    def dx_get_profile(self) -> dict:
+        p = DxProfile()
+        self._chk(self.lib.dx_get_profile(self.h, C.byref(p)), "dx_get_profile")
+        return {"calls": int(p.calls), "gate_up_ms": p.gate_up_ms, "down_ms": p.down_ms, "combine_ms": p.combine_ms}
 
     # pools and transitions
     def dx_pools_create(self, hi_blocks, lo_blocks):

@@ -193,6 +193,9 @@ extern "C" dx_status dx_create(const dx_config *cfg, void *stream, dx_ctx **out)
     };
     hipError_t e;
     if ((e = hipGetDevice(&c->device)) != hipSuccess) return fail(e, "hipGetDevice");
+    if ((e = hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device)) != hipSuccess)
+        return fail(e, "hipDeviceGetAttribute");
+    if (c->n_cu <= 0) c->n_cu = 256;
     if ((e = hipStreamCreateWithFlags(&c->mig, hipStreamNonBlocking)) != hipSuccess) return fail(e, "migration stream");
     if ((e = hipMalloc(&c->d_table, n_entries * sizeof(dx_handle))) != hipSuccess) return fail(e, "handle table");
     if ((e = hipMalloc(&c->d_counters, (size_t)g.L * g.E * 8)) != hipSuccess) return fail(e, "counters");
@@ -234,6 +237,9 @@ extern "C" void dx_destroy(dx_ctx *c)
     }
     for (auto &t : c->inflight) (void)hipEventDestroy(t.done);
     for (auto ev : c->event_pool) (void)hipEventDestroy(ev);
+    for (auto ev : c->timing_pool) (void)hipEventDestroy(ev);
+    for (auto &m : c->marks)
+        for (auto ev : m) (void)hipEventDestroy(ev);
     for (dx_block_pool *p : {&c->pool_hi, &c->pool_lo}) {
         for (auto ev : p->reuse_after)
             if (ev) (void)hipEventDestroy(ev);
@@ -308,7 +314,26 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
     a.group = g.group;
     a.shared_f = g.shared_f;
     a.fmax = c->fmax;
-    DX_HIP(c, dxk_moe_forward(a, c->compute));
+    if (!c->profiling) {
+        DX_HIP(c, dxk_moe_forward(a, c->n_cu, c->compute, nullptr));
+        return DX_OK;
+    }
+    std::array<hipEvent_t, 4> m;
+    for (int i = 0; i < 4; ++i) {
+        if (!c->timing_pool.empty()) {
+            m[i] = c->timing_pool.back();
+            c->timing_pool.pop_back();
+        } else {
+            hipError_t e = hipEventCreate(&m[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) c->timing_pool.push_back(m[j]);
+                DX_FAIL(c, DX_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+            }
+        }
+    }
+    hipError_t e = dxk_moe_forward(a, c->n_cu, c->compute, m.data());
+    c->marks.push_back(m);
+    if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_moe_forward: %s", hipGetErrorString(e));
     return DX_OK;
 }
 
@@ -473,6 +498,34 @@ extern "C" dx_status dx_get_stats(dx_ctx *c, dx_stats *out)
 {
     if (!c || !out) return DX_ERR_INVALID;
     *out = c->stats;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_set_profiling(dx_ctx *c, int enable)
+{
+    if (!c) return DX_ERR_INVALID;
+    c->profiling = enable != 0;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_get_profile(dx_ctx *c, dx_profile *out)
+{
+    if (!c || !out) return DX_ERR_INVALID;
+    *out = dx_profile{};
+    DX_HIP(c, hipStreamSynchronize(c->compute));
+    for (auto &m : c->marks) {
+        float t[3] = {0.f, 0.f, 0.f};
+        for (int i = 0; i < 3; ++i) {
+            hipError_t e = hipEventElapsedTime(&t[i], m[i], m[i + 1]);
+            if (e != hipSuccess) t[i] = 0.f; // a call that recorded nothing (T == 0)
+        }
+        out->calls++;
+        out->gate_up_ms += t[0];
+        out->down_ms += t[1];
+        out->combine_ms += t[2];
+        for (auto ev : m) c->timing_pool.push_back(ev);
+    }
+    c->marks.clear();
     return DX_OK;
 }
 

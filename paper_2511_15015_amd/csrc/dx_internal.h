@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <array>
 #include <cstdint>
 #include <cstdio>
 #include <deque>
@@ -39,6 +40,7 @@ struct dx_transition {
 struct dx_ctx {
     dx_config cfg{};
     int device = 0;
+    int n_cu = 0; // compute units of the device: size of the persistent grids
     hipStream_t compute = nullptr;
     hipStream_t mig = nullptr;
     std::string err;
@@ -72,6 +74,11 @@ struct dx_ctx {
     std::deque<dx_transition> inflight;
     std::vector<hipEvent_t> event_pool;
     dx_stats stats{};
+
+    // optional per-kernel timing of the forward pass
+    bool profiling = false;
+    std::vector<hipEvent_t> timing_pool;           // free timing-enabled events
+    std::vector<std::array<hipEvent_t, 4>> marks;  // one tuple per profiled forward call
 };
 
 #define DX_FAIL(ctx, code, ...)                                   \
@@ -116,4 +123,5 @@ struct dx_fwd_args {
     float *o;    // scratch [T*k (+T), d]
     int T, E, k, d, f, group, shared_f, fmax;
 };
-hipError_t dxk_moe_forward(const dx_fwd_args &a, hipStream_t s);
+// marks: null, or 4 events recorded before gate/up, after it, after down, after combine
+hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, hipEvent_t *marks);

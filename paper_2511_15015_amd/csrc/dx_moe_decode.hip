@@ -7,27 +7,55 @@
 // gfx950.
 //
 // Regime: every activated expert's weights are streamed from HBM exactly once
-// and there are at most a few dozen tokens per expert, so the kernels are
-// bandwidth-bound.  One wavefront owns a strip of 16 weight rows (two strips:
-// gate+up rows of the same index, or two adjacent down strips) over the whole
-// K extent and feeds them straight from global memory into the B operand of
-// v_mfma_f32_16x16x32_bf16; the (few) token rows are the A operand and come
-// from L2.  Lane (r = lane%16, q = lane/16) owns row r and, inside each
-// K-chunk of 4*LK elements, the LK consecutive elements starting at q*LK, so a
-// strip's row is read in contiguous 4*LK-element pieces (256 B for bf16).  A
-// uses the same K ownership, which makes any K order valid for the MFMA.
-// int4 weights are expanded to exact small bf16 integers; because a K-chunk
-// never crosses a quantization group, the group's scale is applied once to the
-// chunk's fp32 partial sums (q*s is never rounded).
+// and there are at most a few dozen tokens per expert, so both GEMM kernels are
+// bandwidth-bound.  What decides the achieved bandwidth on this chip is that
+// every compute unit streams for the whole duration of the kernel, so:
+//   - Persistent grid, one block of 8 wavefronts per compute unit.  The work
+//     is the list of (activated expert, 32-token block, pair of 16-row weight
+//     strips); a bf16 strip pair weighs 4 units, an int4 one 1 unit, and block
+//     b takes the strips that start in units [b*U/G, (b+1)*U/G).  Every block
+//     derives the same partition from `offsets` and the handles' formats in
+//     its prologue (a block-wide scan): no atomics, no work queue.
+//   - The 8 wavefronts of a block split the K extent of a strip pair between
+//     them (wavefront kw owns CPW consecutive K-chunks of 4*LK elements), so a
+//     whole strip pair is in flight at once and the next one is prefetched
+//     into a second register stage while this one is multiplied.  When K is
+//     short (down projection), the block works on several strip pairs side by
+//     side.  Partial sums meet in LDS, are added in a fixed order and finished
+//     (SwiGLU, or the store of the down output) by all threads of the block.
+//   - The token rows (A operand of v_mfma_f32_16x16x32_bf16) only depend on
+//     the expert and the K-chunk, so each wavefront keeps its fragments in
+//     registers for all strips of a run: after the first strip, weights are
+//     the only global traffic.
+//   - Lane (r = lane%16, q = lane/16) owns weight row r.  bf16: step j of a
+//     chunk takes elements 32j + 8q .. +7 (four lanes of a row read 64
+//     contiguous bytes per instruction).  int4: the lane takes the LK
+//     consecutive elements at q*LK (one 16-byte load of nibbles for LK = 32).
+//     Token fragments use the same K ownership, which makes either order valid.
+//   - int4 weights are expanded to exact small bf16 integers; a K-chunk never
+//     crosses a quantization group, so the group's scale multiplies the chunk's
+//     fp32 partial sums once (q*s is never rounded).
 #include "dx_internal.h"
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4; // 16 bytes in registers
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// Pointers that come out of a handle are loaded from memory, so the compiler cannot infer their
+// address space and would fall back to FLAT loads (whose wait counters serialise the pipeline).
+// Everything the kernels stream is in global memory: say so in the type.
+#define DX_GLOBAL __attribute__((address_space(1)))
+typedef const DX_GLOBAL char *gbytes;   // weight bytes
+typedef const DX_GLOBAL dx_bf16 *gbf16; // bf16 rows (scales, tokens)
+typedef const DX_GLOBAL u32x4 *gvec16;
+typedef const DX_GLOBAL u32x2 *gvec8;
+typedef const DX_GLOBAL uint32_t *gvec4;
 
 union frag8 {
-    uint4 u;
+    u32x4 u;
     bf16x8 v;
 };
 
@@ -40,267 +68,474 @@ __device__ __forceinline__ uint32_t float_to_bf16_rne(float f)
     return u >> 16;
 }
 
-// 8 two's-complement nibbles (element t at bits 4t) -> 8 bf16 holding the exact integers
-__device__ __forceinline__ bf16x8 nibbles_to_bf16(uint32_t word)
+// int4 -> bf16 without arithmetic.  XOR with 0x8 turns a two's-complement nibble q into u = q + 8 in
+// [0, 15]; OR-ing u into the mantissa of bf16 128.0 (0x4300) gives exactly 128 + u = 136 + q.  One
+// shift and one and-or yield two such values, elements t and t+4 of the word, so the 8 elements come
+// out in the order (0,4,1,5,2,6,3,7); the token fragment is permuted to match once per run, and the
+// bias is removed through  sum_k a_k (136 + q_k) - 136 sum_k a_k.
+constexpr float kNibbleBias = 136.f;
+
+__device__ __forceinline__ bf16x8 nibbles_to_biased_bf16(uint32_t word)
 {
+    const uint32_t u = word ^ 0x88888888u;
     frag8 out;
-    uint32_t p[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int lo = (int)(word << (28 - 8 * i)) >> 28;
-        const int hi = (int)(word << (24 - 8 * i)) >> 28;
-        // small integers are exact in bf16: keep the upper 16 bits of the fp32 pattern
-        p[i] = (__float_as_uint((float)lo) >> 16) | (__float_as_uint((float)hi) & 0xFFFF0000u);
-    }
-    out.u = make_uint4(p[0], p[1], p[2], p[3]);
+    out.u = u32x4{(u & 0x000F000Fu) | 0x43004300u, ((u >> 4) & 0x000F000Fu) | 0x43004300u,
+                  ((u >> 8) & 0x000F000Fu) | 0x43004300u, ((u >> 12) & 0x000F000Fu) | 0x43004300u};
     return out.v;
 }
 
-// One pipeline stage: the lane's piece of one K-chunk of NB weight strips and MT token tiles.
-template <int NB, int MT, int LK, bool INT4>
-struct stage {
-    uint4 wb[INT4 ? 1 : NB][INT4 ? 1 : LK / 8]; // bf16 weights
-    uint32_t wq[INT4 ? NB : 1][LK / 8];         // int4 weights, 8 nibbles per word
-    uint16_t sc[INT4 ? NB : 1];                 // group scales (bf16 bits)
-    uint4 a[MT][LK / 8];                        // token rows
+// the same element order for a token fragment: (e0..e7) -> (e0,e4,e1,e5,e2,e6,e3,e7)
+__device__ __forceinline__ u32x4 interleave_halves(u32x4 v)
+{
+    return u32x4{(v.x & 0x0000FFFFu) | (v.z << 16), (v.x >> 16) | (v.z & 0xFFFF0000u),
+                 (v.y & 0x0000FFFFu) | (v.w << 16), (v.y >> 16) | (v.w & 0xFFFF0000u)};
+}
+
+constexpr int kWaves = 8;             // wavefronts per block
+constexpr int kThreads = 64 * kWaves; // 512
+constexpr int kMaxExperts = 1024 + 1; // routed + shared
+// Relative cost of a bf16 / int4 strip pair in the partition.  An int4 pair is a quarter of the bytes
+// but carries the same per-step work (barrier, reduction), so it is weighed by measured time, not bytes.
+constexpr int kHiUnits = 8, kLoUnits = 3;
+
+#ifdef DX_TRACE
+// Debug build only: per-block start/end time stamps (100 MHz wall clock).
+__device__ unsigned long long g_trace[2][8192][4];
+#endif
+
+// element offset inside a chunk of MFMA step j for lane quarter q
+template <int LK, bool INT4>
+__device__ __forceinline__ int k_of(int j, int q)
+{
+    return INT4 ? q * LK + 8 * j : 32 * j + 8 * q;
+}
+
+// weight registers of one wavefront for one 16-row strip: CPW chunks
+template <int LK, int CPW, bool INT4>
+struct wstage {
+    static constexpr int JN = LK / 8;
+    u32x4 w[CPW][INT4 ? 1 : JN];    // bf16: JN 16-byte pieces per chunk
+    uint32_t wq[CPW][INT4 ? JN : 1]; // int4: JN words of 8 nibbles
+    uint32_t sc[CPW];               // int4: bf16 bits of the chunk's group scale
 };
 
-template <int NB, int MT, int LK, bool INT4>
-__device__ __forceinline__ void load_stage(stage<NB, MT, LK, INT4> &st, const char *const (&wrow)[NB],
-                                           const dx_bf16 *const (&srow)[NB], const dx_bf16 *const (&arow)[MT],
-                                           int c, int q, int chunks_per_group_shift_unused, int group)
+template <int LK, int CPW, bool INT4>
+__device__ __forceinline__ void issue_weights(wstage<LK, CPW, INT4> &st, gbytes row, gbf16 srow, int c0, int nc, int q,
+                                              int group)
 {
-    constexpr int CHUNK = 4 * LK;
-    const int k0 = c * CHUNK + q * LK; // first K element this lane owns in chunk c
+    constexpr int CHUNK = 4 * LK, JN = LK / 8;
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if constexpr (INT4) {
-            const char *p = wrow[b] + (k0 >> 1);
-            if constexpr (LK == 32) {
-                uint4 t = *reinterpret_cast<const uint4 *>(p);
-                st.wq[b][0] = t.x; st.wq[b][1] = t.y; st.wq[b][2] = t.z; st.wq[b][3] = t.w;
-            } else if constexpr (LK == 16) {
-                uint2 t = *reinterpret_cast<const uint2 *>(p);
-                st.wq[b][0] = t.x; st.wq[b][1] = t.y;
+    for (int i = 0; i < CPW; ++i) {
+        const int c = c0 + i;
+        if (c < nc) { // wavefront-uniform
+            if constexpr (INT4) {
+                gbytes p = row + ((c * CHUNK + q * LK) >> 1);
+                if constexpr (LK == 32) {
+                    const u32x4 t = *reinterpret_cast<gvec16>(p);
+                    st.wq[i][0] = t.x; st.wq[i][1] = t.y; st.wq[i][2] = t.z; st.wq[i][3] = t.w;
+                } else if constexpr (LK == 16) {
+                    const u32x2 t = *reinterpret_cast<gvec8>(p);
+                    st.wq[i][0] = t.x; st.wq[i][1] = t.y;
+                } else {
+                    st.wq[i][0] = *reinterpret_cast<gvec4>(p);
+                }
+                st.sc[i] = srow[(c * CHUNK) / group];
             } else {
-                st.wq[b][0] = *reinterpret_cast<const uint32_t *>(p);
-            }
-            st.sc[b] = srow[b][(c * CHUNK) / group];
-        } else {
-            const uint4 *p = reinterpret_cast<const uint4 *>(wrow[b] + (size_t)k0 * 2);
 #pragma unroll
-            for (int j = 0; j < LK / 8; ++j) st.wb[b][j] = p[j];
+                for (int j = 0; j < JN; ++j)
+                    st.w[i][j] = *reinterpret_cast<gvec16>(row + (size_t)(c * CHUNK + k_of<LK, false>(j, q)) * 2);
+            }
         }
     }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(arow[mt] + k0);
-#pragma unroll
-        for (int j = 0; j < LK / 8; ++j) st.a[mt][j] = p[j];
-    }
-    (void)chunks_per_group_shift_unused;
 }
 
-template <int NB, int MT, int LK, bool INT4>
-__device__ __forceinline__ void compute_stage(const stage<NB, MT, LK, INT4> &st, f32x4 (&acc)[NB][MT])
+template <int LK, int CPW, bool INT4, int MT>
+__device__ __forceinline__ void load_tokens(u32x4 (&x)[CPW][MT][LK / 8], gbf16 arow0, gbf16 arow1, int c0, int nc,
+                                            int q)
 {
+    constexpr int CHUNK = 4 * LK, JN = LK / 8;
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if constexpr (INT4) {
-            f32x4 part[MT];
+    for (int i = 0; i < CPW; ++i) {
+        const int c = c0 + i;
+        if (c < nc) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) part[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int j = 0; j < LK / 8; ++j) {
-                const bf16x8 wv = nibbles_to_bf16(st.wq[b][j]);
+                for (int j = 0; j < JN; ++j)
+                    x[i][mt][j] = *reinterpret_cast<gvec16>((mt ? arow1 : arow0) + c * CHUNK + k_of<LK, INT4>(j, q));
+        }
+    }
+}
+
+// int4 runs: bring the token fragments into the element order of nibbles_to_biased_bf16 and compute
+// bias[i][mt] = 136 * sum over chunk i of the token row (one MFMA against all-ones per step), laid out
+// like an accumulator (every column holds the row's sum).
+template <int LK, int CPW, int MT>
+__device__ __forceinline__ void prepare_int4_tokens(u32x4 (&x)[CPW][MT][LK / 8], f32x4 (&bias)[CPW][MT], int c0, int nc)
+{
+    constexpr int JN = LK / 8;
+    frag8 ones;
+    ones.u = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
+    for (int i = 0; i < CPW; ++i) {
+        if (c0 + i < nc) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < JN; ++j) {
                     frag8 a;
-                    a.u = st.a[mt][j];
-                    part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, wv, part[mt], 0, 0, 0);
+                    a.u = x[i][mt][j];
+                    sum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, ones.v, sum, 0, 0, 0);
+                    x[i][mt][j] = interleave_halves(x[i][mt][j]);
                 }
+                bias[i][mt] = sum * kNibbleBias;
             }
-            const float s = bf16_bits_to_float(st.sc[b]);
+        }
+    }
+}
+
+template <int LK, int CPW, bool INT4, int MT>
+__device__ __forceinline__ void multiply(const wstage<LK, CPW, INT4> &st, const u32x4 (&x)[CPW][MT][LK / 8],
+                                         const f32x4 (&bias)[CPW][MT], int c0, int nc, f32x4 (&acc)[MT])
+{
+    constexpr int JN = LK / 8;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[b][mt] += part[mt] * s;
-        } else {
+    for (int i = 0; i < CPW; ++i) {
+        if (c0 + i < nc) {
+            if constexpr (INT4) {
+                f32x4 part[MT];
 #pragma unroll
-            for (int j = 0; j < LK / 8; ++j) {
-                frag8 wv;
-                wv.u = st.wb[b][j];
+                for (int mt = 0; mt < MT; ++mt) part[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    frag8 a;
-                    a.u = st.a[mt][j];
-                    acc[b][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, wv.v, acc[b][mt], 0, 0, 0);
+                for (int j = 0; j < JN; ++j) {
+                    const bf16x8 wv = nibbles_to_biased_bf16(st.wq[i][j]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        frag8 a;
+                        a.u = x[i][mt][j];
+                        part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, wv, part[mt], 0, 0, 0);
+                    }
+                }
+                const float scale = bf16_bits_to_float(st.sc[i]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[mt] += (part[mt] - bias[i][mt]) * scale;
+            } else {
+#pragma unroll
+                for (int j = 0; j < JN; ++j) {
+                    frag8 wv;
+                    wv.u = st.w[i][j];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        frag8 a;
+                        a.u = x[i][mt][j];
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, wv.v, acc[mt], 0, 0, 0);
+                    }
                 }
             }
         }
     }
 }
 
-// acc[b][mt] = sum over K of tokens(16 rows of tile mt) x strip b (16 weight rows), for this lane's
-// outputs: column n = lane%16 of the strip, token rows 4*(lane/16) .. +3 of the tile.
-template <int NB, int MT, int LK, bool INT4>
-__device__ __forceinline__ void skinny_gemm(const char *const (&wrow)[NB], const dx_bf16 *const (&srow)[NB],
-                                            const dx_bf16 *const (&arow)[MT], int K, int group, int q,
-                                            f32x4 (&acc)[NB][MT])
+// what a block needs to know about the expert it is working on
+struct expert_ctx {
+    gbytes w0, w1;   // gate/up: the gate and up matrices; down: the down matrix twice
+    gbf16 s0, s1;    // their scales (int4)
+    size_t row_bytes;
+    int K;           // contraction length
+    int G;           // scale groups per row
+    int seg0, m;     // segment in the H/O scratch, tokens
+    bool shared, int4;
+};
+
+// Add up the partial sums of the strip pairs sb .. sb+live_groups-1 in a fixed order and finish them:
+// gate/up -> H = silu(gate) * up (bf16); down -> the two 16-row halves of O (fp32).  All threads.
+// Element (group gg, tile mt, accumulator lane L, component i) is token 4*(L/16)+i, column L%16.
+template <bool DOWN, int MT>
+__device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_ctx &ex, int mb, int sb,
+                                             int live_groups, int WPS, const float *redf)
+{
+    const int rows_per_strip = DOWN ? 32 : 16;
+    for (int idx = threadIdx.x; idx < live_groups * MT * 256; idx += kThreads) {
+        const int gg = idx / (MT * 256), rem = idx % (MT * 256);
+        const int mt = rem / 256, L = rem & 63, i = (rem >> 6) & 3;
+        const int slot = mb * 32 + 16 * mt + 4 * (L >> 4) + i;
+        if (slot >= ex.m) continue;
+        float v0 = 0.f, v1 = 0.f;
+        for (int w = 0; w < WPS; ++w) {
+            const float *base = redf + (((gg * WPS + w) * 4) * 64 + L) * 4 + i;
+            v0 += base[(0 * 2 + mt) * 64 * 4];
+            v1 += base[(1 * 2 + mt) * 64 * 4];
+        }
+        const int n = (sb + gg) * rows_per_strip + (L & 15);
+        if constexpr (DOWN) {
+            const int orow = ex.shared ? ex.seg0 + slot : a.perm[ex.seg0 + slot];
+            a.o[(size_t)orow * a.d + n] = v0;
+            a.o[(size_t)orow * a.d + n + 16] = v1;
+        } else {
+            const float hv = v0 / (1.f + expf(-v0)) * v1;
+            a.h[(size_t)(ex.seg0 + slot) * a.fmax + n] = (dx_bf16)float_to_bf16_rne(hv);
+        }
+    }
+}
+
+// One run: strips [s_lo, s_hi) of one expert for one block of up to 32 tokens (mb).
+// All kThreads threads of the block execute this with identical arguments.
+//
+// FAST (K is one round of whole chunks: K / (4*LK) = WPS * CPW with WPS <= 8): the steady-state loop
+// is straight-line code -- every iteration issues the next strip pair's loads unconditionally (the
+// strip index is clamped, so the last iterations of a ragged run fetch a duplicate) -- which lets the
+// compiler wait for exactly the loads it is about to use and keep the prefetch in flight.
+template <int LK, int CPW, bool DOWN, bool INT4, int MT, bool FAST>
+__device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ctx &ex, int mb, int s_lo, int s_hi,
+                                           f32x4 (*red)[kWaves][4][64], int &pb)
 {
     constexpr int CHUNK = 4 * LK;
-    const int nc = K / CHUNK;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, q = lane >> 4;
+    const int nc = ex.K / CHUNK;
+    // wavefronts per strip pair, strip pairs side by side, K rounds
+    const int per = (nc + CPW - 1) / CPW;
+    const int WPS = per < kWaves ? per : kWaves;
+    const int SPP = kWaves / WPS;
+    const int rounds = FAST ? 1 : (per + WPS - 1) / WPS;
+    const int g = wave / WPS, kw = wave % WPS;
+    const bool idle = g >= SPP;
+    const int rows_per_strip = DOWN ? 32 : 16;
+    const int nbatch = (s_hi - s_lo + SPP - 1) / SPP;
+    const int nsteps = nbatch * rounds;
+
+    auto finish = [&](int batch) {
+        __syncthreads();
+        const int sb = s_lo + batch * SPP;
+        const int live_groups = (s_hi - sb) < SPP ? (s_hi - sb) : SPP;
+        finish_batch<DOWN, MT>(a, ex, mb, sb, live_groups, WPS, reinterpret_cast<const float *>(&red[pb][0][0][0]));
+        pb ^= 1; // the other half of `red` is free: its readers passed the barrier above
+    };
+
+    if (idle) { // wavefronts without a K-part (8 is not a multiple of WPS) only help finishing
+        for (int batch = 0; batch < nbatch; ++batch) finish(batch);
+        return;
+    }
+
+    // FAST: nc counts as "unbounded" so that every chunk predicate folds away
+    const int ncp = FAST ? 0x7fffffff : nc;
+    u32x4 x[CPW][MT][LK / 8];
+    f32x4 bias[CPW][MT];
+    gbf16 arow0 = nullptr, arow1 = nullptr; // token rows of this run, looked up after the weight prologue
+    auto fetch_tokens = [&](int c0) {
+        load_tokens<LK, CPW, INT4, MT>(x, arow0, arow1, c0, ncp, q);
+        if constexpr (INT4) prepare_int4_tokens<LK, CPW, MT>(x, bias, c0, ncp);
+    };
+
+    // A step is one 16-row strip: step t = (batch * rounds + round) * 2 + b, b = 0 the first strip of the
+    // pair (gate rows / lower 16 down rows), b = 1 the second (up rows / upper 16 down rows).  NST
+    // register stages: the strip of step t + NST - 1 is fetched while step t is multiplied.  An int4 strip
+    // is a quarter of the bytes, so it gets a deeper pipeline for the same registers.
+    constexpr int NST = INT4 ? 6 : 2;
+    const int nhalf = 2 * nsteps;
+    wstage<LK, CPW, INT4> st[NST];
+    auto issue_step = [&](int t, wstage<LK, CPW, INT4> &dst) {
+        const int b = t & 1, sr = t >> 1;
+        int s = s_lo + (sr / rounds) * SPP + g;
+        s = s < s_hi ? s : s_hi - 1; // ragged tail: fetch a duplicate rather than branch
+        const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
+        const gbytes p = (b ? ex.w1 : ex.w0) + (size_t)n * ex.row_bytes;
+        const gbf16 sp = INT4 ? (b ? ex.s1 : ex.s0) + (size_t)n * ex.G : nullptr;
+        issue_weights<LK, CPW, INT4>(dst, p, sp, ((sr % rounds) * WPS + kw) * CPW, ncp, q, a.group);
+    };
+
+    f32x4 acc[2][MT];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[b][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    stage<NB, MT, LK, INT4> s0, s1;
-    load_stage<NB, MT, LK, INT4>(s0, wrow, srow, arow, 0, q, 0, group);
-    for (int c = 0; c < nc; c += 2) {
-        if (c + 1 < nc) load_stage<NB, MT, LK, INT4>(s1, wrow, srow, arow, c + 1, q, 0, group);
-        compute_stage<NB, MT, LK, INT4>(s0, acc);
-        if (c + 1 < nc) {
-            if (c + 2 < nc) load_stage<NB, MT, LK, INT4>(s0, wrow, srow, arow, c + 2, q, 0, group);
-            compute_stage<NB, MT, LK, INT4>(s1, acc);
-        }
-    }
-}
 
-struct seg_info {
-    int seg0;   // first row of the expert's segment in the H/O scratch
-    int m;      // tokens in the segment
-    bool shared;
-};
+    auto do_step = [&](int t, const wstage<LK, CPW, INT4> &cur, int b /* = t & 1, compile-time at every call */) {
+        const int sr = t >> 1;
+        const int batch = sr / rounds, rnd = sr % rounds;
+        const int c0 = (rnd * WPS + kw) * CPW;
+        if (rounds > 1 && b == 0) fetch_tokens(c0);
+        multiply<LK, CPW, INT4, MT>(cur, x, bias, c0, ncp, acc[b]);
+        if (b == 0 || rnd != rounds - 1) return;
+        // the strip pairs of this batch are complete: park the partial sums (a clamped duplicate is dropped)
+        const bool live = s_lo + batch * SPP + g < s_hi;
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if (live) red[pb][wave][bb * 2 + mt][lane] = acc[bb][mt];
+                acc[bb][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        finish(batch);
+    };
 
-__device__ __forceinline__ seg_info segment_of(int e, int E, int T, int k, const int32_t *offsets)
-{
-    seg_info s;
-    s.shared = e == E;
-    if (s.shared) {
-        s.seg0 = T * k;
-        s.m = T;
-    } else {
-        s.seg0 = offsets[e];
-        s.m = offsets[e + 1] - s.seg0;
-    }
-    return s;
-}
+    // prologue: the first NST-1 strips (nhalf is even and >= 2) go out before anything that depends on
+    // the routing arrays, so that they are in flight while the token rows are looked up
+#pragma unroll
+    for (int i = 0; i < NST - 1; ++i)
+        if (i < nhalf) issue_step(i, st[i]);
 
-constexpr int kTilesPerBlock = 4; // independent wavefronts per block
-
-// ---- gate/up + SwiGLU: H[seg row, n] = silu(x . Wg[n]) * (x . Wu[n]) -------------------
-template <int LK>
-__global__ __launch_bounds__(64 * kTilesPerBlock) void k_gate_up(dx_fwd_args a)
-{
-    const int e = blockIdx.y;
-    const seg_info sg = segment_of(e, a.E, a.T, a.k, a.offsets);
-    if (sg.m == 0) return;
-    const int fe = sg.shared ? a.shared_f : a.f;
-    const int tile = blockIdx.x * kTilesPerBlock + (threadIdx.x >> 6);
-    if (tile * 16 >= fe) return;
-    const dx_handle hd = sg.shared ? *a.shared : a.table[e];
-    const int lane = threadIdx.x & 63, r = lane & 15, q = lane >> 4;
-    const int n = tile * 16 + r;
-    const int K = a.d;
-    const bool int4 = hd.fmt == DX_FMT_INT4G;
-    const size_t row_bytes = int4 ? (size_t)K / 2 : (size_t)K * 2;
-    const char *wrow[2] = {(const char *)hd.w_gate + (size_t)n * row_bytes, (const char *)hd.w_up + (size_t)n * row_bytes};
-    const int G = K / a.group;
-    const dx_bf16 *srow[2] = {int4 ? (const dx_bf16 *)hd.s_gate + (size_t)n * G : nullptr,
-                              int4 ? (const dx_bf16 *)hd.s_up + (size_t)n * G : nullptr};
-
-    for (int mb = 0; mb < sg.m; mb += 32) {
-        const dx_bf16 *arow[2];
+    // token rows of this run (A operand): row r of tile mt
+    {
+        gbf16 arow[2];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            int slot = mb + 16 * mt + r;
-            slot = slot < sg.m ? slot : sg.m - 1;
-            const int tok = sg.shared ? slot : a.perm[sg.seg0 + slot] / a.k;
-            arow[mt] = a.x + (size_t)tok * K;
+            int slot = mb * 32 + 16 * mt + r;
+            slot = slot < ex.m ? slot : ex.m - 1;
+            if constexpr (DOWN) {
+                arow[mt] = (gbf16)a.h + (size_t)(ex.seg0 + slot) * a.fmax;
+            } else {
+                const int tok = ex.shared ? slot : a.perm[ex.seg0 + slot] / a.k;
+                arow[mt] = (gbf16)a.x + (size_t)tok * ex.K;
+            }
         }
-        f32x4 acc[2][2];
-        const bool two = sg.m - mb > 16;
-        if (two) {
-            if (int4) skinny_gemm<2, 2, LK, true>(wrow, srow, arow, K, a.group, q, acc);
-            else skinny_gemm<2, 2, LK, false>(wrow, srow, arow, K, a.group, q, acc);
-        } else {
-            const dx_bf16 *arow1[1] = {arow[0]};
-            f32x4 acc1[2][1];
-            if (int4) skinny_gemm<2, 1, LK, true>(wrow, srow, arow1, K, a.group, q, acc1);
-            else skinny_gemm<2, 1, LK, false>(wrow, srow, arow1, K, a.group, q, acc1);
-            acc[0][0] = acc1[0][0];
-            acc[1][0] = acc1[1][0];
+        arow0 = arow[0];
+        arow1 = arow[1];
+    }
+    if (rounds == 1) fetch_tokens(kw * CPW);
+    int t = 0;
+    // steady state: NST strips per iteration, every prefetch unconditional (NST is even, so stage i always
+    // holds a strip with b = i & 1)
+    for (; t + 2 * NST - 2 < nhalf; t += NST) {
+#pragma unroll
+        for (int i = 0; i < NST; ++i) {
+            issue_step(t + i + NST - 1, st[(i + NST - 1) % NST]);
+            do_step(t + i, st[i], i & 1);
         }
+    }
+    // drain: the same, with the prefetch guarded
+    for (; t < nhalf; t += NST) {
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            if (mt == 1 && !two) break;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int slot = mb + 16 * mt + 4 * q + i;
-                if (slot < sg.m) {
-                    const float g = acc[0][mt][i], u = acc[1][mt][i];
-                    const float hv = g / (1.f + expf(-g)) * u;
-                    a.h[(size_t)(sg.seg0 + slot) * a.fmax + n] = (dx_bf16)float_to_bf16_rne(hv);
-                }
+        for (int i = 0; i < NST; ++i) {
+            if (t + i < nhalf) {
+                if (t + i + NST - 1 < nhalf) issue_step(t + i + NST - 1, st[(i + NST - 1) % NST]);
+                do_step(t + i, st[i], i & 1);
             }
         }
     }
 }
 
-// ---- down: O[out row, n] = H[seg row, :] . Wd[n, :] -------------------------------------
-template <int LK>
-__global__ __launch_bounds__(64 * kTilesPerBlock) void k_down(dx_fwd_args a)
+template <int LK, int CPW, bool DOWN, bool FAST>
+__global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
 {
-    const int e = blockIdx.y;
-    const seg_info sg = segment_of(e, a.E, a.T, a.k, a.offsets);
-    if (sg.m == 0) return;
-    const int K = sg.shared ? a.shared_f : a.f;
-    const int tile = blockIdx.x * kTilesPerBlock + (threadIdx.x >> 6); // 32 output rows per tile
-    if (tile * 32 >= a.d) return;
-    const dx_handle hd = sg.shared ? *a.shared : a.table[e];
-    const int lane = threadIdx.x & 63, r = lane & 15, q = lane >> 4;
-    const int n0 = tile * 32 + r;
-    const bool int4 = hd.fmt == DX_FMT_INT4G;
-    const size_t row_bytes = int4 ? (size_t)K / 2 : (size_t)K * 2;
-    const char *wrow[2] = {(const char *)hd.w_down + (size_t)n0 * row_bytes,
-                           (const char *)hd.w_down + (size_t)(n0 + 16) * row_bytes};
-    const int G = K / a.group;
-    const dx_bf16 *srow[2] = {int4 ? (const dx_bf16 *)hd.s_down + (size_t)n0 * G : nullptr,
-                              int4 ? (const dx_bf16 *)hd.s_down + (size_t)(n0 + 16) * G : nullptr};
+    __shared__ f32x4 red[2][kWaves][4][64]; // 64 KB: partial sums, double buffered
+    __shared__ uint32_t cum[kMaxExperts + 1];
+    __shared__ int seg_start[kMaxExperts], seg_tokens[kMaxExperts];
+    __shared__ uint32_t wave_tot[kWaves];
+    __shared__ int e_first_s;
+#ifdef DX_TRACE
+    const unsigned long long trace_t0 = wall_clock64();
+#endif
+    const int nE = a.E + (a.shared ? 1 : 0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    for (int mb = 0; mb < sg.m; mb += 32) {
-        const dx_bf16 *arow[2];
+    // ---- the partition: cost units of every expert, exclusive prefix, this block's range ----
+    auto tokens_of = [&](int e) { return e == a.E ? a.T : a.offsets[e + 1] - a.offsets[e]; };
+    auto strips_of = [&](int e) { return DOWN ? a.d / 32 : (e == a.E ? a.shared_f : a.f) / 16; };
+    auto fmt_of = [&](int e) { return e == a.E ? (uint32_t)DX_FMT_BF16 : a.table[e].fmt; };
+    const int R = (nE + kThreads - 1) / kThreads; // experts per thread, consecutive
+    uint32_t mine[3] = {0, 0, 0}, local = 0;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            int slot = mb + 16 * mt + r;
-            slot = slot < sg.m ? slot : sg.m - 1;
-            arow[mt] = a.h + (size_t)(sg.seg0 + slot) * a.fmax;
+    for (int i = 0; i < 3; ++i) {
+        const int e = tid * R + i;
+        if (i < R && e < nE) {
+            const int m = tokens_of(e);
+            seg_tokens[e] = m;
+            seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
+            if (m > 0) mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * (fmt_of(e) == DX_FMT_INT4G ? kLoUnits : kHiUnits);
+            local += mine[i];
         }
-        f32x4 acc[2][2];
-        const bool two = sg.m - mb > 16;
-        if (two) {
-            if (int4) skinny_gemm<2, 2, LK, true>(wrow, srow, arow, K, a.group, q, acc);
-            else skinny_gemm<2, 2, LK, false>(wrow, srow, arow, K, a.group, q, acc);
-        } else {
-            const dx_bf16 *arow1[1] = {arow[0]};
-            f32x4 acc1[2][1];
-            if (int4) skinny_gemm<2, 1, LK, true>(wrow, srow, arow1, K, a.group, q, acc1);
-            else skinny_gemm<2, 1, LK, false>(wrow, srow, arow1, K, a.group, q, acc1);
-            acc[0][0] = acc1[0][0];
-            acc[1][0] = acc1[1][0];
+    }
+    uint32_t inc = local;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    if (tid == 0) e_first_s = nE;
+    __syncthreads();
+    uint32_t base = 0, U = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = wave_tot[w];
+        if (w < wave) base += t;
+        U += t;
+    }
+    uint32_t run = base + inc - local;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int e = tid * R + i;
+        if (i < R && e < nE) {
+            cum[e] = run;
+            run += mine[i];
         }
+    }
+    if (tid == 0) cum[nE] = U;
+    const uint32_t ub0 = (uint32_t)(((unsigned long long)U * blockIdx.x) / gridDim.x);
+    const uint32_t ub1 = (uint32_t)(((unsigned long long)U * (blockIdx.x + 1)) / gridDim.x);
+    __syncthreads();
+    // the expert whose unit range contains ub0 (experts without work have empty ranges)
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            if (mt == 1 && !two) break;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int slot = mb + 16 * mt + 4 * q + i;
-                if (slot < sg.m) {
-                    const int orow = sg.shared ? sg.seg0 + slot : a.perm[sg.seg0 + slot];
-                    a.o[(size_t)orow * a.d + n0] = acc[0][mt][i];
-                    a.o[(size_t)orow * a.d + n0 + 16] = acc[1][mt][i];
+    for (int i = 0; i < 3; ++i) {
+        const int e = tid * R + i;
+        if (i < R && e < nE && cum[e] <= ub0 && ub0 < cum[e + 1]) e_first_s = e;
+    }
+    __syncthreads();
+
+#ifdef DX_TRACE
+    const unsigned long long trace_t1 = wall_clock64();
+#endif
+    int pb = 0;
+    if (ub0 < ub1) {
+        for (int e = e_first_s; e < nE && cum[e] < ub1; ++e) {
+            const uint32_t ue = cum[e + 1] - cum[e];
+            if (ue == 0) continue;
+            expert_ctx ex;
+            ex.shared = e == a.E;
+            ex.m = seg_tokens[e];
+            ex.seg0 = seg_start[e];
+            const dx_handle hd = ex.shared ? *a.shared : a.table[e];
+            ex.int4 = hd.fmt == DX_FMT_INT4G;
+            const int fe = ex.shared ? a.shared_f : a.f;
+            ex.K = DOWN ? fe : a.d;
+            ex.G = ex.K / a.group;
+            ex.row_bytes = ex.int4 ? (size_t)ex.K / 2 : (size_t)ex.K * 2;
+            ex.w0 = (gbytes)(DOWN ? hd.w_down : hd.w_gate);
+            ex.w1 = (gbytes)(DOWN ? hd.w_down : hd.w_up);
+            ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
+            ex.s1 = (gbf16)(DOWN ? hd.s_down : hd.s_up);
+            const int spe = strips_of(e);
+            const uint32_t wgt = ex.int4 ? kLoUnits : kHiUnits;
+            const uint32_t lo = (ub0 > cum[e] ? ub0 : cum[e]) - cum[e];
+            const uint32_t hi = (ub1 < cum[e + 1] ? ub1 : cum[e + 1]) - cum[e];
+            // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi)
+            int i = (int)((lo + wgt - 1) / wgt);
+            const int i1 = (int)((hi + wgt - 1) / wgt);
+            while (i < i1) {
+                const int mb = i / spe;
+                const int iend = i1 < (mb + 1) * spe ? i1 : (mb + 1) * spe;
+                const int s_lo = i - mb * spe, s_hi = iend - mb * spe;
+                const bool two = ex.m - mb * 32 > 16;
+                if (ex.int4) {
+                    if (two) run_strips<LK, CPW, DOWN, true, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                    else run_strips<LK, CPW, DOWN, true, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                } else {
+                    if (two) run_strips<LK, CPW, DOWN, false, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                    else run_strips<LK, CPW, DOWN, false, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
                 }
+                i = iend;
             }
         }
     }
+#ifdef DX_TRACE
+    if (threadIdx.x == 0 && blockIdx.x < 8192) {
+        g_trace[DOWN ? 1 : 0][blockIdx.x][0] = trace_t0;
+        g_trace[DOWN ? 1 : 0][blockIdx.x][1] = wall_clock64();
+        g_trace[DOWN ? 1 : 0][blockIdx.x][2] = ub1 - ub0;
+        g_trace[DOWN ? 1 : 0][blockIdx.x][3] = trace_t1;
+    }
+#endif
 }
 
 // ---- combine: y[t] = sum_j w[t,j] * O[t*k+j] (+ O[T*k+t] of the shared expert) ----------
@@ -325,28 +560,79 @@ __global__ __launch_bounds__(256) void k_combine(dx_fwd_args a)
     *reinterpret_cast<uint2 *>(a.y + (size_t)t * a.d + c) = out;
 }
 
-template <int LK>
-hipError_t launch_all(const dx_fwd_args &a, hipStream_t s)
+// Chunks per wavefront for a contraction of nc chunks: the fast path needs nc = WPS * CPW with
+// WPS <= 8 wavefronts; prefer the split that leaves the fewest of the 8 wavefronts without a K-part.
+struct split_choice {
+    int cpw;
+    bool fast;
+};
+
+split_choice pick_split(int nc_a, int nc_b)
 {
-    const int ny = a.E + (a.shared ? 1 : 0);
-    const int fe = a.shared && a.shared_f > a.f ? a.shared_f : a.f;
-    const dim3 block(64 * kTilesPerBlock);
-    const dim3 g1((fe / 16 + kTilesPerBlock - 1) / kTilesPerBlock, ny);
-    hipLaunchKernelGGL(k_gate_up<LK>, g1, block, 0, s, a);
-    const dim3 g2((a.d / 32 + kTilesPerBlock - 1) / kTilesPerBlock, ny);
-    hipLaunchKernelGGL(k_down<LK>, g2, block, 0, s, a);
+    int best = 0, best_busy = -1;
+    for (int cpw = 1; cpw <= 2; ++cpw) {
+        bool ok = true;
+        int busy = kWaves;
+        for (int nc : {nc_a, nc_b}) {
+            if (nc % cpw || nc / cpw > kWaves) ok = false;
+            else {
+                const int wps = nc / cpw;
+                busy = busy < (kWaves / wps) * wps ? busy : (kWaves / wps) * wps;
+            }
+        }
+        if (ok && busy >= best_busy) { // ties go to the larger cpw: more bytes in flight per wavefront
+            best = cpw;
+            best_busy = busy;
+        }
+    }
+    if (best) return {best, true};
+    return {2, false};
+}
+
+template <int LK, bool DOWN>
+void launch_stream(const dx_fwd_args &a, split_choice c, dim3 grid, hipStream_t s)
+{
+    const dim3 block(kThreads);
+    if (c.fast) {
+        if (c.cpw == 2) hipLaunchKernelGGL((k_stream<LK, 2, DOWN, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_stream<LK, 1, DOWN, true>), grid, block, 0, s, a);
+    } else {
+        hipLaunchKernelGGL((k_stream<LK, 2, DOWN, false>), grid, block, 0, s, a);
+    }
+}
+
+template <int LK>
+hipError_t launch_all(const dx_fwd_args &a, int n_blocks, hipStream_t s, hipEvent_t *marks)
+{
+    constexpr int CHUNK = 4 * LK;
+    const dim3 grid(n_blocks);
+    if (marks) (void)hipEventRecord(marks[0], s);
+    launch_stream<LK, false>(a, pick_split(a.d / CHUNK, a.d / CHUNK), grid, s);
+    if (marks) (void)hipEventRecord(marks[1], s);
+    launch_stream<LK, true>(a, pick_split(a.f / CHUNK, (a.shared ? a.shared_f : a.f) / CHUNK), grid, s);
+    if (marks) (void)hipEventRecord(marks[2], s);
     const dim3 g3((a.d / 4 + 255) / 256, a.T);
     hipLaunchKernelGGL(k_combine, g3, dim3(256), 0, s, a);
+    if (marks) (void)hipEventRecord(marks[3], s);
     return hipGetLastError();
 }
 
 } // namespace
 
-hipError_t dxk_moe_forward(const dx_fwd_args &a, hipStream_t s)
+#ifdef DX_TRACE
+extern "C" int dx_debug_read_trace(void *dst, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
+
+hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, hipEvent_t *marks)
 {
     if (a.T == 0) return hipSuccess;
+    static const int bpc = getenv("DX_BPC") ? atoi(getenv("DX_BPC")) : 1;
+    const int n_blocks = n_cu * (bpc > 0 ? bpc : 1);
     // K-chunk = min(group, 128) so that a chunk never crosses a quantization group
-    if (a.group >= 128) return launch_all<32>(a, s);
-    if (a.group == 64) return launch_all<16>(a, s);
-    return launch_all<8>(a, s);
+    if (a.group >= 128) return launch_all<32>(a, n_blocks, s, marks);
+    if (a.group == 64) return launch_all<16>(a, n_blocks, s, marks);
+    return launch_all<8>(a, n_blocks, s, marks);
 }
