@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-precision MoE layer on one MI355X.
 
-A step is one pass of the whole hot path over one batch: dx_route ->
-dx_hotness_update -> dx_moe_forward for one 30B-shaped MoE layer at decode
-batch 32 (workload C2).  Steps rotate over `--layers` independent layers'
+A step is one pass of the whole hot path over one batch: dx_route (top-k,
+routing weights, permutation, and the hotness counters, which the context is
+configured to update inside the routing kernel) -> dx_moe_forward for one
+30B-shaped MoE layer at decode batch 32 (workload C2).  Steps rotate over `--layers` independent layers'
 weights (default 48, the model's depth, ~26 GB) so that no step finds its
 expert weights in the 256 MB last-level cache.  Each layer's bf16 resident set
 is what the budget rule selects from a warm-up window of router traces.
@@ -66,7 +67,8 @@ def main():
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         ctx = B.Context(L=L, E=E, d=d, f=f, top_k=k, group=wl.group, max_tokens=T,
-                        window_steps=args.window, budget_bytes=L * C2_LAYER_BUDGET, stream=stream.cuda_stream)
+                        window_steps=args.window, budget_bytes=L * C2_LAYER_BUDGET,
+                        route_updates_hotness=True, stream=stream.cuda_stream)
         rb = LY.RoutingBuffers(T, E, k)
         # inputs of every layer: the measured batch plus the warm-up window's router traces
         xs, lgs = [], []
@@ -79,8 +81,7 @@ def main():
             for layer in range(L):
                 xw = W.activations(wl, seed, layer, step)
                 lg = torch.from_numpy(W.router_logits(wl, xw, wr[layer], seed, layer)).cuda()
-                rb.route(ctx, layer, lg)
-                ctx.dx_hotness_update(layer, rb.counts)
+                rb.route(ctx, layer, lg)          # also counts the selections (route_updates_hotness)
         ctx.dx_window_end()
         resident = [ctx.dx_select_resident(layer, C2_LAYER_BUDGET) for layer in range(L)]
         assert all(len(r) == wl.n_hi for r in resident), [len(r) for r in resident]
@@ -93,7 +94,7 @@ def main():
         y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
         stream.synchronize()
 
-        # argument tuples resolved once: the timed loop is three C calls per step
+        # argument tuples resolved once: the timed loop is two C calls per step
         lib, h = ctx.lib, ctx.h
         p_ids, p_w, p_counts, p_off, p_perm = (t.data_ptr() for t in (rb.ids, rb.w, rb.counts, rb.offsets, rb.perm))
         route_args = [(h, layer, lgs[layer].data_ptr(), T, p_ids, p_w, p_counts, p_off, p_perm) for layer in range(L)]
@@ -102,8 +103,7 @@ def main():
 
         def step_fn(i):
             layer = i % L
-            if lib.dx_route(*route_args[layer]) or lib.dx_hotness_update(h, layer, p_counts) \
-                    or lib.dx_moe_forward(*fwd_args[layer]):
+            if lib.dx_route(*route_args[layer]) or lib.dx_moe_forward(*fwd_args[layer]):
                 raise RuntimeError(lib.dx_last_error(h).decode())
 
         for i in range(args.warmup):
@@ -157,7 +157,7 @@ def main():
         "config": {"workload": f"{wl.name}: 30B-A3B-shaped MoE layer, decode T={T}, d={d}, f={f}, E={E}, top-{k}, "
                                f"Zipf(s={wl.zipf_s}) routing, {wl.n_hi} bf16 + {E - wl.n_hi} int4-g{wl.group} experts "
                                f"per layer, rotating over {L} layers' weights",
-                   "step": "dx_route + dx_hotness_update + dx_moe_forward of one layer"},
+                   "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
                       "combine": prof["combine_ms"] * 1e3 / prof["calls"]},
         "roofline": {"bound": "hbm", "kernel": "k_gate_up", "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -63,6 +63,9 @@ typedef struct {
     int32_t max_tokens;   /* largest T a call will pass; sizes the scratch buffers */
     int32_t window_steps; /* informational: forward passes per hotness window */
     uint32_t alpha_q16;   /* EMA factor alpha * 65536, 0 <= alpha_q16 < 65536 (Sec. 3.5) */
+    int32_t route_updates_hotness; /* != 0: dx_route itself adds `counts` to the layer's window counters
+                                      (the router trace tap of Sec. 4); do not also call dx_hotness_update */
+    int32_t reserved0;
     uint64_t budget_bytes;    /* expert-weight budget of the whole stack, steady state */
     uint64_t transient_bytes; /* extra bytes in-flight transitions may hold on top of it */
 } dx_config;
@@ -114,7 +117,8 @@ const char *dx_status_str(dx_status s);
  *   counts   int32 [E]    pairs routed to each expert
  *   offsets  int32 [E+1]  exclusive prefix sum of counts
  *   perm     int32 [T*k]  pair indices p = t*k + j grouped by expert, increasing inside a segment
- * 0 <= T <= max_tokens.  Logits must be finite. */
+ * 0 <= T <= max_tokens.  Logits must be finite.  With route_updates_hotness
+ * set in the configuration the call also performs dx_hotness_update(counts). */
 dx_status dx_route(dx_ctx *ctx, int layer, const float *logits, int T,
                    int32_t *topk_ids, float *topk_w,
                    int32_t *counts, int32_t *offsets, int32_t *perm);

@@ -34,6 +34,7 @@ class DxConfig(C.Structure):
     _fields_ = [("L", C.c_int32), ("E", C.c_int32), ("d", C.c_int32), ("f", C.c_int32),
                 ("top_k", C.c_int32), ("group", C.c_int32), ("shared_f", C.c_int32),
                 ("max_tokens", C.c_int32), ("window_steps", C.c_int32), ("alpha_q16", C.c_uint32),
+                ("route_updates_hotness", C.c_int32), ("reserved0", C.c_int32),
                 ("budget_bytes", C.c_uint64), ("transient_bytes", C.c_uint64)]
 
 
@@ -158,11 +159,11 @@ class Context:
     """Owns one dx_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, *, L, E, d, f, top_k, group, max_tokens, shared_f=0, window_steps=256,
-                 alpha_q16=0, budget_bytes=0, transient_bytes=0, stream=None):
+                 alpha_q16=0, budget_bytes=0, transient_bytes=0, route_updates_hotness=False, stream=None):
         import torch
         self.lib = load()
         self.cfg = DxConfig(L, E, d, f, top_k, group, shared_f, max_tokens, window_steps, alpha_q16,
-                            budget_bytes, transient_bytes)
+                            1 if route_updates_hotness else 0, 0, budget_bytes, transient_bytes)
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
         self.stream = stream

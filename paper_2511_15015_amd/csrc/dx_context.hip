@@ -267,8 +267,9 @@ extern "C" dx_status dx_route(dx_ctx *c, int layer, const float *logits, int T, 
     if (T < 0 || T > c->cfg.max_tokens) DX_FAIL(c, DX_ERR_INVALID, "dx_route: T=%d outside [0,%d]", T, c->cfg.max_tokens);
     if (!counts || !offsets || (T > 0 && (!logits || !ids || !w || !perm)))
         DX_FAIL(c, DX_ERR_INVALID, "dx_route: null pointer");
+    unsigned long long *hot = c->cfg.route_updates_hotness ? c->d_counters + (size_t)layer * c->cfg.E : nullptr;
     DX_HIP(c, dxk_route(logits, T, c->cfg.E, c->cfg.top_k, ids, w, counts, offsets, perm, c->d_mask, c->d_chunk_base,
-                        c->compute));
+                        hot, c->compute));
     return DX_OK;
 }
 

@@ -20,11 +20,6 @@ constexpr int kChunk = 64;      // tokens per chunk = bits per mask word
 constexpr int kRouteThreads = 1024;
 constexpr int kWaves = kRouteThreads / 64;
 
-__device__ __forceinline__ bool better(float av, int ai, float bv, int bi)
-{
-    return av > bv || (av == bv && ai < bi);
-}
-
 // exclusive scan of one int per thread across a 1024-thread block
 __device__ int block_exclusive_scan(int v, int *lds_wave_tot /*[kWaves]*/, int *total)
 {
@@ -49,12 +44,44 @@ __device__ int block_exclusive_scan(int v, int *lds_wave_tot /*[kWaves]*/, int *
     return base + inc - v;
 }
 
+// Wave-wide max / sum in six DPP steps (no LDS round trips).  Lane 63 ends up with the reduction over
+// all 64 lanes and is read back as a scalar.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ float dpp_move(float old, float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL, ROW_MASK, 0xF, BOUND));
+}
+
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = fmaxf(x, dpp_move<0xB1, 0xF, false>(x, x));  // quad_perm [1,0,3,2]
+    x = fmaxf(x, dpp_move<0x4E, 0xF, false>(x, x));  // quad_perm [2,3,0,1]
+    x = fmaxf(x, dpp_move<0x141, 0xF, false>(x, x)); // row_half_mirror
+    x = fmaxf(x, dpp_move<0x140, 0xF, false>(x, x)); // row_mirror: every 16-lane row is uniform now
+    x = fmaxf(x, dpp_move<0x142, 0xA, false>(x, x)); // row_bcast:15 into rows 1 and 3
+    x = fmaxf(x, dpp_move<0x143, 0xC, false>(x, x)); // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+    // inclusive scan inside each row by shifts (lanes shifted in from outside the row contribute 0) ...
+    x += dpp_move<0x111, 0xF, true>(0.f, x); // row_shr:1
+    x += dpp_move<0x112, 0xF, true>(0.f, x); // row_shr:2
+    x += dpp_move<0x114, 0xF, true>(0.f, x); // row_shr:4
+    x += dpp_move<0x118, 0xF, true>(0.f, x); // row_shr:8 -> lane 15 of every row holds the row's sum
+    // ... then the row sums travel to lane 63
+    x += dpp_move<0x142, 0xA, false>(0.f, x); // row_bcast:15 into rows 1 and 3
+    x += dpp_move<0x143, 0xC, false>(0.f, x); // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
 // One chunk of 64 tokens per block.  NV = logits held per lane (E <= 64*NV).
 template <int NV>
 __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
-    const float *__restrict__ logits, int T, int E, int k, int32_t *__restrict__ ids,
-    float *__restrict__ w, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
-    int32_t *__restrict__ perm, unsigned long long *__restrict__ mask_out, int fused)
+    const float *__restrict__ logits, int T, int E, int k, int32_t *__restrict__ ids, float *__restrict__ w,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    unsigned long long *__restrict__ mask_out, unsigned long long *__restrict__ hotness, int fused)
 {
     extern __shared__ unsigned long long lds_mask[]; // [E], then int ids [64*k], then wave totals
     int *lds_ids = reinterpret_cast<int *>(lds_mask + E);
@@ -72,34 +99,36 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
         float v[NV];
 #pragma unroll
         for (int s = 0; s < NV; ++s) {
-            int e = lane + 64 * s;
+            const int e = lane + 64 * s;
             v[s] = e < E ? row[e] : -INFINITY;
         }
         int my_id = 0;
-        float my_logit = 0.f;
+        float my_logit = -INFINITY;
         for (int j = 0; j < k; ++j) {
             float bv = v[0];
-            int bi = lane;
 #pragma unroll
-            for (int s = 1; s < NV; ++s) {
-                if (v[s] > bv) { bv = v[s]; bi = lane + 64 * s; } // strict: lower index wins
-            }
+            for (int s = 1; s < NV; ++s) bv = fmaxf(bv, v[s]);
+            const float top = wave_max(bv);
+            // the lowest expert index holding `top`: element e = lane + 64*s, so scan s upward and take
+            // the lowest lane of the first non-empty ballot (taken entries are -inf and never match)
+            int idx = 0;
+            bool found = false;
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                float ov = __shfl_xor(bv, off, 64);
-                int oi = __shfl_xor(bi, off, 64);
-                if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            for (int s = 0; s < NV; ++s) {
+                const unsigned long long bal = __ballot(v[s] == top);
+                if (!found && bal) {
+                    idx = 64 * s + __builtin_ctzll(bal);
+                    found = true;
+                }
             }
 #pragma unroll
             for (int s = 0; s < NV; ++s)
-                if (bi == lane + 64 * s) v[s] = -INFINITY;
-            if (lane == j) { my_id = bi; my_logit = bv; }
+                if (idx == lane + 64 * s) v[s] = -INFINITY;
+            if (lane == j) { my_id = idx; my_logit = top; }
         }
-        const float top = __shfl(my_logit, 0, 64);
-        float ex = lane < k ? expf(my_logit - top) : 0.f;
-        float sum = ex;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        const float top0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_logit), 0));
+        const float ex = lane < k ? expf(my_logit - top0) : 0.f;
+        const float sum = wave_sum(ex);
         if (lane < k) {
             ids[(size_t)t * k + lane] = my_id;
             w[(size_t)t * k + lane] = ex / sum;
@@ -121,6 +150,7 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
     if (e < E) {
         counts[e] = c;
         offsets[e] = off;
+        if (hotness) hotness[e] += (unsigned long long)c;
         lds_ids[kChunk * k + kWaves + e] = off; // offsets kept in LDS after the wave totals
     }
     if (e == 0) offsets[E] = total;
@@ -138,7 +168,7 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
 // counts/offsets and per-chunk bases from the chunk masks (one block)
 __global__ __launch_bounds__(kRouteThreads) void k_route_scan(
     const unsigned long long *__restrict__ mask, int n_chunks, int E, int32_t *__restrict__ chunk_base,
-    int32_t *__restrict__ counts, int32_t *__restrict__ offsets)
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, unsigned long long *__restrict__ hotness)
 {
     __shared__ int lds_tot[kWaves];
     const int e = threadIdx.x;
@@ -154,6 +184,7 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_scan(
     if (e < E) {
         counts[e] = run;
         offsets[e] = off;
+        if (hotness) hotness[e] += (unsigned long long)run;
     }
     if (e == 0) offsets[E] = total;
 }
@@ -190,12 +221,13 @@ __global__ void k_store_handle(dx_handle *slot, dx_handle h)
 
 template <int NV>
 hipError_t launch_topk(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
-                       int32_t *offsets, int32_t *perm, unsigned long long *mask, int n_chunks, hipStream_t s)
+                       int32_t *offsets, int32_t *perm, unsigned long long *mask, unsigned long long *hotness,
+                       int n_chunks, hipStream_t s)
 {
     const int fused = n_chunks == 1;
     size_t lds = (size_t)E * 8 + (size_t)(kChunk * k + kWaves + E) * 4;
     hipLaunchKernelGGL(k_route_topk<NV>, dim3(n_chunks), dim3(kRouteThreads), lds, s, logits, T, E, k, ids, w,
-                       counts, offsets, perm, mask, fused);
+                       counts, offsets, perm, mask, hotness, fused);
     return hipGetLastError();
 }
 
@@ -203,19 +235,19 @@ hipError_t launch_topk(const float *logits, int T, int E, int k, int32_t *ids, f
 
 hipError_t dxk_route(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
                      int32_t *offsets, int32_t *perm, unsigned long long *mask, int32_t *chunk_base,
-                     hipStream_t s)
+                     unsigned long long *hotness, hipStream_t s)
 {
     // T == 0 still runs one (empty) chunk so that counts and offsets are written.
     const int n_chunks = T > 0 ? (T + kChunk - 1) / kChunk : 1;
     hipError_t e;
-    if (E <= 64) e = launch_topk<1>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
-    else if (E <= 128) e = launch_topk<2>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
-    else if (E <= 256) e = launch_topk<4>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
-    else if (E <= 512) e = launch_topk<8>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
-    else e = launch_topk<16>(logits, T, E, k, ids, w, counts, offsets, perm, mask, n_chunks, s);
+    if (E <= 64) e = launch_topk<1>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (E <= 128) e = launch_topk<2>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (E <= 256) e = launch_topk<4>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (E <= 512) e = launch_topk<8>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else e = launch_topk<16>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
     if (e != hipSuccess || n_chunks == 1) return e;
     hipLaunchKernelGGL(k_route_scan, dim3(1), dim3(kRouteThreads), 0, s, mask, n_chunks, E, chunk_base, counts,
-                       offsets);
+                       offsets, hotness);
     const int P = T * k;
     hipLaunchKernelGGL(k_route_place, dim3((P + 255) / 256), dim3(256), 0, s, ids, P, E, k, mask, chunk_base,
                        offsets, perm);

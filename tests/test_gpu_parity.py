@@ -350,3 +350,21 @@ def test_hotness_window_and_selection_match_oracle(B, LY, dxo):
         ctx.dx_select_resident(0, wl.E * b_lo - 1)
     assert ei.value.status == B.DX_ERR_BUDGET
     ctx.close()
+
+
+def test_route_can_update_hotness_itself(B, LY, dxo):
+    wl = WORKLOADS["C2"]
+    for T in (wl.T, 200):                       # single-chunk and multi-chunk routing paths
+        ctx = B.Context(L=2, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=T,
+                        route_updates_hotness=True)
+        rb = LY.RoutingBuffers(T, wl.E, wl.k)
+        c = np.zeros((2, wl.E), np.int64)
+        g = np.random.default_rng(T)
+        for step in range(5):
+            for layer in range(2):
+                lg = g.standard_normal((T, wl.E)).astype(np.float32)
+                rb.route(ctx, layer, torch.from_numpy(lg).cuda())
+                _, _, counts, _, _ = dxo.route(lg, wl.k)
+                dxo.hotness_update(c[layer], counts)
+        assert np.array_equal(ctx.dx_get_counters(), c)
+        ctx.close()

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_struct_sizes_match_the_header(B):
     assert C.sizeof(B.DxHandle) == 64
-    assert C.sizeof(B.DxConfig) == 56
+    assert C.sizeof(B.DxConfig) == 64
     assert C.sizeof(B.DxStats) == 80
 
 
