@@ -95,8 +95,11 @@ constexpr int kWaves = 8;             // wavefronts per block
 constexpr int kThreads = 64 * kWaves; // 512
 constexpr int kMaxExperts = 1024 + 1; // routed + shared
 // Relative cost of a bf16 / int4 strip pair in the partition.  An int4 pair is a quarter of the bytes
-// but carries the same per-step work (barrier, reduction), so it is weighed by measured time, not bytes.
-constexpr int kHiUnits = 8, kLoUnits = 3;
+// but carries the same per-step work (barrier, reduction), so it is weighed by measured time, not
+// bytes: 3/8 of a bf16 pair when K is long (gate/up), 5/8 when it is short (down).
+constexpr int kHiUnits = 8;
+template <bool DOWN>
+constexpr int kLoUnits = DOWN ? 5 : 3;
 
 #ifdef DX_TRACE
 // Debug build only: per-block start/end time stamps (100 MHz wall clock).
@@ -442,7 +445,7 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             const int m = tokens_of(e);
             seg_tokens[e] = m;
             seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
-            if (m > 0) mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * (fmt_of(e) == DX_FMT_INT4G ? kLoUnits : kHiUnits);
+            if (m > 0) mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * (fmt_of(e) == DX_FMT_INT4G ? kLoUnits<DOWN> : kHiUnits);
             local += mine[i];
         }
     }
@@ -506,7 +509,7 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
             ex.s1 = (gbf16)(DOWN ? hd.s_down : hd.s_up);
             const int spe = strips_of(e);
-            const uint32_t wgt = ex.int4 ? kLoUnits : kHiUnits;
+            const uint32_t wgt = ex.int4 ? kLoUnits<DOWN> : kHiUnits;
             const uint32_t lo = (ub0 > cum[e] ? ub0 : cum[e]) - cum[e];
             const uint32_t hi = (ub1 < cum[e + 1] ? ub1 : cum[e + 1]) - cum[e];
             // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi)
