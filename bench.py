@@ -135,7 +135,7 @@ def main():
         achieved = alg_per_launch / (gate_up_us * 1e-6) / 1e9
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"k_gate_up_{args.workload}_decode_pmc.txt")
+    tpath = os.path.join(ROOT, "profiles", f"k_stream_gate_up_{args.workload}_decode_pmc.txt")
     if os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -160,7 +160,7 @@ def main():
                    "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
                       "combine": prof["combine_ms"] * 1e3 / prof["calls"]},
-        "roofline": {"bound": "hbm", "kernel": "k_gate_up", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "k_stream<gate/up>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us},
     }
