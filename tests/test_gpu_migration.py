@@ -1,0 +1,260 @@
+"""GPU tests of the residency machinery: weight pools, budget tracker,
+promotion from pinned host memory and on-device demotion on the migration
+stream, and publication between forward passes (Sec. 3.2-3.4 of the paper).
+Every forward result is checked against the CPU oracle evaluated with the
+format map the library reports for that step."""
+import ctypes as C
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_15015_amd import workloads as W
+from paper_2511_15015_amd.workloads import WORKLOADS, bf16_bits_to_f32
+
+pytestmark = pytest.mark.gpu
+REL_L2_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2511_15015_amd import binding
+    binding.load()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def LY():
+    from paper_2511_15015_amd import layer
+    return layer
+
+
+def _hip():
+    lib = C.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
+    lib.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+    return lib
+
+
+def read_device(ptr, nbytes):
+    """Copy nbytes from a raw device pointer into a numpy uint8 array."""
+    out = np.empty(nbytes, np.uint8)
+    rc = _hip().hipMemcpy(out.ctypes.data, C.c_void_p(ptr), nbytes, 2)  # device to host
+    assert rc == 0
+    return out
+
+
+class Stack:
+    """L small layers set up through the pools, mirrored on the oracle side."""
+
+    def __init__(self, B, LY, dxo, L=2, n_hi=2, spare_hi=1, spare_lo=1, seed=7):
+        wl = WORKLOADS["C1"]
+        self.B, self.LY, self.dxo, self.wl, self.L = B, LY, dxo, wl, L
+        self.b_hi = dxo.expert_bytes(wl.d, wl.f, wl.group, 0)
+        self.b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, 1)
+        self.layer_budget = n_hi * self.b_hi + (wl.E - n_hi) * self.b_lo
+        self.budget = L * self.layer_budget
+        self.transient = spare_hi * self.b_hi + spare_lo * self.b_lo
+        self.ctx = B.Context(L=L, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T,
+                             budget_bytes=self.budget, transient_bytes=self.transient)
+        self.ctx.dx_pools_create(L * n_hi + spare_hi, L * (wl.E - n_hi) + spare_lo)
+        self.masters = [W.layer_masters(wl, seed, l) for l in range(L)]
+        # pinned host copies (what promotions read) and the oracle's two versions of every expert
+        self.pinned = [[tuple(torch.from_numpy(m[e].view(np.int16)).pin_memory() for m in self.masters[l])
+                        for e in range(wl.E)] for l in range(L)]
+        self.hi = [[dxo.ExpertVersion.bf16(*(m[e] for m in self.masters[l])) for e in range(wl.E)] for l in range(L)]
+        self.lo = [[dxo.ExpertVersion.int4_from_master(*(m[e] for m in self.masters[l]), wl.group)
+                    for e in range(wl.E)] for l in range(L)]
+        self.rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+        self.y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+
+    def install(self, resident):
+        for l in range(self.L):
+            for e in range(self.wl.E):
+                fmt = self.B.DX_FMT_BF16 if e in resident[l] else self.B.DX_FMT_INT4G
+                if (l + e) % 2:      # alternate host and device sources
+                    src = [self.LY.bits_to_device(m[e]) for m in self.masters[l]]
+                    self.ctx.dx_expert_install(l, e, fmt, *src, src_on_device=True)
+                else:
+                    self.ctx.dx_expert_install(l, e, fmt, *self.pinned[l][e], src_on_device=False)
+
+    def forward_bits(self, layer, step):
+        x, lg = W.layer_inputs(self.wl, 11, layer, step)
+        self.rb.route(self.ctx, layer, torch.from_numpy(lg).cuda())
+        self.rb.forward(self.ctx, layer, self.LY.bits_to_device(x), self.y)
+        torch.cuda.synchronize()
+        return self.LY.device_to_bits(self.y).copy(), x, lg
+
+    def check(self, layer, step):
+        """Forward on the GPU with the published map; oracle with the map the library reports."""
+        fm = self.ctx.dx_get_formats()[layer]
+        y_bits, x, lg = self.forward_bits(layer, step)
+        ids, w, *_ = self.dxo.route(lg, self.wl.k)
+        versions = [self.hi[layer][e] if fm[e] == self.B.DX_FMT_BF16 else self.lo[layer][e] for e in range(self.wl.E)]
+        y_ref = self.dxo.moe_forward(versions, self.wl.d, self.wl.f, self.wl.group, x, ids, w)
+        y = bf16_bits_to_f32(y_bits).astype(np.float64)
+        err = float(np.linalg.norm(y - y_ref) / np.linalg.norm(y_ref))
+        assert err <= REL_L2_TOL, (layer, step, err)
+        return y_bits
+
+
+def test_install_promote_demote_publish(B, LY, dxo):
+    st = Stack(B, LY, dxo)
+    wl, ctx = st.wl, st.ctx
+    resident = [{1, 6}, {0, 3}]
+    st.install(resident)
+    fm = ctx.dx_get_formats()
+    for l in range(2):
+        assert set(np.flatnonzero(fm[l] == B.DX_FMT_BF16)) == resident[l]
+    stats = ctx.dx_get_stats()
+    assert stats["reserved_bytes"] == st.budget                      # exactly the steady-state footprint
+    for l in range(2):
+        st.check(l, 0)
+
+    # int4 versions written by installation are the oracle's quantization of the masters, bit for bit
+    h = ctx.dx_get_handle(0, 2)
+    assert h.fmt == B.DX_FMT_INT4G
+    lo = st.lo[0][2].arrays
+    assert np.array_equal(read_device(h.w_gate, lo[0].nbytes), lo[0].ravel())
+    assert np.array_equal(read_device(h.w_down, lo[2].nbytes), lo[2].ravel())
+    assert np.array_equal(read_device(h.s_up, lo[4].nbytes).view(np.uint16), lo[4].ravel())
+
+    # admission control: the layer already holds its 2 high-precision experts
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_promote_async(0, 4, *st.pinned[0][4])
+    assert ei.value.status == B.DX_ERR_BUDGET
+    assert ctx.dx_get_states()[0, 4] == B.DX_STATE_RESIDENT_LO
+    assert ctx.dx_get_stats()["deferred"] == 1
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_demote_async(0, 4)                                    # not a bf16 resident
+    assert ei.value.status == B.DX_ERR_BUSY
+
+    # candidates = set differences against the current resident set
+    pro, dem = ctx.dx_plan_transitions(0, np.array([6, 4], np.int32))
+    cur = np.zeros(wl.E, np.uint8); cur[[1, 6]] = 1
+    new = np.zeros(wl.E, np.uint8); new[[6, 4]] = 1
+    pro_r, dem_r = dxo.transition_sets(cur, new)
+    assert pro.tolist() == pro_r.tolist() == [4] and dem.tolist() == dem_r.tolist() == [1]
+
+    # demotion in flight: the handle keeps resolving to the bf16 version until it is published
+    before = st.check(0, 1)
+    ctx.dx_demote_async(0, 1)
+    assert ctx.dx_get_states()[0, 1] == B.DX_STATE_DEMOTING
+    assert ctx.dx_get_formats()[0, 1] == B.DX_FMT_BF16
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_demote_async(0, 1)
+    assert ei.value.status == B.DX_ERR_BUSY
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_swap_handle(0, 1, ctx.dx_get_handle(0, 2))
+    assert ei.value.status == B.DX_ERR_BUSY
+    again, _, _ = st.forward_bits(0, 1)
+    assert np.array_equal(before, again)                             # bit for bit the old mapping
+    assert ctx.dx_migrate_poll(wait=True) == 1
+    assert ctx.dx_get_states()[0, 1] == B.DX_STATE_RESIDENT_LO
+    assert ctx.dx_get_formats()[0, 1] == B.DX_FMT_INT4G
+    after = st.check(0, 1)
+    assert not np.array_equal(before, after)
+    h = ctx.dx_get_handle(0, 1)                                      # demoted content = quantize(master)
+    lo = st.lo[0][1].arrays
+    for ptr, ref in ((h.w_gate, lo[0]), (h.w_up, lo[1]), (h.w_down, lo[2]), (h.s_gate, lo[3]), (h.s_down, lo[5])):
+        assert np.array_equal(read_device(ptr, ref.nbytes), ref.ravel().view(np.uint8))
+
+    # promotion in flight, then published
+    ctx.dx_promote_async(0, 4, *st.pinned[0][4])
+    assert ctx.dx_get_states()[0, 4] == B.DX_STATE_PROMOTING
+    assert ctx.dx_get_formats()[0, 4] == B.DX_FMT_INT4G
+    mid, _, _ = st.forward_bits(0, 1)
+    assert np.array_equal(mid, after)
+    assert ctx.dx_migrate_poll(wait=True) == 1
+    assert ctx.dx_get_states()[0, 4] == B.DX_STATE_RESIDENT_HI
+    st.check(0, 1)
+    h = ctx.dx_get_handle(0, 4)
+    assert np.array_equal(read_device(h.w_up, st.masters[0][1][4].nbytes).view(np.uint16), st.masters[0][1][4].ravel())
+
+    stats = ctx.dx_get_stats()
+    assert stats["promotions_published"] == 1 and stats["demotions_published"] == 1
+    assert stats["h2d_bytes"] == st.b_hi and stats["quantize_read_bytes"] == st.b_hi
+    assert stats["quantize_write_bytes"] == st.b_lo
+    assert stats["reserved_bytes"] == st.budget                      # back to the steady-state footprint
+    assert stats["peak_reserved_bytes"] <= st.budget + st.transient  # never above budget + transient
+    ctx.close()
+
+
+def test_hot_set_churn_every_step_matches_oracle(B, LY, dxo):
+    """Windows of routed steps; at each window end the resident set follows the window's counts
+    (select -> plan -> demote, poll, promote, poll); every step is checked with the reported map."""
+    st = Stack(B, LY, dxo, L=2, n_hi=2, spare_lo=2)
+    wl, ctx = st.wl, st.ctx
+    st.install([{0, 1}, {0, 1}])
+    g = np.random.default_rng(3)
+    step = 0
+    cycles = {}
+    for window in range(4):
+        for _ in range(3):
+            for l in range(2):
+                st.check(l, step)
+                ctx.dx_hotness_update(l, st.rb.counts)
+            step += 1
+        S = ctx.dx_window_end()
+        for l in range(2):
+            target = ctx.dx_select_resident(l, st.layer_budget)
+            assert np.array_equal(target, dxo.select_topn(S[l], 2))
+            pro, dem = ctx.dx_plan_transitions(l, target)
+            assert len(pro) == len(dem)
+            for e in dem:
+                ctx.dx_demote_async(l, int(e))
+            # promotions wait for capacity: the demotions must be published first
+            for e in pro:
+                with pytest.raises(B.DxError):
+                    ctx.dx_promote_async(l, int(e), *st.pinned[l][int(e)])
+                break
+            assert ctx.dx_migrate_poll(wait=True) == len(dem)
+            for e in pro:
+                ctx.dx_promote_async(l, int(e), *st.pinned[l][int(e)])
+                cycles[(l, int(e))] = cycles.get((l, int(e)), 0) + 1
+            # a forward pass while promotions are in flight still sees complete versions only
+            st.check(l, step)
+            ctx.dx_migrate_poll(wait=True)
+            fm = ctx.dx_get_formats()[l]
+            assert set(np.flatnonzero(fm == B.DX_FMT_BF16)) == set(int(e) for e in target)
+            stats = ctx.dx_get_stats()
+            assert stats["reserved_bytes"] == st.budget
+            assert stats["peak_reserved_bytes"] <= st.budget + st.transient
+    assert ctx.dx_get_stats()["promotions_published"] == sum(cycles.values())
+    ctx.close()
+
+
+def test_pool_exhaustion_and_errors(B, LY, dxo):
+    wl = WORKLOADS["C1"]
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, 0), dxo.expert_bytes(wl.d, wl.f, wl.group, 1)
+    ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T)   # no byte budget
+    with pytest.raises(B.DxError):
+        ctx.dx_expert_install(0, 0, B.DX_FMT_BF16, *[torch.zeros(8, device="cuda")] * 3)          # no pools yet
+    ctx.dx_pools_create(1, 2)
+    with pytest.raises(B.DxError):
+        ctx.dx_pools_create(1, 1)                                                                 # only once
+    m = W.layer_masters(wl, 1, 0)
+    dev = lambda e: [torch.from_numpy(a[e].view(np.int16)).cuda() for a in m]
+    ctx.dx_expert_install(0, 0, B.DX_FMT_BF16, *dev(0))
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_expert_install(0, 1, B.DX_FMT_BF16, *dev(1))
+    assert ei.value.status == B.DX_ERR_NOMEM                                                      # pool_hi is full
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_expert_install(0, 0, B.DX_FMT_INT4G, *dev(0))
+    assert ei.value.status == B.DX_ERR_BUSY                                                       # already installed
+    ctx.dx_expert_install(0, 1, B.DX_FMT_INT4G, *dev(1))
+    ctx.dx_expert_install(0, 2, B.DX_FMT_INT4G, *dev(2))
+    pinned = [torch.from_numpy(a[1].view(np.int16)).pin_memory() for a in m]
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_promote_async(0, 1, *pinned)
+    assert ei.value.status == B.DX_ERR_NOMEM                                                      # no free hi block
+    with pytest.raises(B.DxError) as ei:
+        ctx.dx_demote_async(0, 0)
+    assert ei.value.status == B.DX_ERR_NOMEM                                                      # no free lo block
+    assert ctx.dx_get_states()[0, :3].tolist() == [B.DX_STATE_RESIDENT_HI, B.DX_STATE_RESIDENT_LO, B.DX_STATE_RESIDENT_LO]
+    assert ctx.dx_migrate_poll() == 0
+    for bad in [(1, 0), (0, wl.E), (0, -1)]:
+        with pytest.raises(B.DxError) as ei:
+            ctx.dx_demote_async(*bad)
+        assert ei.value.status == B.DX_ERR_INVALID
+    ctx.close()
