@@ -25,17 +25,19 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 C2_LAYER_BUDGET = 535560192   # bytes: 32 bf16 + 96 int4 experts of the 30B shape
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=960)
-    ap.add_argument("--warmup", type=int, default=96)
-    ap.add_argument("--workload", default="C2", choices=["C2", "C3"])
-    ap.add_argument("--layers", type=int, default=48, help="independent weight sets to rotate over")
-    ap.add_argument("--window", type=int, default=64, help="routing-only warm-up steps per layer for hotness")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="C2", choices=["C2", "C3"],
+                    help="C2: decode T=32 (the headline metric); C3: the same layer in prefill, T=4096")
+    ap.add_argument("--layers", type=int, default=None, help="independent weight sets to rotate over")
+    ap.add_argument("--window", type=int, default=None, help="routing-only warm-up steps per layer for hotness")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
@@ -43,6 +45,11 @@ def parse():
 
 def main():
     args = parse()
+    defaults = {"C2": dict(steps=960, warmup=96, layers=48, window=64),
+                "C3": dict(steps=48, warmup=8, layers=4, window=2)}[args.workload]
+    for key, val in defaults.items():
+        if getattr(args, key) is None:
+            setattr(args, key, val)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one process, one MI355X); --gpus must be 1",
               file=sys.stderr)
@@ -118,31 +125,47 @@ def main():
 
         # second pass over the same steps with HIP events around each forward kernel
         ctx.dx_set_profiling(True)
-        alg_bytes = 0.0
+        alg_bytes = alg_flops = 0.0
         for i in range(args.steps):
             step_fn(i)
-            if i < L:   # algorithmic bytes of the gate/up launch for this layer's batch
+            if i < L:   # algorithmic work of the dominant (gate/up) launch for this layer's batch
                 counts = rb.counts.cpu().numpy()
                 act = counts > 0
                 hi = layers[i % L].is_hi
-                alg = (act & hi).sum() * (2 * b_hi // 3) + (act & ~hi).sum() * (2 * b_lo // 3) + T * d * 2
-                alg_bytes += float(alg)
+                # decode: activated experts' gate+up bytes in their stored format + the token rows
+                alg_bytes += float((act & hi).sum() * (2 * b_hi // 3) + (act & ~hi).sum() * (2 * b_lo // 3) + T * d * 2)
+                # prefill: the tiled kernel multiplies the segments above 32 tokens: 2 * m * d * 2f each
+                alg_flops += float(counts[counts > 32].sum()) * 2.0 * d * 2 * f
         prof = ctx.dx_get_profile()
         ctx.dx_set_profiling(False)
         n_alg = min(args.steps, L)
         alg_per_launch = alg_bytes / n_alg
+        flops_per_launch = alg_flops / n_alg
         gate_up_us = prof["gate_up_ms"] * 1e3 / prof["calls"]
-        achieved = alg_per_launch / (gate_up_us * 1e-6) / 1e9
 
+    decode = args.workload == "C2"
+    if decode:
+        achieved = alg_per_launch / (gate_up_us * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": "k_stream<gate/up>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us}
+    else:
+        achieved = flops_per_launch / (gate_up_us * 1e-6) / 1e12
+        roofline = {"bound": "mfma", "kernel": "k_tiled<gate/up>", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                    "algorithmic_flops_per_launch": flops_per_launch, "avg_launch_us": gate_up_us}
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"k_stream_gate_up_{args.workload}_decode_pmc.txt")
+    tpath = os.path.join(ROOT, "profiles", "k_stream_gate_up_C2_decode_pmc.txt" if decode
+                         else "k_tiled_gate_up_C3_prefill_pmc.txt")
     if os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
+    roofline["traffic"] = traffic
 
     out = {
-        "metric": "MoE-layer tokens/s (decode B=32) + achieved HBM GB/s",
+        "metric": "MoE-layer tokens/s (decode B=32) + achieved HBM GB/s" if decode
+                  else "MoE-layer tokens/s (prefill T=4096) + MFMA utilisation",
         "value": T / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -154,15 +177,13 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{wl.name}: 30B-A3B-shaped MoE layer, decode T={T}, d={d}, f={f}, E={E}, top-{k}, "
+        "config": {"workload": f"{wl.name}: 30B-A3B-shaped MoE layer, {'decode' if decode else 'prefill'} T={T}, d={d}, f={f}, E={E}, top-{k}, "
                                f"Zipf(s={wl.zipf_s}) routing, {wl.n_hi} bf16 + {E - wl.n_hi} int4-g{wl.group} experts "
                                f"per layer, rotating over {L} layers' weights",
                    "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
                       "combine": prof["combine_ms"] * 1e3 / prof["calls"]},
-        "roofline": {"bound": "hbm", "kernel": "k_stream<gate/up>", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us},
+        "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
@@ -173,26 +194,40 @@ def main():
         res0 = set(int(e) for e in resident[0])
         versions = [dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if e in res0
                     else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(E)]
-        batches = [W.layer_inputs(wl, seed, 0, step=i) for i in range(400)]
-        calls, y_ref0, ids0 = 0, None, None
-        t0 = time.perf_counter()
-        while calls < len(batches) and time.perf_counter() - t0 < 10.0:
-            xb, lgb = batches[calls]
-            ids, w, counts, offsets, perm = dxo.route(lgb, k)
-            y_ref = dxo.moe_forward(versions, d, f, wl.group, xb, ids, w)
-            if calls == 0:
-                y_ref0, ids0 = y_ref, ids
-            calls += 1
-        dt = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": calls * T / dt, "unit": "tokens/s", "cores": dxo.threads(), "kind": "oracle",
-                               "sample": f"{calls} full layer calls (layer 0's experts, all {T} tokens each, "
-                                         f"route + forward) in {dt:.1f} s"}
+        if decode:
+            batches = [W.layer_inputs(wl, seed, 0, step=i) for i in range(400)]
+            calls, y_ref0, ids0 = 0, None, None
+            t0 = time.perf_counter()
+            while calls < len(batches) and time.perf_counter() - t0 < 10.0:
+                xb, lgb = batches[calls]
+                ids, w, counts, offsets, perm = dxo.route(lgb, k)
+                y_ref = dxo.moe_forward(versions, d, f, wl.group, xb, ids, w)
+                if calls == 0:
+                    y_ref0, ids0 = y_ref, ids
+                calls += 1
+            dt = time.perf_counter() - t0
+            tokens0 = None
+            out["cpu_baseline"] = {"value": calls * T / dt, "unit": "tokens/s", "cores": dxo.threads(), "kind": "oracle",
+                                   "sample": f"{calls} full layer calls (layer 0's experts, all {T} tokens each, "
+                                             f"route + forward) in {dt:.1f} s"}
+        else:
+            xb, lgb = W.layer_inputs(wl, seed, 0, step=0)
+            tokens0 = np.arange(0, T, 2, dtype=np.int32)                 # every second token of the batch
+            t0 = time.perf_counter()
+            ids0, w, counts, offsets, perm = dxo.route(lgb, k)
+            y_ref0 = dxo.moe_forward(versions, d, f, wl.group, xb, ids0, w, tokens=tokens0)
+            dt = time.perf_counter() - t0
+            out["cpu_baseline"] = {"value": len(tokens0) / dt, "unit": "tokens/s", "cores": dxo.threads(), "kind": "oracle",
+                                   "sample": f"routing of all {T} tokens + the layer output of {len(tokens0)} evenly "
+                                             f"spaced tokens of one batch (layer 0's experts) in {dt:.1f} s"}
         # the first of those calls on the GPU, as a sanity check of the benchmarked path
         with torch.cuda.stream(stream):
             rb.route(ctx, 0, lgs[0])
             rb.forward(ctx, 0, xs[0], y)
             stream.synchronize()
         yg = W.bf16_bits_to_f32(LY.device_to_bits(y)).astype(np.float64)
+        if tokens0 is not None:
+            yg = yg[tokens0]
         out["parity_rel_l2_layer0"] = float(np.linalg.norm(yg - y_ref0) / np.linalg.norm(y_ref0))
         out["parity_ids_exact_layer0"] = bool(np.array_equal(rb.ids.cpu().numpy(), ids0))
     ctx.close()

@@ -122,6 +122,9 @@ struct dx_fwd_args {
     dx_bf16 *h;  // scratch [T*k (+T), fmax]
     float *o;    // scratch [T*k (+T), d]
     int T, E, k, d, f, group, shared_f, fmax;
+    int m_small; // experts with at most this many tokens take the streaming kernels, the others the tiled ones
 };
 // marks: null, or 4 events recorded before gate/up, after it, after down, after combine
 hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, hipEvent_t *marks);
+// dx_moe_prefill.hip: tiled gate/up then tiled down for the experts above a.m_small tokens
+hipError_t dxk_moe_forward_tiled(const dx_fwd_args &a, hipStream_t s, hipEvent_t *mark_after_gate_up);

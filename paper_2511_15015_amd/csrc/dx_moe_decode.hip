@@ -433,7 +433,11 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     // ---- the partition: cost units of every expert, exclusive prefix, this block's range ----
-    auto tokens_of = [&](int e) { return e == a.E ? a.T : a.offsets[e + 1] - a.offsets[e]; };
+    // experts above m_small tokens belong to the tiled kernels: they count as empty here
+    auto tokens_of = [&](int e) {
+        const int m = e == a.E ? a.T : a.offsets[e + 1] - a.offsets[e];
+        return m <= a.m_small ? m : 0;
+    };
     auto strips_of = [&](int e) { return DOWN ? a.d / 32 : (e == a.E ? a.shared_f : a.f) / 16; };
     auto fmt_of = [&](int e) { return e == a.E ? (uint32_t)DX_FMT_BF16 : a.table[e].fmt; };
     const int R = (nE + kThreads - 1) / kThreads; // experts per thread, consecutive
@@ -605,15 +609,33 @@ void launch_stream(const dx_fwd_args &a, split_choice c, dim3 grid, hipStream_t 
 }
 
 template <int LK>
-hipError_t launch_all(const dx_fwd_args &a, int n_blocks, hipStream_t s, hipEvent_t *marks)
+hipError_t launch_all(const dx_fwd_args &a_in, int n_blocks, hipStream_t s, hipEvent_t *marks)
 {
     constexpr int CHUNK = 4 * LK;
     const dim3 grid(n_blocks);
-    if (marks) (void)hipEventRecord(marks[0], s);
-    launch_stream<LK, false>(a, pick_split(a.d / CHUNK, a.d / CHUNK), grid, s);
-    if (marks) (void)hipEventRecord(marks[1], s);
-    launch_stream<LK, true>(a, pick_split(a.f / CHUNK, (a.shared ? a.shared_f : a.f) / CHUNK), grid, s);
-    if (marks) (void)hipEventRecord(marks[2], s);
+    dx_fwd_args a = a_in;
+    // Few tokens per expert everywhere (decode): the streaming kernels take every expert.  Otherwise
+    // experts above 32 tokens go to the tiled MFMA kernels (when the shapes fit their tiles).
+    const bool tiles_fit = a.d % 128 == 0 && a.f % 64 == 0 && (!a.shared || a.shared_f % 64 == 0);
+    const bool mixed = a.T > 64 && tiles_fit;
+    a.m_small = mixed ? 32 : 0x7fffffff;
+    const split_choice gu = pick_split(a.d / CHUNK, a.d / CHUNK);
+    const split_choice dn = pick_split(a.f / CHUNK, (a.shared ? a.shared_f : a.f) / CHUNK);
+    if (!mixed) {
+        if (marks) (void)hipEventRecord(marks[0], s);
+        launch_stream<LK, false>(a, gu, grid, s);
+        if (marks) (void)hipEventRecord(marks[1], s);
+        launch_stream<LK, true>(a, dn, grid, s);
+        if (marks) (void)hipEventRecord(marks[2], s);
+    } else {
+        // small experts first (both projections), then the tiled pair; the marks bracket the tiled kernels
+        launch_stream<LK, false>(a, gu, grid, s);
+        launch_stream<LK, true>(a, dn, grid, s);
+        if (marks) (void)hipEventRecord(marks[0], s);
+        const hipError_t e = dxk_moe_forward_tiled(a, s, marks ? &marks[1] : nullptr);
+        if (e != hipSuccess) return e;
+        if (marks) (void)hipEventRecord(marks[2], s);
+    }
     const dim3 g3((a.d / 4 + 255) / 256, a.T);
     hipLaunchKernelGGL(k_combine, g3, dim3(256), 0, s, a);
     if (marks) (void)hipEventRecord(marks[3], s);

@@ -368,3 +368,84 @@ def test_route_can_update_hotness_itself(B, LY, dxo):
                 dxo.hotness_update(c[layer], counts)
         assert np.array_equal(ctx.dx_get_counters(), c)
         ctx.close()
+
+
+# ------------------------------------------------------- prefill-sized batches
+@pytest.mark.parametrize("T,E,k,resident", [(65, 4, 2, [0, 2]), (200, 4, 2, [1]), (300, 8, 3, [0, 5, 6]),
+                                            (129, 2, 2, [0]), (400, 4, 1, [])])
+def test_forward_prefill_tiles_small_shapes(B, LY, dxo, T, E, k, resident):
+    """Segments above 32 tokens take the tiled MFMA kernels (bf16 and int4), the others the streaming
+    ones; ragged row tiles; every token checked."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k)
+    print(f"prefill tiles T={T} E={E} k={k} resident={resident}", flush=True)
+    x, logits = W.layer_inputs(wl, seed=6)
+    ly = Layer(B, LY, dxo, wl, resident, seed=6)
+    y_gpu, y_ref = ly.run(x, logits)
+    err = rel_l2(y_gpu, y_ref)
+    print("  rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    yg = bf16_bits_to_f32(y_gpu).astype(np.float64)
+    tok = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
+    assert tok.max() <= 2 * REL_L2_TOL
+    ly.ctx.close()
+
+
+def test_forward_prefill_with_shared_expert(B, LY, dxo):
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C4"], L=1, E=16, k=4, T=150, d=256, f=128, shared_f=256, group=128)
+    x, logits = W.layer_inputs(wl, seed=8)
+    shared = W.shared_master(wl, 8, 0)
+    ly = Layer(B, LY, dxo, wl, [0, 5, 9], seed=8, shared=shared)
+    y_gpu, y_ref = ly.run(x, logits)
+    err = rel_l2(y_gpu, y_ref)
+    print("  prefill shared rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    ly.ctx.close()
+
+
+def test_forward_c3_prefill_sampled_tokens(B, LY, dxo):
+    """The 30B-shaped prefill layer at full size (T=4096): routing bit-exact on all tokens, layer output
+    checked on sampled tokens the oracle computes one by one."""
+    wl = WORKLOADS["C3"]
+    print("forward C3: drawing masters", flush=True)
+    masters = W.layer_masters(wl, 0, 0)
+    x, logits = W.layer_inputs(wl, seed=0)
+    ids, w, counts, offsets, perm = dxo.route(logits, wl.k)
+    S = counts.astype(np.uint64) << np.uint64(16)
+    resident = set(int(e) for e in dxo.select_topn(S, wl.n_hi))
+    ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T)
+    dev = [LY.bits_to_device(m) for m in masters]
+    lw = LY.LayerWeights(ctx, 0, *dev, resident, wl.group)
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+    print("forward C3: running", flush=True)
+    rb.route(ctx, 0, torch.from_numpy(logits).cuda())
+    rb.forward(ctx, 0, LY.bits_to_device(x), y)
+    sync()
+    assert np.array_equal(rb.ids.cpu().numpy(), ids)
+    assert np.array_equal(rb.perm.cpu().numpy(), perm)
+    g = np.random.default_rng(0)
+    # sampled tokens: random ones plus tokens routed to the largest and to the smallest segments
+    big, small = int(np.argmax(counts)), int(np.argmin(np.where(counts > 0, counts, 1 << 30)))
+    forced = [int(perm[offsets[big]] // wl.k), int(perm[offsets[big + 1] - 1] // wl.k), int(perm[offsets[small]] // wl.k)]
+    tokens = np.unique(np.concatenate([g.choice(wl.T, 40, replace=False), forced])).astype(np.int32)
+    wg, wu, wd = masters
+    needed = set(int(e) for e in ids[tokens].ravel())
+    filler = None
+    versions = [None] * wl.E
+    for e in needed:
+        versions[e] = (dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if e in resident
+                       else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group))
+        filler = versions[e]
+    versions = [v if v is not None else filler for v in versions]
+    y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w, tokens=tokens)
+    y_gpu = LY.device_to_bits(y)[tokens]
+    err = rel_l2(y_gpu, y_ref)
+    print("  C3 sampled rel-L2", err, "segments max/min", counts.max(), counts[counts > 0].min(), flush=True)
+    assert err <= REL_L2_TOL
+    yg = bf16_bits_to_f32(y_gpu).astype(np.float64)
+    tok = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
+    assert tok.max() <= 2 * REL_L2_TOL
+    del lw
+    ctx.close()
