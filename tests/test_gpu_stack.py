@@ -1,0 +1,195 @@
+"""GPU parity at the full shapes of the stack workloads: the 80B-shaped layer
+(512 experts, top-10, one shared expert, budget rule giving 12 bf16 experts)
+and the 30B-shaped stack with hot-set drift, live promotion/demotion and
+publication between steps.  Layer outputs are checked against the CPU oracle
+with the format map the library reports; integer stages bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_15015_amd import workloads as W
+from paper_2511_15015_amd.workloads import WORKLOADS, bf16_bits_to_f32
+
+pytestmark = pytest.mark.gpu
+REL_L2_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2511_15015_amd import binding
+    binding.load()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def LY():
+    from paper_2511_15015_amd import layer
+    return layer
+
+
+def rel_l2(y_bits, y_ref):
+    y = bf16_bits_to_f32(y_bits).astype(np.float64)
+    return float(np.linalg.norm(y - y_ref) / np.linalg.norm(y_ref))
+
+
+def test_c4_layer_full_shape_with_budget_rule(B, LY, dxo):
+    """One 80B-shaped layer at full size: the 40 GiB stack budget gives 12 bf16 experts per layer,
+    chosen from a warm-up window; 500 int4 experts; the shared expert is added with weight 1."""
+    wl = WORKLOADS["C4"]
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, 0), dxo.expert_bytes(wl.d, wl.f, wl.group, 1)
+    b_sh = dxo.expert_bytes(wl.d, wl.shared_f, wl.group, 0)
+    stack_budget = 40 * 2 ** 30
+    layer_budget = (stack_budget - wl.L * b_sh) // wl.L
+    L = 2                                                           # two of the 48 layers are materialised
+    ctx = B.Context(L=L, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T, shared_f=wl.shared_f,
+                    route_updates_hotness=True)
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    # warm-up window of router traces -> scores -> resident set (GPU and oracle side by side)
+    c = np.zeros((L, wl.E), np.int64)
+    for step in range(1, 17):
+        for layer in range(L):
+            _, lg = W.layer_inputs(wl, 0, layer, step)
+            rb.route(ctx, layer, torch.from_numpy(lg).cuda())
+            _, _, counts, _, _ = dxo.route(lg, wl.k)
+            dxo.hotness_update(c[layer], counts)
+    S_gpu = ctx.dx_window_end()
+    S = np.zeros((L, wl.E), np.uint64)
+    for layer in range(L):
+        dxo.window_end(S[layer], c[layer], 0)
+    assert np.array_equal(S_gpu, S)
+    for layer in range(L):
+        print(f"C4 layer {layer}: selecting and materialising", flush=True)
+        resident = ctx.dx_select_resident(layer, layer_budget)
+        n = dxo.budget_capacity(layer_budget, wl.E, b_hi, b_lo)
+        assert n == 12 and np.array_equal(resident, dxo.select_topn(S[layer], n))
+        assert wl.L * (n * b_hi + (wl.E - n) * b_lo + b_sh) <= stack_budget        # the whole stack fits
+        wg, wu, wd = W.device_masters(wl, 0, layer)
+        lw = LY.LayerWeights(ctx, layer, wg, wu, wd, resident, wl.group, keep_masters=False)
+        g = torch.Generator(device="cuda"); g.manual_seed(1000 + layer)
+        shared = [(0.02 * torch.randn(s, generator=g, device="cuda")).to(torch.bfloat16)
+                  for s in ((wl.shared_f, wl.d), (wl.shared_f, wl.d), (wl.d, wl.shared_f))]
+        ctx.dx_swap_handle(layer, wl.E, B.make_handle(B.DX_FMT_BF16, *shared))
+        x, lg = W.layer_inputs(wl, 0, layer, 0)
+        y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+        rb.route(ctx, layer, torch.from_numpy(lg).cuda())
+        rb.forward(ctx, layer, LY.bits_to_device(x), y)
+        torch.cuda.synchronize()
+        ids, w, counts, offsets, perm = dxo.route(lg, wl.k)
+        assert np.array_equal(rb.ids.cpu().numpy(), ids) and np.array_equal(rb.perm.cpu().numpy(), perm)
+        res = set(int(e) for e in resident)
+        mh = [LY.device_to_bits(m) for m in (wg, wu, wd)]
+        versions, filler = [None] * wl.E, None
+        for e in np.flatnonzero(counts > 0):
+            e = int(e)
+            versions[e] = (dxo.ExpertVersion.bf16(*(m[e] for m in mh)) if e in res
+                           else dxo.ExpertVersion.int4_from_master(*(m[e] for m in mh), wl.group))
+            filler = versions[e]
+        versions = [v if v is not None else filler for v in versions]
+        sh = dxo.ExpertVersion.bf16(*(LY.device_to_bits(t) for t in shared))
+        y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w, shared=sh, shared_f=wl.shared_f)
+        err = rel_l2(LY.device_to_bits(y), y_ref)
+        print(f"  C4 layer {layer}: active {int((counts > 0).sum())} experts, "
+              f"{int(sum(counts[e] for e in res))}/{wl.T * wl.k} pairs on bf16 experts, rel-L2 {err:.2e}", flush=True)
+        assert err <= REL_L2_TOL
+        del lw, wg, wu, wd
+    ctx.close()
+
+
+def test_c5_drift_full_shape_few_layers(B, LY, dxo):
+    """30B-shaped layers through the pools with the Zipf permutation re-drawn every window: promotions
+    from pinned host masters and on-device demotions on the migration stream, polled between steps
+    (no waiting), every checked step replayed by the oracle with the reported format map."""
+    wl = WORKLOADS["C5"]
+    L, window, n_windows = 2, 6, 3
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, 0), dxo.expert_bytes(wl.d, wl.f, wl.group, 1)
+    layer_budget = wl.n_hi * b_hi + (wl.E - wl.n_hi) * b_lo
+    spare = 8
+    ctx = B.Context(L=L, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T,
+                    budget_bytes=L * layer_budget, transient_bytes=spare * (b_hi + b_lo), route_updates_hotness=True,
+                    window_steps=window)
+    ctx.dx_pools_create(L * wl.n_hi + spare, L * (wl.E - wl.n_hi) + spare)
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+    masters, pinned, lo_versions, hi_versions = [], [], [], []
+    for layer in range(L):
+        print(f"C5 layer {layer}: masters, pinned copies, oracle versions", flush=True)
+        dev = W.device_masters(wl, 0, layer)
+        host = [LY.device_to_bits(m) for m in dev]
+        masters.append(host)
+        pinned.append([torch.from_numpy(h.view(np.int16)).pin_memory() for h in host])
+        hi_versions.append([dxo.ExpertVersion.bf16(*(h[e] for h in host)) for e in range(wl.E)])
+        lo_versions.append([None] * wl.E)                        # quantised by the oracle on first use
+        # initial state: experts 0..31 bf16 (the all-zero-score selection), the rest int4
+        for e in range(wl.E):
+            fmt = B.DX_FMT_BF16 if e < wl.n_hi else B.DX_FMT_INT4G
+            ctx.dx_expert_install(layer, e, fmt, *(m[e] for m in dev), src_on_device=True)
+        del dev
+    assert ctx.dx_get_stats()["reserved_bytes"] == L * layer_budget
+
+    def lo_version(layer, e):
+        if lo_versions[layer][e] is None:
+            lo_versions[layer][e] = dxo.ExpertVersion.int4_from_master(*(h[e] for h in masters[layer]), wl.group)
+        return lo_versions[layer][e]
+
+    def check(layer, step, epoch):
+        fm = ctx.dx_get_formats()[layer]
+        x, lg = W.layer_inputs(wl, 0, layer, step, epoch)
+        rb.route(ctx, layer, torch.from_numpy(lg).cuda())
+        rb.forward(ctx, layer, LY.bits_to_device(x), y)
+        torch.cuda.synchronize()
+        ids, w, counts, *_ = dxo.route(lg, wl.k)
+        assert np.array_equal(rb.ids.cpu().numpy(), ids)
+        versions, filler = [None] * wl.E, None
+        for e in np.flatnonzero(counts > 0):
+            e = int(e)
+            versions[e] = hi_versions[layer][e] if fm[e] == B.DX_FMT_BF16 else lo_version(layer, e)
+            filler = versions[e]
+        versions = [v if v is not None else filler for v in versions]
+        err = rel_l2(LY.device_to_bits(y), dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w))
+        assert err <= REL_L2_TOL, (layer, step, err)
+        return int(sum(counts[e] for e in np.flatnonzero(fm == B.DX_FMT_BF16)))
+
+    pending = {layer: [] for layer in range(L)}                  # promotions waiting for capacity
+    step = 0
+    for wdw in range(n_windows):
+        epoch = wdw                                              # the hot set is re-drawn every window
+        for s in range(window):
+            for layer in range(L):
+                hot_pairs = check(layer, step, epoch)
+                if s in (0, window - 1):
+                    print(f"  window {wdw} step {step} layer {layer}: {hot_pairs}/{wl.T * wl.k} pairs on bf16 experts",
+                          flush=True)
+            # between steps: publish what has completed, then admit waiting promotions
+            ctx.dx_migrate_poll()
+            for layer in range(L):
+                still = []
+                for e in pending[layer]:
+                    try:
+                        ctx.dx_promote_async(layer, e, *(p[e] for p in pinned[layer]))
+                    except B.DxError as err:
+                        assert err.status in (B.DX_ERR_BUDGET, B.DX_ERR_NOMEM)
+                        still.append(e)
+                pending[layer] = still
+            step += 1
+        S = ctx.dx_window_end()
+        for layer in range(L):
+            target = ctx.dx_select_resident(layer, layer_budget)
+            assert np.array_equal(target, dxo.select_topn(S[layer], wl.n_hi))
+            pro, dem = ctx.dx_plan_transitions(layer, target)
+            for e in dem:
+                try:
+                    ctx.dx_demote_async(layer, int(e))
+                except B.DxError as err:                          # out of transient room: retried next window
+                    assert err.status in (B.DX_ERR_BUDGET, B.DX_ERR_NOMEM)
+            pending[layer] = [int(e) for e in pro]
+        st = ctx.dx_get_stats()
+        assert st["peak_reserved_bytes"] <= L * layer_budget + spare * (b_hi + b_lo)
+    ctx.dx_migrate_poll(wait=True)
+    st = ctx.dx_get_stats()
+    print("  C5 stats:", st, flush=True)
+    assert st["promotions_published"] > 0 and st["demotions_published"] > 0
+    assert st["h2d_bytes"] == st["promotions_issued"] * b_hi
+    assert st["quantize_read_bytes"] == st["demotions_issued"] * b_hi
+    for layer in range(L):
+        check(layer, step, n_windows - 1)
+    ctx.close()
