@@ -197,6 +197,11 @@ extern "C" dx_status dx_create(const dx_config *cfg, void *stream, dx_ctx **out)
         return fail(e, "hipDeviceGetAttribute");
     if (c->n_cu <= 0) c->n_cu = 256;
     if ((e = hipStreamCreateWithFlags(&c->mig, hipStreamNonBlocking)) != hipSuccess) return fail(e, "migration stream");
+    for (int i = 0; i < 2; ++i) {
+        if ((e = hipStreamCreateWithFlags(&c->aux[i], hipStreamNonBlocking)) != hipSuccess) return fail(e, "side stream");
+        if ((e = hipEventCreateWithFlags(&c->join[i], hipEventDisableTiming)) != hipSuccess) return fail(e, "join event");
+    }
+    if ((e = hipEventCreateWithFlags(&c->fork, hipEventDisableTiming)) != hipSuccess) return fail(e, "fork event");
     if ((e = hipMalloc(&c->d_table, n_entries * sizeof(dx_handle))) != hipSuccess) return fail(e, "handle table");
     if ((e = hipMalloc(&c->d_counters, (size_t)g.L * g.E * 8)) != hipSuccess) return fail(e, "counters");
     if ((e = hipHostMalloc(&c->h_counters, (size_t)g.L * g.E * 8, hipHostMallocDefault)) != hipSuccess)
@@ -235,6 +240,14 @@ extern "C" void dx_destroy(dx_ctx *c)
         (void)hipStreamSynchronize(c->mig);
         (void)hipStreamDestroy(c->mig);
     }
+    for (int i = 0; i < 2; ++i) {
+        if (c->aux[i]) {
+            (void)hipStreamSynchronize(c->aux[i]);
+            (void)hipStreamDestroy(c->aux[i]);
+        }
+        if (c->join[i]) (void)hipEventDestroy(c->join[i]);
+    }
+    if (c->fork) (void)hipEventDestroy(c->fork);
     for (auto &t : c->inflight) (void)hipEventDestroy(t.done);
     for (auto ev : c->event_pool) (void)hipEventDestroy(ev);
     for (auto ev : c->timing_pool) (void)hipEventDestroy(ev);
@@ -315,8 +328,9 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
     a.group = g.group;
     a.shared_f = g.shared_f;
     a.fmax = c->fmax;
+    const dx_fwd_streams side{{c->aux[0], c->aux[1]}, c->fork, {c->join[0], c->join[1]}};
     if (!c->profiling) {
-        DX_HIP(c, dxk_moe_forward(a, c->n_cu, c->compute, nullptr));
+        DX_HIP(c, dxk_moe_forward(a, c->n_cu, c->compute, &side, nullptr));
         return DX_OK;
     }
     std::array<hipEvent_t, 4> m;
@@ -332,7 +346,7 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
             }
         }
     }
-    hipError_t e = dxk_moe_forward(a, c->n_cu, c->compute, m.data());
+    hipError_t e = dxk_moe_forward(a, c->n_cu, c->compute, &side, m.data());
     c->marks.push_back(m);
     if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_moe_forward: %s", hipGetErrorString(e));
     return DX_OK;

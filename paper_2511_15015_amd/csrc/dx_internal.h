@@ -43,6 +43,9 @@ struct dx_ctx {
     int n_cu = 0; // compute units of the device: size of the persistent grids
     hipStream_t compute = nullptr;
     hipStream_t mig = nullptr;
+    // side streams and fork/join events of the prefill forward pass (independent kernel chains)
+    hipStream_t aux[2] = {nullptr, nullptr};
+    hipEvent_t fork = nullptr, join[2] = {nullptr, nullptr};
     std::string err;
 
     // handle tables: routed [L*E] then shared [L]
@@ -120,11 +123,22 @@ struct dx_fwd_args {
     const int32_t *offsets;
     const int32_t *perm;
     dx_bf16 *h;  // scratch [T*k (+T), fmax]
-    float *o;    // scratch [T*k (+T), d]
+    float *o;    // scratch [T*k (+T), d]: fp32, or bf16 in the same allocation when o_bf16
     int T, E, k, d, f, group, shared_f, fmax;
     int m_small; // experts with at most this many tokens take the streaming kernels, the others the tiled ones
+    int o_bf16;  // O rows are bf16 (prefill: halves the traffic between the down kernels and the combine), else fp32
+    int m_big;   // non-zero: the leading multiple of 256 rows of a bf16 expert takes the 256 x 256 tile kernel
 };
-// marks: null, or 4 events recorded before gate/up, after it, after down, after combine
-hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, hipEvent_t *marks);
-// dx_moe_prefill.hip: tiled gate/up then tiled down for the experts above a.m_small tokens
-hipError_t dxk_moe_forward_tiled(const dx_fwd_args &a, hipStream_t s, hipEvent_t *mark_after_gate_up);
+// Side streams for the prefill pass: its kernel chains (streamed small experts; 128-row tiles; 256-row
+// tiles) touch disjoint rows of H and O and run concurrently between `fork` and the joins.
+struct dx_fwd_streams {
+    hipStream_t aux[2];
+    hipEvent_t fork, join[2];
+};
+// marks: null, or 4 events recorded before gate/up, after it, after down, after combine (prefill: around
+// the chain on the caller's stream)
+hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks);
+// dx_moe_prefill.hip: gate/up then down for the experts above a.m_small tokens.  The 256-row tile
+// kernels (when a.m_big) go to s_big, the 128-row ones to s_tiled (the two may be the same stream).
+hipError_t dxk_moe_forward_tiled(const dx_fwd_args &a, hipStream_t s_big, hipStream_t s_tiled,
+                                 hipEvent_t *mark_after_gate_up);

@@ -273,8 +273,14 @@ __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_
         const int n = (sb + gg) * rows_per_strip + (L & 15);
         if constexpr (DOWN) {
             const int orow = ex.shared ? ex.seg0 + slot : a.perm[ex.seg0 + slot];
-            a.o[(size_t)orow * a.d + n] = v0;
-            a.o[(size_t)orow * a.d + n + 16] = v1;
+            if (a.o_bf16) {
+                dx_bf16 *ob = reinterpret_cast<dx_bf16 *>(a.o) + (size_t)orow * a.d + n;
+                ob[0] = (dx_bf16)float_to_bf16_rne(v0);
+                ob[16] = (dx_bf16)float_to_bf16_rne(v1);
+            } else {
+                a.o[(size_t)orow * a.d + n] = v0;
+                a.o[(size_t)orow * a.d + n + 16] = v1;
+            }
         } else {
             const float hv = v0 / (1.f + expf(-v0)) * v1;
             a.h[(size_t)(ex.seg0 + slot) * a.fmax + n] = (dx_bf16)float_to_bf16_rne(hv);
@@ -567,6 +573,33 @@ __global__ __launch_bounds__(256) void k_combine(dx_fwd_args a)
     *reinterpret_cast<uint2 *>(a.y + (size_t)t * a.d + c) = out;
 }
 
+// the same with bf16 O rows: 8 columns per thread
+__global__ __launch_bounds__(256) void k_combine_bf16(dx_fwd_args a)
+{
+    const int t = blockIdx.y;
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (c >= a.d) return;
+    const dx_bf16 *ob = reinterpret_cast<const dx_bf16 *>(a.o);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto add_row = [&](size_t row, float wj) {
+        const uint4 o = *reinterpret_cast<const uint4 *>(ob + row * a.d + c);
+        const uint32_t p[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += wj * __uint_as_float(p[i] << 16);
+            acc[2 * i + 1] += wj * __uint_as_float(p[i] & 0xFFFF0000u);
+        }
+    };
+    for (int j = 0; j < a.k; ++j) add_row((size_t)t * a.k + j, a.w[(size_t)t * a.k + j]);
+    if (a.shared) add_row((size_t)a.T * a.k + t, 1.f);
+    uint4 out;
+    out.x = float_to_bf16_rne(acc[0]) | (float_to_bf16_rne(acc[1]) << 16);
+    out.y = float_to_bf16_rne(acc[2]) | (float_to_bf16_rne(acc[3]) << 16);
+    out.z = float_to_bf16_rne(acc[4]) | (float_to_bf16_rne(acc[5]) << 16);
+    out.w = float_to_bf16_rne(acc[6]) | (float_to_bf16_rne(acc[7]) << 16);
+    *reinterpret_cast<uint4 *>(a.y + (size_t)t * a.d + c) = out;
+}
+
 // Chunks per wavefront for a contraction of nc chunks: the fast path needs nc = WPS * CPW with
 // WPS <= 8 wavefronts; prefer the split that leaves the fewest of the 8 wavefronts without a K-part.
 struct split_choice {
@@ -609,35 +642,67 @@ void launch_stream(const dx_fwd_args &a, split_choice c, dim3 grid, hipStream_t 
 }
 
 template <int LK>
-hipError_t launch_all(const dx_fwd_args &a_in, int n_blocks, hipStream_t s, hipEvent_t *marks)
+hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks)
 {
     constexpr int CHUNK = 4 * LK;
-    const dim3 grid(n_blocks);
     dx_fwd_args a = a_in;
     // Few tokens per expert everywhere (decode): the streaming kernels take every expert.  Otherwise
     // experts above 32 tokens go to the tiled MFMA kernels (when the shapes fit their tiles).
     const bool tiles_fit = a.d % 128 == 0 && a.f % 64 == 0 && (!a.shared || a.shared_f % 64 == 0);
     const bool mixed = a.T > 64 && tiles_fit;
     a.m_small = mixed ? 32 : 0x7fffffff;
+    // the 256 x 256 kernel addresses rows with 32-bit byte offsets from the matrix base
+    const uint64_t span_x = (uint64_t)a.T * a.d * 2, span_h = (uint64_t)a.T * (a.k + 1) * a.fmax * 2;
+    const bool big_fit = a.d % 256 == 0 && a.f % 128 == 0 && (!a.shared || a.shared_f % 128 == 0) &&
+                         span_x < (1ull << 32) && span_h < (1ull << 32) && (uint64_t)a.d * a.fmax * 2 < (1ull << 32);
+    a.m_big = mixed && big_fit ? 256 : 0;
+    a.o_bf16 = mixed; // d % 128 == 0 there, so rows split into 8-column pieces
+#ifdef DX_SERIAL_CHAINS
+    side = nullptr;
+#endif
     const split_choice gu = pick_split(a.d / CHUNK, a.d / CHUNK);
     const split_choice dn = pick_split(a.f / CHUNK, (a.shared ? a.shared_f : a.f) / CHUNK);
     if (!mixed) {
+        const dim3 grid(n_cu);
         if (marks) (void)hipEventRecord(marks[0], s);
         launch_stream<LK, false>(a, gu, grid, s);
         if (marks) (void)hipEventRecord(marks[1], s);
         launch_stream<LK, true>(a, dn, grid, s);
         if (marks) (void)hipEventRecord(marks[2], s);
-    } else {
-        // small experts first (both projections), then the tiled pair; the marks bracket the tiled kernels
+    } else if (!side) {
+        const dim3 grid(n_cu);
         launch_stream<LK, false>(a, gu, grid, s);
         launch_stream<LK, true>(a, dn, grid, s);
         if (marks) (void)hipEventRecord(marks[0], s);
-        const hipError_t e = dxk_moe_forward_tiled(a, s, marks ? &marks[1] : nullptr);
+        const hipError_t e = dxk_moe_forward_tiled(a, s, s, marks ? &marks[1] : nullptr);
         if (e != hipSuccess) return e;
         if (marks) (void)hipEventRecord(marks[2], s);
+    } else {
+        // Three chains on three streams.  The streamed experts are bound by memory, the tiles by the
+        // matrix cores, and the tail of each tiled grid leaves compute units idle: run together they
+        // fill each other's gaps.  The streaming grid is a quarter of the chip here so that the tile
+        // kernels (whose LDS footprint does not share a compute unit with it) keep the rest.
+        hipError_t e;
+        if ((e = hipEventRecord(side->fork, s)) != hipSuccess) return e;
+        for (int i = 0; i < 2; ++i)
+            if ((e = hipStreamWaitEvent(side->aux[i], side->fork, 0)) != hipSuccess) return e;
+        if (marks) (void)hipEventRecord(marks[0], s);
+        hipStream_t s_tiled = a.m_big ? side->aux[1] : s;
+        if ((e = dxk_moe_forward_tiled(a, s, s_tiled, marks ? &marks[1] : nullptr)) != hipSuccess) return e;
+        if (marks) (void)hipEventRecord(marks[2], s);
+        const dim3 grid(n_cu >= 8 ? n_cu / 4 : n_cu);
+        launch_stream<LK, false>(a, gu, grid, side->aux[0]);
+        launch_stream<LK, true>(a, dn, grid, side->aux[0]);
+        for (int i = 0; i < 2; ++i) {
+            if ((e = hipEventRecord(side->join[i], side->aux[i])) != hipSuccess) return e;
+            if ((e = hipStreamWaitEvent(s, side->join[i], 0)) != hipSuccess) return e;
+        }
     }
-    const dim3 g3((a.d / 4 + 255) / 256, a.T);
-    hipLaunchKernelGGL(k_combine, g3, dim3(256), 0, s, a);
+    if (a.o_bf16) {
+        hipLaunchKernelGGL(k_combine_bf16, dim3((a.d / 8 + 255) / 256, a.T), dim3(256), 0, s, a);
+    } else {
+        hipLaunchKernelGGL(k_combine, dim3((a.d / 4 + 255) / 256, a.T), dim3(256), 0, s, a);
+    }
     if (marks) (void)hipEventRecord(marks[3], s);
     return hipGetLastError();
 }
@@ -651,13 +716,11 @@ extern "C" int dx_debug_read_trace(void *dst, size_t bytes)
 }
 #endif
 
-hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, hipEvent_t *marks)
+hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks)
 {
     if (a.T == 0) return hipSuccess;
-    static const int bpc = getenv("DX_BPC") ? atoi(getenv("DX_BPC")) : 1;
-    const int n_blocks = n_cu * (bpc > 0 ? bpc : 1);
     // K-chunk = min(group, 128) so that a chunk never crosses a quantization group
-    if (a.group >= 128) return launch_all<32>(a, n_blocks, s, marks);
-    if (a.group == 64) return launch_all<16>(a, n_blocks, s, marks);
-    return launch_all<8>(a, n_blocks, s, marks);
+    if (a.group >= 128) return launch_all<32>(a, n_cu, s, side, marks);
+    if (a.group == 64) return launch_all<16>(a, n_cu, s, side, marks);
+    return launch_all<8>(a, n_cu, s, side, marks);
 }

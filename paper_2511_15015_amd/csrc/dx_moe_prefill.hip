@@ -14,12 +14,14 @@
 //   gate/up: the tile's 128 columns are 64 gate rows and the 64 up rows of the
 //            same indices, and every wavefront owns matching gate/up columns,
 //            so SwiGLU happens on the accumulators; H is written once as bf16.
-//   down:    plain 128 x 128 tiles of O = H . W_down^T, written as fp32 rows in
+//   down:    plain 128 x 128 tiles of O = H . W_down^T, written as bf16 rows in
 //            pair order for the combine kernel.
 // Tiles are listed expert-major, column-tile next, row-tile innermost, and the
 // list is cut into 8 contiguous ranges, one per XCD (block b works in range
 // b % 8), so the row tiles that share a weight tile run on the same L2.
 #include "dx_internal.h"
+
+#include <type_traits>
 
 namespace {
 
@@ -52,6 +54,12 @@ __device__ __forceinline__ uint32_t float_to_bf16_rne(float f)
     return u >> 16;
 }
 
+// silu(g) * u with the hardware exp2 and reciprocal (their error is far below the bf16 rounding of H)
+__device__ __forceinline__ float swiglu_fast(float g, float u)
+{
+    return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
+}
+
 // 8 nibbles of `word` times scale -> 8 bf16 in element order
 __device__ __forceinline__ u32x4 dequant8(uint32_t word, float scale)
 {
@@ -67,24 +75,48 @@ __device__ __forceinline__ u32x4 dequant8(uint32_t word, float scale)
 
 struct tile_id {
     int e, mt, nt; // expert (E = shared), row tile, column tile
-    int seg0, m;
+    int seg0, m;   // first pair slot and number of rows of the part of the segment this kernel owns
+    int tok0;      // shared expert: token of row 0 of that part
     bool valid;
 };
 
-// Every block derives the tile list from `offsets`: experts with more than m_small tokens, each
-// ceil(m/128) row tiles x ntn column tiles.  LDS: tile prefix per expert.
+constexpr int kBigRows = 256; // row granularity of the big-tile kernel
+
+// Rows of expert e that belong to the calling kernel.  Segments up to m_small tokens are not tiled at
+// all.  When the big-tile kernel is on (a.m_big), it owns the leading multiple of 256 rows of every
+// bf16 expert and the 128-row kernel owns the rest (all rows of an int4 expert).
+template <bool BIG>
+__device__ __forceinline__ void owned_rows(const dx_fwd_args &a, int e, int &row0, int &rows)
+{
+    const int m = e == a.E ? a.T : a.offsets[e + 1] - a.offsets[e];
+    row0 = rows = 0;
+    if (m <= a.m_small) return;
+    int lead = 0;
+    if (a.m_big && m >= kBigRows) {
+        const int fmt = e == a.E ? a.shared->fmt : a.table[e].fmt;
+        if (fmt == DX_FMT_BF16) lead = m / kBigRows * kBigRows;
+    }
+    if (BIG) rows = lead;
+    else row0 = lead, rows = m - lead;
+}
+
+// Every block derives the tile list from `offsets`: per expert ceil(rows/TM) row tiles x ntn column
+// tiles, expert-major, column tile next, row tile innermost.  The list is cut into 8 contiguous
+// ranges, one per XCD (block b works in range b % 8).  LDS: tile prefix per expert.
+template <int THREADS, int TM, bool BIG>
 __device__ tile_id find_tile(const dx_fwd_args &a, int ntn_routed, int ntn_shared, uint32_t *cum, uint32_t *wave_tot)
 {
     const int nE = a.E + (a.shared ? 1 : 0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int R = (nE + kThreads - 1) / kThreads; // <= 5
+    const int R = (nE + THREADS - 1) / THREADS; // <= 5
     uint32_t mine[5] = {0, 0, 0, 0, 0}, local = 0;
 #pragma unroll
     for (int i = 0; i < 5; ++i) {
         const int e = tid * R + i;
         if (i < R && e < nE) {
-            const int m = e == a.E ? a.T : a.offsets[e + 1] - a.offsets[e];
-            if (m > a.m_small) mine[i] = (uint32_t)((m + BM - 1) / BM) * (e == a.E ? ntn_shared : ntn_routed);
+            int row0, rows;
+            owned_rows<BIG>(a, e, row0, rows);
+            mine[i] = (uint32_t)((rows + TM - 1) / TM) * (e == a.E ? ntn_shared : ntn_routed);
             local += mine[i];
         }
     }
@@ -98,7 +130,7 @@ __device__ tile_id find_tile(const dx_fwd_args &a, int ntn_routed, int ntn_share
     __syncthreads();
     uint32_t base = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) {
+    for (int w = 0; w < THREADS / 64; ++w) {
         const uint32_t t = wave_tot[w];
         if (w < wave) base += t;
         total += t;
@@ -116,24 +148,25 @@ __device__ tile_id find_tile(const dx_fwd_args &a, int ntn_routed, int ntn_share
     __syncthreads();
     tile_id t;
     t.valid = false;
-    t.e = t.mt = t.nt = t.seg0 = t.m = 0;
-    // XCD-contiguous ranges of the tile list
+    t.e = t.mt = t.nt = t.seg0 = t.m = t.tok0 = 0;
     const uint32_t per_xcd = (total + 7) / 8;
     const uint32_t idx = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((blockIdx.x >> 3) >= per_xcd || idx >= total) return t;
-    // binary search: the expert whose range contains idx
+    // binary search: the expert whose range contains idx (experts with empty ranges are skipped)
     int lo = 0, hi = nE; // cum[lo] <= idx < cum[hi]
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (cum[mid] <= idx) lo = mid;
         else hi = mid;
     }
-    // skip experts with empty ranges that share cum[lo]
     t.e = lo;
     const uint32_t local_idx = idx - cum[lo];
-    t.m = t.e == a.E ? a.T : a.offsets[t.e + 1] - a.offsets[t.e];
-    t.seg0 = t.e == a.E ? a.T * a.k : a.offsets[t.e];
-    const int nmt = (t.m + BM - 1) / BM;
+    int row0, rows;
+    owned_rows<BIG>(a, t.e, row0, rows);
+    t.m = rows;
+    t.tok0 = row0;
+    t.seg0 = (t.e == a.E ? a.T * a.k : a.offsets[t.e]) + row0;
+    const int nmt = (rows + TM - 1) / TM;
     t.nt = local_idx / nmt;
     t.mt = local_idx % nmt;
     t.valid = true;
@@ -170,10 +203,10 @@ struct b_regs {
     uint32_t scale;
 };
 
-__device__ __forceinline__ void load_b(b_regs &r, bool int4, const gbytes (&rowp)[4], gbytes qrow, gbf16 srow, int k0,
-                                       int group)
+template <bool INT4>
+__device__ __forceinline__ void load_b(b_regs &r, const gbytes (&rowp)[4], gbytes qrow, gbf16 srow, int k0, int group)
 {
-    if (int4) {
+    if constexpr (INT4) {
         const int half = threadIdx.x & 1;
         r.v[0] = *reinterpret_cast<gvec16>(qrow + ((k0 + half * 32) >> 1));
         r.scale = srow[(k0 + half * 32) / group];
@@ -184,9 +217,10 @@ __device__ __forceinline__ void load_b(b_regs &r, bool int4, const gbytes (&rowp
     }
 }
 
-__device__ __forceinline__ void store_b(const b_regs &r, bool int4, char *tile)
+template <bool INT4>
+__device__ __forceinline__ void store_b(const b_regs &r, char *tile)
 {
-    if (int4) {
+    if constexpr (INT4) {
         const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
         const float s = bf16_bits_to_float(r.scale);
         char *dst = tile + row * kRowBytes + half * 64;
@@ -230,21 +264,13 @@ __device__ __forceinline__ void mma_step(const char *ta, const char *tb, int wm,
 // accumulator element v of a 32x32 tile: row (v/4)*8 + (lane/32)*4 + v%4, column lane%32
 __device__ __forceinline__ int acc_row(int v, int lane) { return (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3); }
 
-template <bool DOWN>
-__global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
+// One output tile.  INT4 selects the staging of the weight tile at compile time so that the bf16
+// loop carries no trace of the int4 expansion (and the other way round).
+template <bool DOWN, bool INT4>
+__device__ __forceinline__ void tile_main(const dx_fwd_args &a, const tile_id &t, const dx_handle &hd, char *lds)
 {
-    __shared__ __attribute__((aligned(16))) char lds[4 * kTileBytes]; // A0 A1 B0 B1: 72 KB
-    __shared__ uint32_t cum[kMaxExperts + 1];
-    __shared__ uint32_t wave_tot[kThreads / 64];
-
-    const int ntn_routed = DOWN ? a.d / BN : a.f / (BN / 2);
-    const int ntn_shared = DOWN ? a.d / BN : a.shared_f / (BN / 2);
-    const tile_id t = find_tile(a, ntn_routed, ntn_shared, cum, wave_tot);
-    if (!t.valid) return; // block-uniform
-
+    constexpr bool int4 = INT4;
     const bool shared = t.e == a.E;
-    const dx_handle hd = shared ? *a.shared : a.table[t.e];
-    const bool int4 = hd.fmt == DX_FMT_INT4G;
     const int fe = shared ? a.shared_f : a.f;
     const int K = DOWN ? fe : a.d;
     const size_t wrow_bytes = int4 ? (size_t)K / 2 : (size_t)K * 2;
@@ -262,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
         if constexpr (DOWN) {
             arow[i] = (gbf16)a.h + (size_t)(t.seg0 + slot) * a.fmax;
         } else {
-            const int tok = shared ? slot : a.perm[t.seg0 + slot] / a.k;
+            const int tok = shared ? t.tok0 + slot : a.perm[t.seg0 + slot] / a.k;
             arow[i] = (gbf16)a.x + (size_t)tok * K;
         }
     }
@@ -311,27 +337,38 @@ __global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
 
     auto ta = [&](int i) { return lds + i * kTileBytes; };
     auto tb = [&](int i) { return lds + (2 + i) * kTileBytes; };
-    a_regs ra;
-    b_regs rb;
+    // Two register stages: while the MFMA loop works on K-step kt from LDS, the tile of kt + 1 is on
+    // its way from memory in one register set (it is written to the other LDS buffer at the end of
+    // this step) and the loads of kt + 2 are issued into the other set, so every load has two full
+    // steps to arrive.  Loads past the end re-read the last tile (never stored).
+    a_regs ra[2];
+    b_regs rb[2];
     const int nk = K / BK;
-    load_a(ra, arow, 0);
-    load_b(rb, int4, brow, qrow, srow, 0, a.group);
-    store_a(ra, ta(0));
-    store_b(rb, int4, tb(0));
+    auto k_of = [&](int kt) { return (kt < nk ? kt : nk - 1) * BK; };
+    load_a(ra[0], arow, 0);
+    load_b<INT4>(rb[0], brow, qrow, srow, 0, a.group);
+    load_a(ra[1], arow, k_of(1));
+    load_b<INT4>(rb[1], brow, qrow, srow, k_of(1), a.group);
+    store_a(ra[0], ta(0));
+    store_b<INT4>(rb[0], tb(0));
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
+    auto step = [&](int kt, auto parity) {
+        constexpr int P = decltype(parity)::value;
+        load_a(ra[P], arow, k_of(kt + 2));
+        load_b<INT4>(rb[P], brow, qrow, srow, k_of(kt + 2), a.group);
+        mma_step(ta(P), tb(P), wm, brow0, brow1, acc);
         if (kt + 1 < nk) {
-            load_a(ra, arow, (kt + 1) * BK);
-            load_b(rb, int4, brow, qrow, srow, (kt + 1) * BK, a.group);
-        }
-        mma_step(ta(cur), tb(cur), wm, brow0, brow1, acc);
-        if (kt + 1 < nk) {
-            store_a(ra, ta(cur ^ 1));
-            store_b(rb, int4, tb(cur ^ 1));
+            store_a(ra[P ^ 1], ta(P ^ 1));
+            store_b<INT4>(rb[P ^ 1], tb(P ^ 1));
         }
         __syncthreads();
+    };
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        step(kt, std::integral_constant<int, 0>{});
+        step(kt + 1, std::integral_constant<int, 1>{});
     }
+    if (kt < nk) step(kt, std::integral_constant<int, 0>{});
 
     // ---- epilogue ----
     const int col = lane & 31;
@@ -343,32 +380,254 @@ __global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
             if (slot >= t.m) continue;
             if constexpr (DOWN) {
                 const size_t orow = shared ? (size_t)(t.seg0 + slot) : (size_t)a.perm[t.seg0 + slot];
-                float *dst = a.o + orow * a.d + t.nt * BN + wn * 64 + col;
-                dst[0] = acc[ms][0][v];
-                dst[32] = acc[ms][1][v];
+                dx_bf16 *dst = reinterpret_cast<dx_bf16 *>(a.o) + orow * a.d + t.nt * BN + wn * 64 + col;
+                dst[0] = (dx_bf16)float_to_bf16_rne(acc[ms][0][v]);
+                dst[32] = (dx_bf16)float_to_bf16_rne(acc[ms][1][v]);
             } else {
                 const float g = acc[ms][0][v], u = acc[ms][1][v];
-                const float hv = g / (1.f + expf(-g)) * u;
+                const float hv = swiglu_fast(g, u);
                 a.h[(size_t)(t.seg0 + slot) * a.fmax + t.nt * (BN / 2) + wn * 32 + col] = (dx_bf16)float_to_bf16_rne(hv);
             }
         }
     }
 }
 
+template <bool DOWN>
+__global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
+{
+    __shared__ __attribute__((aligned(16))) char lds[4 * kTileBytes]; // A0 A1 B0 B1: 72 KB
+    __shared__ uint32_t cum[kMaxExperts + 1];
+    __shared__ uint32_t wave_tot[kThreads / 64];
+
+    const int ntn_routed = DOWN ? a.d / BN : a.f / (BN / 2);
+    const int ntn_shared = DOWN ? a.d / BN : a.shared_f / (BN / 2);
+    const tile_id t = find_tile<kThreads, BM, false>(a, ntn_routed, ntn_shared, cum, wave_tot);
+    if (!t.valid) return; // block-uniform
+    const dx_handle hd = t.e == a.E ? *a.shared : a.table[t.e];
+    if (hd.fmt == DX_FMT_INT4G) tile_main<DOWN, true>(a, t, hd, lds);
+    else tile_main<DOWN, false>(a, t, hd, lds);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Large bf16 segments: 256 x 256 output tiles, 8 wavefronts (2 along rows x 4 along columns, each a
+// 128 x 64 sub-tile = 4 x 2 MFMA tiles), K in steps of 32 through a four-stage LDS ring that is
+// filled by global_load_lds_dwordx4 (memory to LDS without passing through registers), up to four
+// steps ahead of the MFMA loop.  One barrier per step.
+//   LDS rows are 64 bytes (4 pieces of 16 bytes), unpadded because a wavefront-wide LDS load writes
+//   1 KB contiguously (lane l -> byte 16*l).  The piece stored in slot c of row r is c ^ ((r>>2)&3):
+//   the 16 lanes that read one piece index of 16 consecutive rows then hit 16 different bank groups.
+//   The loads are inline assembly so that the compiler does not serialise them against the LDS
+//   reads; their completion is awaited with explicit vmcnt counts (4 loads per wavefront per step).
+constexpr int TM = 256, TN = 256, TK = 32;
+constexpr int kBigThreads = 512;
+constexpr int kStageBytes = (TM + TN) * TK * 2; // 32 KB: A rows then B rows
+constexpr int kStages = 4;
+
+typedef __attribute__((address_space(3))) char lds_char;
+
+// one wavefront-wide 16-byte-per-lane load: memory (sbase + voff) -> LDS (m0 + 16 * lane)
+__device__ __forceinline__ void load_to_lds(uint32_t m0, uint32_t voff, uint64_t sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+template <bool DOWN>
+__global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
+{
+    // 128 KB ring; the tail keeps room for the staged output tile (256 rows of 512 + 16 bytes)
+    __shared__ __attribute__((aligned(1024))) char ring[kStages * kStageBytes + TM * 16];
+    __shared__ uint32_t cum[kMaxExperts + 1];
+    __shared__ uint32_t wave_tot[kBigThreads / 64];
+
+    const int ntn_routed = DOWN ? a.d / TN : a.f / (TN / 2);
+    const int ntn_shared = DOWN ? a.d / TN : a.shared_f / (TN / 2);
+    const tile_id t = find_tile<kBigThreads, TM, true>(a, ntn_routed, ntn_shared, cum, wave_tot);
+    if (!t.valid) return; // block-uniform
+    const bool shared = t.e == a.E;
+    const dx_handle hd = shared ? *a.shared : a.table[t.e];
+    const int fe = shared ? a.shared_f : a.f;
+    const int K = DOWN ? fe : a.d;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+
+    // ---- loader role: wavefront w fills rows [32w, 32w + 32) of the A part and of the B part ----
+    uint32_t a_off[2], b_off[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = 32 * wave + 16 * i + (lane >> 2);
+        const uint32_t piece = (uint32_t)((lane & 3) ^ ((row >> 2) & 3));
+        const int slot = t.mt * TM + row; // big tiles are full: slot < t.m
+        if constexpr (DOWN) {
+            a_off[i] = (uint32_t)(t.seg0 + slot) * (uint32_t)a.fmax * 2u + piece * 16u;
+            b_off[i] = (uint32_t)(t.nt * TN + row) * (uint32_t)K * 2u + piece * 16u;
+        } else {
+            const int tok = shared ? t.tok0 + slot : a.perm[t.seg0 + slot] / a.k;
+            a_off[i] = (uint32_t)tok * (uint32_t)K * 2u + piece * 16u;
+            b_off[i] = (uint32_t)(t.nt * (TN / 2) + (row & 127)) * (uint32_t)K * 2u + piece * 16u;
+        }
+    }
+    const uint64_t a_base = (uint64_t)(DOWN ? (const void *)a.h : (const void *)a.x);
+    const void *bmat = DOWN ? hd.w_down : (wave < 4 ? hd.w_gate : hd.w_up);
+    // wave-uniform matrix base as a scalar pair (the halves go through unsigned 32-bit values: the
+    // builtin returns int, which must not be sign-extended into the upper half)
+    const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)bmat);
+    const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)bmat >> 32));
+    const uint64_t b_base = (uint64_t)b_lo | ((uint64_t)b_hi << 32);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char *)ring;
+    const uint32_t m0_a = lds0 + wave * 2048, m0_b = lds0 + TM * TK * 2 + wave * 2048;
+    const int nk = K / TK;
+    auto issue = [&](int kt, int stage) {
+        const uint64_t kb = (uint64_t)(kt < nk ? kt : nk - 1) * (TK * 2);
+        const uint32_t so = (uint32_t)stage * kStageBytes;
+        load_to_lds(m0_a + so, a_off[0], a_base + kb);
+        load_to_lds(m0_a + so + 1024, a_off[1], a_base + kb);
+        load_to_lds(m0_b + so, b_off[0], b_base + kb);
+        load_to_lds(m0_b + so + 1024, b_off[1], b_base + kb);
+    };
+
+    // ---- MFMA role ----
+    const int r = lane & 31, kq = lane >> 5, swz = (r >> 2) & 3;
+    const int a_lane = (wm * 128 + r) * (TK * 2);
+    const int b_lane0 = TM * TK * 2 + (DOWN ? wn * 64 + r : wn * 32 + r) * (TK * 2);
+    const int b_lane1 = TM * TK * 2 + (DOWN ? wn * 64 + 32 + r : 128 + wn * 32 + r) * (TK * 2);
+    const int slot0 = (kq ^ swz) * 16, slot1 = ((2 + kq) ^ swz) * 16;
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+        for (int ns = 0; ns < 2; ++ns)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ms][ns][v] = 0.f;
+
+    // Software pipeline.  Each K-step has two halves (16 k-values each); the fragments of a half sit
+    // in registers before its MFMAs start.  The barrier is in the middle of a step, in the shadow of
+    // the first half's MFMAs: past it every wavefront holds all of stage S in registers, so S is
+    // refilled at once with step kt + 4, and the landed stage of step kt + 1 may be read.
+    frag8 fa[2][4], fb[2][2];
+    auto read_frags = [&](int stage, int half, frag8 (&af)[4], frag8 (&bf)[2]) {
+        const char *st = ring + stage * kStageBytes;
+        const int so = half ? slot1 : slot0;
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms) af[ms].u = *reinterpret_cast<const u32x4 *>(st + a_lane + ms * 2048 + so);
+        bf[0].u = *reinterpret_cast<const u32x4 *>(st + b_lane0 + so);
+        bf[1].u = *reinterpret_cast<const u32x4 *>(st + b_lane1 + so);
+    };
+    auto mma_half = [&](const frag8 (&af)[4], const frag8 (&bf)[2]) {
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+            for (int ns = 0; ns < 2; ++ns)
+                acc[ms][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ns].v, af[ms].v, acc[ms][ns], 0, 0, 0);
+    };
+    issue(0, 0);
+    issue(1, 1);
+    issue(2, 2);
+    issue(3, 3);
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); // own loads of step 0
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, 0, fa[0], fb[0]);
+    auto step = [&](int kt, auto stage_c) {
+        constexpr int S = decltype(stage_c)::value;
+        // (the scheduling fences keep the LDS reads ahead of the MFMAs they overlap with)
+        read_frags(S, 1, fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_half(fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // own loads of step kt + 1 have landed (8 younger ones may still fly) and own LDS reads of
+        // stage S have returned; after the barrier that holds for every wavefront
+        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        issue(kt + 4, S);
+        read_frags((S + 1) & 3, 0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_half(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int kt = 0; kt < nk; kt += 4) { // nk is a multiple of 4 (K a multiple of 128)
+        step(kt, std::integral_constant<int, 0>{});
+        step(kt + 1, std::integral_constant<int, 1>{});
+        step(kt + 2, std::integral_constant<int, 2>{});
+        step(kt + 3, std::integral_constant<int, 3>{});
+    }
+    // the redundant loads issued past the end still target this block's LDS: drain them
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // ---- epilogue: through LDS, so that the tile leaves as whole rows in 16-byte pieces ----
+    // The weights were the first MFMA operand: accumulator element v of a 32 x 32 tile is output column
+    // (v/4)*8 + (lane/32)*4 + v%4 of token lane%32, i.e. four consecutive columns per group of four v.
+    __builtin_amdgcn_s_barrier(); // every wavefront is done with the ring
+    constexpr int OUT_COLS = DOWN ? TN : TN / 2;
+    constexpr int OUT_STRIDE = OUT_COLS * 2 + 16; // bytes per staged row
+    {
+        const int tok_l = lane & 31, nq = (lane >> 5) * 4;
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms) {
+            char *rowp = ring + (wm * 128 + ms * 32 + tok_l) * OUT_STRIDE;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if constexpr (DOWN) {
+#pragma unroll
+                    for (int ns = 0; ns < 2; ++ns) {
+                        uint2 pk;
+                        pk.x = float_to_bf16_rne(acc[ms][ns][4 * q]) | (float_to_bf16_rne(acc[ms][ns][4 * q + 1]) << 16);
+                        pk.y = float_to_bf16_rne(acc[ms][ns][4 * q + 2]) | (float_to_bf16_rne(acc[ms][ns][4 * q + 3]) << 16);
+                        *reinterpret_cast<uint2 *>(rowp + (wn * 64 + ns * 32 + q * 8 + nq) * 2) = pk;
+                    }
+                } else {
+                    uint32_t hb[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        hb[i] = float_to_bf16_rne(swiglu_fast(acc[ms][0][4 * q + i], acc[ms][1][4 * q + i]));
+                    uint2 pk;
+                    pk.x = hb[0] | (hb[1] << 16);
+                    pk.y = hb[2] | (hb[3] << 16);
+                    *reinterpret_cast<uint2 *>(rowp + (wn * 32 + q * 8 + nq) * 2) = pk;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    constexpr int PIECES = OUT_COLS / 8;               // 16-byte pieces per row
+    constexpr int ROWS_PER_PASS = kBigThreads / PIECES; // rows written per pass of the block
+    const int piece = tid % PIECES;
+#pragma unroll 4
+    for (int row = tid / PIECES; row < TM; row += ROWS_PER_PASS) {
+        const int slot = t.mt * TM + row;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(ring + row * OUT_STRIDE + piece * 16);
+        dx_bf16 *dst;
+        if constexpr (DOWN) {
+            const size_t orow = shared ? (size_t)(t.seg0 + slot) : (size_t)a.perm[t.seg0 + slot];
+            dst = reinterpret_cast<dx_bf16 *>(a.o) + orow * a.d + t.nt * TN + piece * 8;
+        } else {
+            dst = a.h + (size_t)(t.seg0 + slot) * a.fmax + t.nt * (TN / 2) + piece * 8;
+        }
+        *reinterpret_cast<u32x4 *>(dst) = v;
+    }
+}
+
 } // namespace
 
-// upper bound on the number of tiles: sum over experts of ceil(m/128) <= pairs/128 + experts
-hipError_t dxk_moe_forward_tiled(const dx_fwd_args &a, hipStream_t s, hipEvent_t *m_after_gate_up)
+// Grid sizes are upper bounds on the tile counts (sum over experts of ceil(rows/TM) <= pairs/TM + experts);
+// surplus blocks find no tile and leave.
+hipError_t dxk_moe_forward_tiled(const dx_fwd_args &a, hipStream_t s_big, hipStream_t s_tiled,
+                                 hipEvent_t *m_after_gate_up)
 {
     const long pairs = (long)a.T * a.k;
-    const long row_tiles = pairs / BM + a.E + (a.shared ? (a.T + BM - 1) / BM : 0);
     const int fe = a.shared && a.shared_f > a.f ? a.shared_f : a.f;
-    long g1 = row_tiles * (fe / (BN / 2));
-    long g2 = row_tiles * (a.d / BN);
-    g1 = ((g1 + 7) / 8) * 8;
-    g2 = ((g2 + 7) / 8) * 8;
-    hipLaunchKernelGGL((k_tiled<false>), dim3((unsigned)g1), dim3(kThreads), 0, s, a);
-    if (m_after_gate_up) (void)hipEventRecord(*m_after_gate_up, s);
-    hipLaunchKernelGGL((k_tiled<true>), dim3((unsigned)g2), dim3(kThreads), 0, s, a);
+    auto round8 = [](long g) { return (unsigned)(((g + 7) / 8) * 8); };
+    const long row_tiles = pairs / BM + a.E + (a.shared ? (a.T + BM - 1) / BM : 0);
+    const long big_tiles = a.m_big ? pairs / TM + (a.shared ? a.T / TM : 0) : 0;
+    // the long-running 256-row kernels are queued first
+    if (big_tiles) {
+        hipLaunchKernelGGL((k_big<false>), dim3(round8(big_tiles * (fe / (TN / 2)))), dim3(kBigThreads), 0, s_big, a);
+        if (m_after_gate_up && s_big != s_tiled) (void)hipEventRecord(*m_after_gate_up, s_big);
+        hipLaunchKernelGGL((k_big<true>), dim3(round8(big_tiles * (a.d / TN))), dim3(kBigThreads), 0, s_big, a);
+    }
+    hipLaunchKernelGGL((k_tiled<false>), dim3(round8(row_tiles * (fe / (BN / 2)))), dim3(kThreads), 0, s_tiled, a);
+    if (m_after_gate_up && !(big_tiles && s_big != s_tiled)) (void)hipEventRecord(*m_after_gate_up, s_tiled);
+    hipLaunchKernelGGL((k_tiled<true>), dim3(round8(row_tiles * (a.d / BN))), dim3(kThreads), 0, s_tiled, a);
     return hipGetLastError();
 }

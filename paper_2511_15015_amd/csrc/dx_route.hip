@@ -174,7 +174,19 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_scan(
     const int e = threadIdx.x;
     int run = 0;
     if (e < E) {
-        for (int c = 0; c < n_chunks; ++c) {
+        // eight independent mask loads in flight per round
+        int c = 0;
+        for (; c + 8 <= n_chunks; c += 8) {
+            unsigned long long m[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m[i] = mask[(size_t)(c + i) * E + e];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                chunk_base[(size_t)(c + i) * E + e] = run;
+                run += __popcll(m[i]);
+            }
+        }
+        for (; c < n_chunks; ++c) {
             chunk_base[(size_t)c * E + e] = run;
             run += __popcll(mask[(size_t)c * E + e]);
         }

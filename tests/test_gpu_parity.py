@@ -372,7 +372,10 @@ def test_route_can_update_hotness_itself(B, LY, dxo):
 
 # ------------------------------------------------------- prefill-sized batches
 @pytest.mark.parametrize("T,E,k,resident", [(65, 4, 2, [0, 2]), (200, 4, 2, [1]), (300, 8, 3, [0, 5, 6]),
-                                            (129, 2, 2, [0]), (400, 4, 1, [])])
+                                            (129, 2, 2, [0]), (400, 4, 1, []),
+                                            # bf16 segments of 256 rows and more: 256 x 256 tiles plus a remainder
+                                            (700, 4, 2, [0, 2]), (1100, 2, 2, [0, 1]), (512, 2, 2, [1]),
+                                            (256, 1, 1, [0])])
 def test_forward_prefill_tiles_small_shapes(B, LY, dxo, T, E, k, resident):
     """Segments above 32 tokens take the tiled MFMA kernels (bf16 and int4), the others the streaming
     ones; ragged row tiles; every token checked."""
@@ -391,9 +394,10 @@ def test_forward_prefill_tiles_small_shapes(B, LY, dxo, T, E, k, resident):
     ly.ctx.close()
 
 
-def test_forward_prefill_with_shared_expert(B, LY, dxo):
+@pytest.mark.parametrize("T", [150, 600])
+def test_forward_prefill_with_shared_expert(B, LY, dxo, T):
     import dataclasses
-    wl = dataclasses.replace(WORKLOADS["C4"], L=1, E=16, k=4, T=150, d=256, f=128, shared_f=256, group=128)
+    wl = dataclasses.replace(WORKLOADS["C4"], L=1, E=16, k=4, T=T, d=256, f=128, shared_f=256, group=128)
     x, logits = W.layer_inputs(wl, seed=8)
     shared = W.shared_master(wl, 8, 0)
     ly = Layer(B, LY, dxo, wl, [0, 5, 9], seed=8, shared=shared)
