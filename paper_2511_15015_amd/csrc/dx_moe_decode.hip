@@ -657,9 +657,6 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
                          span_x < (1ull << 32) && span_h < (1ull << 32) && (uint64_t)a.d * a.fmax * 2 < (1ull << 32);
     a.m_big = mixed && big_fit ? 256 : 0;
     a.o_bf16 = mixed; // d % 128 == 0 there, so rows split into 8-column pieces
-#ifdef DX_SERIAL_CHAINS
-    side = nullptr;
-#endif
     const split_choice gu = pick_split(a.d / CHUNK, a.d / CHUNK);
     const split_choice dn = pick_split(a.f / CHUNK, (a.shared ? a.shared_f : a.f) / CHUNK);
     if (!mixed) {
