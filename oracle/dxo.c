@@ -340,6 +340,93 @@ int dxo_select_topn(const uint64_t *S, int E, int n, int32_t *out_ids)
     return 0;
 }
 
+/* rank order of Sec. 3.5's TopN: a ranks above b when its score is larger,
+ * equal scores to the lower index */
+static int ranks_above(const uint64_t *S, int a, int b)
+{
+    return S[a] != S[b] ? S[a] > S[b] : a < b;
+}
+
+/* lowest-ranked member (in = 1) or highest-ranked outsider (in = 0) of the
+ * set flagged by `member`; -1 when there is none */
+static int extreme_of(const uint64_t *S, const uint8_t *member, int E, int in)
+{
+    int pick = -1;
+    for (int e = 0; e < E; ++e) {
+        if ((member[e] != 0) != in) continue;
+        if (pick < 0) pick = e;
+        else if (in ? ranks_above(S, pick, e) : ranks_above(S, e, pick)) pick = e;
+    }
+    return pick;
+}
+
+static void members_in_rank_order(const uint64_t *S, const uint8_t *member, int E, int32_t *out_ids)
+{
+    int n = 0;
+    for (int e = 0; e < E; ++e)
+        if (member[e]) out_ids[n++] = e;
+    for (int i = 1; i < n; ++i)
+        for (int j = i; j > 0 && ranks_above(S, out_ids[j], out_ids[j - 1]); --j) {
+            int32_t t = out_ids[j]; out_ids[j] = out_ids[j - 1]; out_ids[j - 1] = t;
+        }
+}
+
+/* Hysteresis with an additive margin (Sec. 3.5, "Hysteresis for Stability").
+ * Start from the current set H_cur (flags `cur`).  An outsider replaces the
+ * lowest-ranked member only if its score exceeds that member's by more than
+ * `margin`; the member it replaces is, by the same inequality, below the
+ * highest-ranked outsider by more than the margin.  Repeat until the best
+ * outsider no longer beats the worst member.  The capacity n is kept: a set
+ * above n first loses its lowest-ranked members, a set below n takes the
+ * highest-ranked outsiders into its empty slots (no member to displace, so
+ * no margin applies).  margin = 0 gives exactly TopN(S, n).  out_ids in rank
+ * order.  Returns 0, or 1 for a bad argument. */
+int dxo_select_hysteresis(const uint64_t *S, int E, const uint8_t *cur, int n, uint64_t margin,
+                          int32_t *out_ids)
+{
+    if (E <= 0 || n < 0 || n > E) return 1;
+    uint8_t *member = (uint8_t *)malloc((size_t)E);
+    if (!member) return 4;
+    int size = 0;
+    for (int e = 0; e < E; ++e) size += (member[e] = cur[e] != 0);
+    while (size > n) { member[extreme_of(S, member, E, 1)] = 0; --size; }
+    while (size < n) { member[extreme_of(S, member, E, 0)] = 1; ++size; }
+    for (;;) {
+        const int lo = extreme_of(S, member, E, 1), out = extreme_of(S, member, E, 0);
+        if (lo < 0 || out < 0) break;
+        const int beats = margin ? (S[out] > S[lo] && S[out] - S[lo] > margin) : ranks_above(S, out, lo);
+        if (!beats) break;
+        member[lo] = 0;
+        member[out] = 1;
+    }
+    members_in_rank_order(S, member, E, out_ids);
+    free(member);
+    return 0;
+}
+
+/* Hysteresis as a rank slack (same paragraph): a member keeps its place as
+ * long as it ranks inside the wider candidate set, the top n + slack; the
+ * places of the members that fell out of it (and empty places) go to the
+ * highest-ranked outsiders.  slack = 0 gives exactly TopN(S, n). */
+int dxo_select_rank_slack(const uint64_t *S, int E, const uint8_t *cur, int n, int slack, int32_t *out_ids)
+{
+    if (E <= 0 || n < 0 || n > E || slack < 0) return 1;
+    uint8_t *member = (uint8_t *)malloc((size_t)E);
+    if (!member) return 4;
+    int size = 0;
+    for (int e = 0; e < E; ++e) {
+        int rank = 0; /* experts that rank above e */
+        for (int o = 0; o < E; ++o) rank += o != e && ranks_above(S, o, e);
+        member[e] = cur[e] != 0 && rank < n + slack;
+        size += member[e];
+    }
+    while (size > n) { member[extreme_of(S, member, E, 1)] = 0; --size; }
+    while (size < n) { member[extreme_of(S, member, E, 0)] = 1; ++size; }
+    members_in_rank_order(S, member, E, out_ids);
+    free(member);
+    return 0;
+}
+
 /* promote = H \ H_cur, demote = H_cur \ H, each in increasing expert id
  * (Sec. 3.5).  is_hi_cur / is_hi_new are 0/1 flags of length E. */
 void dxo_transition_sets(const uint8_t *is_hi_cur, const uint8_t *is_hi_new, int E,

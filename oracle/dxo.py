@@ -198,6 +198,28 @@ def select_topn(S: np.ndarray, n: int) -> np.ndarray:
     return out
 
 
+def select_hysteresis(S: np.ndarray, cur: np.ndarray, n: int, margin: int) -> np.ndarray:
+    """Additive-margin hysteresis; `cur` = 0/1 flags of the current set; ids in rank order."""
+    S = np.ascontiguousarray(S, np.uint64)
+    cur = np.ascontiguousarray(cur, np.uint8)
+    out = np.empty(n, np.int32)
+    rc = lib().dxo_select_hysteresis(_p(S), C.c_int(S.size), _p(cur), C.c_int(n), C.c_uint64(int(margin)), _p(out))
+    if rc:
+        raise ValueError(f"dxo_select_hysteresis rc={rc}")
+    return out
+
+
+def select_rank_slack(S: np.ndarray, cur: np.ndarray, n: int, slack: int) -> np.ndarray:
+    """Rank-slack hysteresis; ids in rank order."""
+    S = np.ascontiguousarray(S, np.uint64)
+    cur = np.ascontiguousarray(cur, np.uint8)
+    out = np.empty(n, np.int32)
+    rc = lib().dxo_select_rank_slack(_p(S), C.c_int(S.size), _p(cur), C.c_int(n), C.c_int(slack), _p(out))
+    if rc:
+        raise ValueError(f"dxo_select_rank_slack rc={rc}")
+    return out
+
+
 def transition_sets(is_hi_cur: np.ndarray, is_hi_new: np.ndarray):
     cur = np.ascontiguousarray(is_hi_cur, np.uint8)
     new = np.ascontiguousarray(is_hi_new, np.uint8)

@@ -444,6 +444,94 @@ def test_transition_sets_are_set_differences(dxo):
         assert pro.tolist() == sorted(H - Hc) and dem.tolist() == sorted(Hc - H)
 
 
+def _rank_key(S):
+    return lambda e: (-int(S[e]), e)
+
+
+def test_hysteresis_worked_example(dxo):
+    """Five experts with scores 10, 9, 8, 7, 6, capacity 2, current set {2, 3}: worked by hand."""
+    S = np.array([10, 9, 8, 7, 6], np.uint64)
+    cur = np.array([0, 0, 1, 1, 0], np.uint8)
+    assert dxo.select_hysteresis(S, cur, 2, 0).tolist() == [0, 1]       # no margin: plain top-2
+    # margin 2: 10 > 7 + 2 replaces expert 3; then 9 > 8 + 2 fails and expert 2 stays
+    assert dxo.select_hysteresis(S, cur, 2, 2).tolist() == [0, 2]
+    # margin 3: 10 > 7 + 3 fails ("exceeds by a margin" is strict): nothing moves
+    assert dxo.select_hysteresis(S, cur, 2, 3).tolist() == [2, 3]
+    # rank slack 1: the top 3 hold expert 2 but not expert 3, whose place goes to expert 0
+    assert dxo.select_rank_slack(S, cur, 2, 1).tolist() == [0, 2]
+    assert dxo.select_rank_slack(S, cur, 2, 2).tolist() == [2, 3]
+    assert dxo.select_rank_slack(S, cur, 2, 0).tolist() == [0, 1]
+    # an empty place is filled without a margin; a set above capacity sheds its lowest-ranked member
+    assert dxo.select_hysteresis(S, np.array([0, 0, 0, 1, 0], np.uint8), 2, 100).tolist() == [0, 3]
+    assert dxo.select_hysteresis(S, np.array([0, 1, 1, 1, 0], np.uint8), 2, 100).tolist() == [1, 2]
+
+
+def test_hysteresis_without_margin_is_top_n(dxo):
+    g = np.random.default_rng(21)
+    for E, n in [(8, 2), (128, 32), (64, 0), (16, 16), (40, 7)]:
+        for _ in range(6):
+            S = g.integers(0, 12, E).astype(np.uint64) << np.uint64(16)      # many ties
+            cur = (g.random(E) < g.random()).astype(np.uint8)                # any size, not only n
+            ref = dxo.select_topn(S, n).tolist()
+            assert dxo.select_hysteresis(S, cur, n, 0).tolist() == ref
+            assert dxo.select_rank_slack(S, cur, n, 0).tolist() == ref
+
+
+def test_hysteresis_matches_sorted_pairing_and_its_invariants(dxo):
+    """Independent formulation: pair the i-th best outsider with the i-th worst member; the swaps are
+    the leading pairs whose score gap exceeds the margin.  Plus what the rule promises."""
+    g = np.random.default_rng(22)
+    for trial in range(60):
+        E = int(g.integers(4, 80))
+        n = int(g.integers(1, E))
+        S = g.integers(0, 50, E).astype(np.uint64)
+        margin = int(g.integers(1, 12))
+        cur_ids = g.choice(E, n, replace=False)
+        cur = np.zeros(E, np.uint8)
+        cur[cur_ids] = 1
+        got = dxo.select_hysteresis(S, cur, n, margin)
+        members = sorted(cur_ids.tolist(), key=_rank_key(S), reverse=True)       # worst first
+        outsiders = sorted(set(range(E)) - set(cur_ids.tolist()), key=_rank_key(S))  # best first
+        H = set(cur_ids.tolist())
+        for m, o in zip(members, outsiders):
+            if int(S[o]) - int(S[m]) > margin:
+                H.remove(m)
+                H.add(o)
+            else:
+                break
+        assert set(got.tolist()) == H
+        assert got.tolist() == sorted(H, key=_rank_key(S))                      # rank order
+        new, gone, rest = H - set(cur_ids.tolist()), set(cur_ids.tolist()) - H, set(range(E)) - H
+        assert len(H) == n
+        assert all(int(S[p]) - int(S[q]) > margin for p in new for q in gone)
+        assert all(int(S[o]) - int(S[m]) <= margin for o in rest for m in H)    # a fixed point
+        again = np.zeros(E, np.uint8)
+        again[got] = 1
+        assert dxo.select_hysteresis(S, again, n, margin).tolist() == got.tolist()   # idempotent
+        # a wider margin never moves more experts
+        wider = dxo.select_hysteresis(S, cur, n, margin + 5)
+        assert len(set(wider.tolist()) - set(cur_ids.tolist())) <= len(new)
+
+
+def test_rank_slack_keeps_members_inside_the_wider_set(dxo):
+    g = np.random.default_rng(23)
+    for trial in range(60):
+        E = int(g.integers(4, 80))
+        n = int(g.integers(1, E))
+        slack = int(g.integers(0, 6))
+        S = g.integers(0, 30, E).astype(np.uint64)
+        cur_ids = g.choice(E, n, replace=False).tolist()
+        cur = np.zeros(E, np.uint8)
+        cur[cur_ids] = 1
+        got = dxo.select_rank_slack(S, cur, n, slack).tolist()
+        order = sorted(range(E), key=_rank_key(S))
+        wide = set(order[:n + slack])
+        keep = [e for e in cur_ids if e in wide]
+        fill = [e for e in order if e not in keep][:n - len(keep)]
+        assert set(got) == set(keep) | set(fill)
+        assert got == sorted(got, key=_rank_key(S)) and len(got) == n
+
+
 # --------------------------------------------------- the workload recipe itself
 def test_zipf_routing_is_heavy_tailed():
     wl = WORKLOADS["C2"]
