@@ -160,6 +160,31 @@ uint64_t dx_expert_bytes(int d, int f, int group, int fmt);
 int dx_budget_capacity(uint64_t budget_bytes, int E, uint64_t b_hi, uint64_t b_lo); /* -1: infeasible */
 dx_status dx_select_topn(const uint64_t *scores, int E, int n, int32_t *out_ids);
 
+/* Hysteresis (Sec. 3.5, "Hysteresis for Stability"), pure host functions.
+ * cur: E flags (non-zero = member of the current high-precision set), n: the
+ * capacity, out_ids: host int32, capacity n, the new set in rank order (score
+ * descending, ties to the lower index).
+ *   dx_select_hysteresis: an outsider replaces the lowest-ranked member only
+ *     if its score exceeds that member's by more than margin (same units as
+ *     the scores, 2^-16 counts); repeated until the best outsider no longer
+ *     does.  Empty places (fewer than n members) are filled with the best
+ *     outsiders, a set above n first sheds its lowest-ranked members.
+ *   dx_select_rank_slack: a member keeps its place while it ranks inside the
+ *     top n + slack; freed and empty places go to the best outsiders.
+ * margin = 0 / slack = 0 give exactly dx_select_topn.  DX_ERR_INVALID for a
+ * null pointer, n outside 0..E or a negative slack. */
+dx_status dx_select_hysteresis(const uint64_t *scores, int E, const uint8_t *cur, int n, uint64_t margin,
+                               int32_t *out_ids);
+dx_status dx_select_rank_slack(const uint64_t *scores, int E, const uint8_t *cur, int n, int slack,
+                               int32_t *out_ids);
+
+/* dx_select_resident with hysteresis against the layer's current set (the
+ * experts that are Resident-Hi or Promoting): n from the budget as above,
+ * then dx_select_rank_slack if rank_slack > 0, else dx_select_hysteresis
+ * with margin_q16. */
+dx_status dx_select_resident_stable(dx_ctx *ctx, int layer, uint64_t budget_bytes, uint64_t margin_q16,
+                                    int rank_slack, int32_t *out_ids, int32_t *out_n);
+
 /* Candidates for residency change (Sec. 3.5): promote = H \ H_cur,
  * demote = H_cur \ H, where H_cur is the set of experts of `layer` that are
  * Resident-Hi or Promoting.  Outputs host int32, capacity E each, ascending. */

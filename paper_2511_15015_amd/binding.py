@@ -23,6 +23,7 @@ EXPORTS = [
     "dx_create", "dx_destroy", "dx_last_error", "dx_status_str",
     "dx_route", "dx_moe_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
+    "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
     "dx_quantize_expert", "dx_swap_handle",
     "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats",
     "dx_set_profiling", "dx_get_profile",
@@ -99,6 +100,9 @@ def load():
     L.dx_budget_capacity.argtypes = [u64, i32, u64, u64]
     L.dx_budget_capacity.restype = i32
     L.dx_select_topn.argtypes = [vp, i32, i32, vp]
+    L.dx_select_hysteresis.argtypes = [vp, i32, vp, i32, u64, vp]
+    L.dx_select_rank_slack.argtypes = [vp, i32, vp, i32, i32, vp]
+    L.dx_select_resident_stable.argtypes = [vp, i32, u64, u64, i32, vp, C.POINTER(C.c_int32)]
     L.dx_plan_transitions.argtypes = [vp, i32, vp, i32, vp, C.POINTER(C.c_int32), vp, C.POINTER(C.c_int32)]
     L.dx_quantize_expert.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     L.dx_swap_handle.argtypes = [vp, i32, i32, C.POINTER(DxHandle), vp]
@@ -152,6 +156,26 @@ def dx_select_topn(scores: np.ndarray, n: int) -> np.ndarray:
     s = load().dx_select_topn(scores.ctypes.data, scores.size, n, out.ctypes.data)
     if s:
         raise DxError(s, "dx_select_topn", "invalid argument")
+    return out
+
+
+def dx_select_hysteresis(scores: np.ndarray, cur: np.ndarray, n: int, margin: int) -> np.ndarray:
+    scores = np.ascontiguousarray(scores, np.uint64)
+    cur = np.ascontiguousarray(cur, np.uint8)
+    out = np.empty(max(n, 0), np.int32)
+    s = load().dx_select_hysteresis(scores.ctypes.data, scores.size, cur.ctypes.data, n, int(margin), out.ctypes.data)
+    if s:
+        raise DxError(s, "dx_select_hysteresis", "invalid argument")
+    return out
+
+
+def dx_select_rank_slack(scores: np.ndarray, cur: np.ndarray, n: int, slack: int) -> np.ndarray:
+    scores = np.ascontiguousarray(scores, np.uint64)
+    cur = np.ascontiguousarray(cur, np.uint8)
+    out = np.empty(max(n, 0), np.int32)
+    s = load().dx_select_rank_slack(scores.ctypes.data, scores.size, cur.ctypes.data, n, slack, out.ctypes.data)
+    if s:
+        raise DxError(s, "dx_select_rank_slack", "invalid argument")
     return out
 
 
@@ -210,6 +234,13 @@ class Context:
         n = C.c_int32(0)
         self._chk(self.lib.dx_select_resident(self.h, layer, budget_bytes, ids.ctypes.data, C.byref(n)),
                   "dx_select_resident")
+        return ids[:n.value].copy()
+
+    def dx_select_resident_stable(self, layer, budget_bytes, margin_q16=0, rank_slack=0):
+        ids = np.empty(self.cfg.E, np.int32)
+        n = C.c_int32(0)
+        self._chk(self.lib.dx_select_resident_stable(self.h, layer, budget_bytes, int(margin_q16), rank_slack,
+                                                     ids.ctypes.data, C.byref(n)), "dx_select_resident_stable")
         return ids[:n.value].copy()
 
     def dx_plan_transitions(self, layer, target_ids):

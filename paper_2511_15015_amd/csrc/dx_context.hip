@@ -147,6 +147,78 @@ extern "C" dx_status dx_select_topn(const uint64_t *scores, int E, int n, int32_
     return DX_OK;
 }
 
+namespace {
+
+// members (best first) and outsiders (best first) of the flagged set, brought to exactly n members:
+// a larger set sheds its lowest-ranked members, a smaller one takes the best outsiders
+void split_by_rank(const uint64_t *scores, int E, const uint8_t *cur, int n, std::vector<int32_t> &members,
+                   std::vector<int32_t> &outsiders)
+{
+    auto above = [&](int32_t a, int32_t b) { return scores[a] != scores[b] ? scores[a] > scores[b] : a < b; };
+    std::vector<int32_t> order(E);
+    for (int e = 0; e < E; ++e) order[e] = e;
+    std::sort(order.begin(), order.end(), above);
+    members.clear();
+    outsiders.clear();
+    for (int32_t e : order) (cur[e] ? members : outsiders).push_back(e);
+    if ((int)members.size() > n) {
+        outsiders.insert(outsiders.end(), members.begin() + n, members.end());
+        members.resize(n);
+        std::sort(outsiders.begin(), outsiders.end(), above);
+    } else if ((int)members.size() < n) {
+        const size_t take = n - members.size();
+        members.insert(members.end(), outsiders.begin(), outsiders.begin() + take);
+        outsiders.erase(outsiders.begin(), outsiders.begin() + take);
+        std::sort(members.begin(), members.end(), above);
+    }
+}
+
+void emit_in_rank_order(const uint64_t *scores, std::vector<int32_t> &members, int32_t *out_ids)
+{
+    std::sort(members.begin(), members.end(),
+              [&](int32_t a, int32_t b) { return scores[a] != scores[b] ? scores[a] > scores[b] : a < b; });
+    for (size_t i = 0; i < members.size(); ++i) out_ids[i] = members[i];
+}
+
+} // namespace
+
+extern "C" dx_status dx_select_hysteresis(const uint64_t *scores, int E, const uint8_t *cur, int n, uint64_t margin,
+                                          int32_t *out_ids)
+{
+    if (!scores || !cur || E <= 0 || n < 0 || n > E || (n > 0 && !out_ids)) return DX_ERR_INVALID;
+    std::vector<int32_t> members, outsiders;
+    split_by_rank(scores, E, cur, n, members, outsiders);
+    // i-th worst member against i-th best outsider: the exchanges are a prefix of these pairs
+    for (size_t i = 0; i < members.size() && i < outsiders.size(); ++i) {
+        int32_t &m = members[members.size() - 1 - i];
+        const int32_t o = outsiders[i];
+        const bool beats = margin ? (scores[o] > scores[m] && scores[o] - scores[m] > margin)
+                                  : (scores[o] != scores[m] ? scores[o] > scores[m] : o < m);
+        if (!beats) break;
+        m = o;
+    }
+    emit_in_rank_order(scores, members, out_ids);
+    return DX_OK;
+}
+
+extern "C" dx_status dx_select_rank_slack(const uint64_t *scores, int E, const uint8_t *cur, int n, int slack,
+                                          int32_t *out_ids)
+{
+    if (!scores || !cur || E <= 0 || n < 0 || n > E || slack < 0 || (n > 0 && !out_ids)) return DX_ERR_INVALID;
+    // members outside the top n + slack lose their flag, then the set is brought back to n
+    std::vector<int32_t> order(E);
+    for (int e = 0; e < E; ++e) order[e] = e;
+    std::sort(order.begin(), order.end(),
+              [&](int32_t a, int32_t b) { return scores[a] != scores[b] ? scores[a] > scores[b] : a < b; });
+    std::vector<uint8_t> keep(E, 0);
+    const long wide = std::min<long>((long)n + slack, E);
+    for (long r = 0; r < wide; ++r) keep[order[r]] = cur[order[r]] != 0;
+    std::vector<int32_t> members, outsiders;
+    split_by_rank(scores, E, keep.data(), n, members, outsiders);
+    emit_in_rank_order(scores, members, out_ids);
+    return DX_OK;
+}
+
 extern "C" const char *dx_status_str(dx_status s)
 {
     switch (s) {
@@ -400,6 +472,32 @@ extern "C" dx_status dx_select_resident(dx_ctx *c, int layer, uint64_t budget_by
                 (unsigned long long)budget_bytes, (unsigned long long)(c->cfg.E * c->b_lo));
     dx_status s = dx_select_topn(c->scores.data() + (size_t)layer * c->cfg.E, c->cfg.E, n, out_ids);
     if (s != DX_OK) DX_FAIL(c, s, "dx_select_resident: selection failed");
+    *out_n = n;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_select_resident_stable(dx_ctx *c, int layer, uint64_t budget_bytes, uint64_t margin_q16,
+                                               int rank_slack, int32_t *out_ids, int32_t *out_n)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!out_n) DX_FAIL(c, DX_ERR_INVALID, "dx_select_resident_stable: null out_n");
+    *out_n = 0;
+    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_select_resident_stable: layer %d out of range", layer);
+    if (!out_ids || rank_slack < 0) DX_FAIL(c, DX_ERR_INVALID, "dx_select_resident_stable: bad argument");
+    const int E = c->cfg.E;
+    const int n = dx_budget_capacity(budget_bytes, E, c->b_hi, c->b_lo);
+    if (n < 0)
+        DX_FAIL(c, DX_ERR_BUDGET, "dx_select_resident_stable: budget %llu B is below the all-int4 layer (%llu B)",
+                (unsigned long long)budget_bytes, (unsigned long long)(E * c->b_lo));
+    std::vector<uint8_t> cur(E);
+    for (int e = 0; e < E; ++e) {
+        const uint8_t st = c->entries[entry_index(c, layer, e)].state;
+        cur[e] = st == DX_STATE_RESIDENT_HI || st == DX_STATE_PROMOTING;
+    }
+    const uint64_t *S = c->scores.data() + (size_t)layer * E;
+    const dx_status s = rank_slack > 0 ? dx_select_rank_slack(S, E, cur.data(), n, rank_slack, out_ids)
+                                       : dx_select_hysteresis(S, E, cur.data(), n, margin_q16, out_ids);
+    if (s != DX_OK) DX_FAIL(c, s, "dx_select_resident_stable: selection failed");
     *out_n = n;
     return DX_OK;
 }

@@ -193,3 +193,74 @@ def test_c5_drift_full_shape_few_layers(B, LY, dxo):
     for layer in range(L):
         check(layer, step, n_windows - 1)
     ctx.close()
+
+
+def test_c5_churn_with_ema_and_hysteresis(B, LY, dxo):
+    """Policy over the drifting 30B-shaped router traces (routing and counting on the GPU, no expert
+    weights needed): EMA scores and the selections with hysteresis are bit-exact against the oracle
+    in every window; promotions per policy are counted, and the share of the next window's routed
+    pairs that lands on the selected set shows what the steadier sets cost."""
+    wl = WORKLOADS["C5"]
+    L, window, n_windows, redraw = 4, 16, 12, 4
+    n = wl.n_hi
+    policies = {                                                     # name: (alpha_q16, margin in counts, rank slack)
+        "alpha0": (0, 0, 0), "ema": (32768, 0, 0), "ema+margin2": (32768, 2, 0), "ema+margin8": (32768, 8, 0),
+        "ema+slack4": (32768, 0, 4), "ema+slack8": (32768, 0, 8),
+    }
+    ctxs = {a: B.Context(L=L, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T,
+                         alpha_q16=a, route_updates_hotness=True, window_steps=window)
+            for a in sorted({p[0] for p in policies.values()})}
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    S_ref = {a: np.zeros((L, wl.E), np.uint64) for a in ctxs}
+    cur = {name: np.zeros((L, wl.E), np.uint8) for name in policies}
+    for name in policies:
+        cur[name][:, :n] = 1                                         # the all-zero-score selection
+    promotions = {name: 0 for name in policies}
+    covered = {name: 0 for name in policies}
+    total_pairs = 0
+    step = 0
+    for wdw in range(n_windows):
+        epoch = wdw // redraw
+        c = np.zeros((L, wl.E), np.int64)
+        for s in range(window):
+            for layer in range(L):
+                _, lg = W.layer_inputs(wl, 0, layer, step, epoch)
+                lgd = torch.from_numpy(lg).cuda()
+                for ctx in ctxs.values():
+                    rb.route(ctx, layer, lgd)
+                _, _, counts, _, _ = dxo.route(lg, wl.k)
+                dxo.hotness_update(c[layer], counts)
+            step += 1
+        if wdw > 0:                                                  # what the sets chosen a window ago caught
+            total_pairs += int(c.sum())
+            for name in policies:
+                covered[name] += int((c * cur[name]).sum())
+        for a, ctx in ctxs.items():
+            S_gpu = ctx.dx_window_end()
+            for layer in range(L):
+                cl = c[layer].copy()
+                dxo.window_end(S_ref[a][layer], cl, a)
+            assert np.array_equal(S_gpu, S_ref[a]), (wdw, a)
+        for name, (a, margin, slack) in policies.items():
+            for layer in range(L):
+                S = S_ref[a][layer]
+                if slack:
+                    got = B.dx_select_rank_slack(S, cur[name][layer], n, slack)
+                    ref = dxo.select_rank_slack(S, cur[name][layer], n, slack)
+                else:
+                    got = B.dx_select_hysteresis(S, cur[name][layer], n, margin << 16)
+                    ref = dxo.select_hysteresis(S, cur[name][layer], n, margin << 16)
+                assert np.array_equal(got, ref), (wdw, name, layer)
+                new = np.zeros(wl.E, np.uint8)
+                new[got] = 1
+                pro, dem = dxo.transition_sets(cur[name][layer], new)
+                assert len(pro) == len(dem)
+                promotions[name] += len(pro)
+                cur[name][layer] = new
+    for name in policies:
+        print(f"  C5 policy {name:12s}: {promotions[name]:5d} promotions over {n_windows} windows x {L} layers, "
+              f"{100.0 * covered[name] / total_pairs:5.1f} % of routed pairs on the selected set", flush=True)
+    assert promotions["ema+margin2"] <= promotions["ema"] and promotions["ema+margin8"] <= promotions["ema+margin2"]
+    assert promotions["ema+slack8"] <= promotions["ema+slack4"] <= promotions["ema"]
+    for ctx in ctxs.values():
+        ctx.close()

@@ -54,6 +54,28 @@ def test_host_rules_agree_with_oracle(B, dxo):
         B.dx_select_topn(np.zeros(4, np.uint64), 5)
 
 
+def test_hysteresis_rules_agree_with_oracle(B, dxo):
+    """The library's selection with hysteresis (its own implementation) against the oracle's, on
+    random scores with many ties, current sets of any size, the whole range of margins and slacks."""
+    g = np.random.default_rng(5)
+    for trial in range(300):
+        E = int(g.integers(1, 140))
+        n = int(g.integers(0, E + 1))
+        S = g.integers(0, 25, E).astype(np.uint64) << np.uint64(14)
+        cur = (g.random(E) < g.random()).astype(np.uint8)
+        if trial % 3 == 0:                                   # a current set of exactly n members
+            cur[:] = 0
+            cur[g.choice(E, n, replace=False)] = 1
+        margin = int(g.integers(0, 6)) << 14 if trial % 4 else 0
+        slack = int(g.integers(0, 8))
+        assert np.array_equal(B.dx_select_hysteresis(S, cur, n, margin), dxo.select_hysteresis(S, cur, n, margin))
+        assert np.array_equal(B.dx_select_rank_slack(S, cur, n, slack), dxo.select_rank_slack(S, cur, n, slack))
+    with pytest.raises(B.DxError):
+        B.dx_select_hysteresis(np.zeros(4, np.uint64), np.zeros(4, np.uint8), 5, 0)
+    with pytest.raises(B.DxError):
+        B.dx_select_rank_slack(np.zeros(4, np.uint64), np.zeros(4, np.uint8), 2, -1)
+
+
 def test_no_fallback_when_library_is_missing(B, monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libdynaexq.so")
