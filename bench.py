@@ -34,8 +34,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="C2", choices=["C2", "C3"],
-                    help="C2: decode T=32 (the headline metric); C3: the same layer in prefill, T=4096")
+    ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C5"],
+                    help="C2: decode T=32 (the headline metric); C3: the same layer in prefill, T=4096; "
+                         "C5: a decode stack whose hot set drifts, with live promotions and demotions")
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets to rotate over")
     ap.add_argument("--window", type=int, default=None, help="routing-only warm-up steps per layer for hotness")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -43,10 +44,137 @@ def parse():
     return ap.parse_args()
 
 
+def run_c5(args):
+    """Decode stack under hot-set drift (30B-shaped layers, Zipf permutation re-drawn every two
+    windows): every step runs route + forward of all layers and then one worker step of the transition
+    queue; at each window end the EMA scores pick the next resident sets.  Reports stack tokens/s over
+    all steps, per-step time percentiles against a run of the same length without drift, and the
+    migration traffic."""
+    import numpy as np
+    import torch
+
+    from paper_2511_15015_amd import binding as B
+    from paper_2511_15015_amd import layer as LY
+    from paper_2511_15015_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    wl = W.WORKLOADS["C5"]
+    L, T, E, k, d, f, n = args.layers, wl.T, wl.E, wl.k, wl.d, wl.f, wl.n_hi
+    window, n_windows, redraw, n_batches = args.window, args.steps // args.window, 2, 16
+    b_hi = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_BF16)
+    b_lo = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_INT4G)
+    layer_budget, spare = n * b_hi + (E - n) * b_lo, 16
+    stream = torch.cuda.Stream()
+    results = {}
+    with torch.cuda.stream(stream):
+        ctx = B.Context(L=L, E=E, d=d, f=f, top_k=k, group=wl.group, max_tokens=T, window_steps=window,
+                        alpha_q16=32768, budget_bytes=L * layer_budget, transient_bytes=spare * (b_hi + b_lo),
+                        route_updates_hotness=True, stream=stream.cuda_stream)
+        ctx.dx_pools_create(L * n + spare, L * (E - n) + spare)
+        ctx.dx_transitions_limits(8)
+        pinned = []
+        for layer in range(L):
+            dev = W.device_masters(wl, args.seed, layer)
+            host = [torch.empty(m.shape, dtype=m.dtype).pin_memory() for m in dev]
+            for h, m in zip(host, dev):
+                h.copy_(m)
+            pinned.append(host)
+            for e in range(E):
+                ctx.dx_expert_install(layer, e, B.DX_FMT_BF16 if e < n else B.DX_FMT_INT4G, *(m[e] for m in dev),
+                                      src_on_device=True)
+                ctx.dx_register_host_master(layer, e, *(h[e] for h in host))
+            del dev
+        rb = LY.RoutingBuffers(T, E, k)
+        y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+        n_epochs = (n_windows + redraw - 1) // redraw
+        xs = [[None] * n_batches for _ in range(L)]
+        lgs = [[[None] * n_batches for _ in range(L)] for _ in range(n_epochs)]
+        for layer in range(L):
+            for b in range(n_batches):
+                xb = W.activations(wl, args.seed, layer, b)
+                xs[layer][b] = LY.bits_to_device(xb)
+                wr = W.router_matrix(wl, args.seed, layer)
+                for ep in range(n_epochs):
+                    lgs[ep][layer][b] = torch.from_numpy(W.router_logits(wl, xb, wr, args.seed, layer, ep)).cuda()
+        lib, h = ctx.lib, ctx.h
+        p_ids, p_w, p_counts, p_off, p_perm = (t.data_ptr() for t in (rb.ids, rb.w, rb.counts, rb.offsets, rb.perm))
+
+        def run(drift):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_windows * window + 1)]
+            st0 = ctx.dx_get_stats()
+            settle = []                      # steps from a re-draw until the queue and the migration stream are empty
+            since_redraw, armed = None, False
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev[0].record(stream)
+            step = 0
+            for wdw in range(n_windows):
+                ep = wdw // redraw if drift else 0
+                if drift and wdw % redraw == 0 and wdw > 0:
+                    since_redraw, armed = 0, False
+                for s_ in range(window):
+                    b = step % n_batches
+                    for layer in range(L):
+                        if lib.dx_route(h, layer, lgs[ep][layer][b].data_ptr(), T, p_ids, p_w, p_counts, p_off, p_perm) or \
+                           lib.dx_moe_forward(h, layer, None, xs[layer][b].data_ptr(), T, p_ids, p_w, p_off, p_perm,
+                                              y.data_ptr()):
+                            raise RuntimeError(lib.dx_last_error(h).decode())
+                    step += 1
+                    ev[step].record(stream)
+                    stream.synchronize()       # a decode loop reads its tokens here; keeps host and GPU in step
+                    issued, published, queued = ctx.dx_transitions_pump(4)
+                    if since_redraw is not None:
+                        since_redraw += 1
+                        if armed and queued == 0 and ctx.dx_get_stats()["in_flight"] == 0:
+                            settle.append(since_redraw)
+                            since_redraw = None
+                ctx.dx_window_end()
+                for layer in range(L):
+                    target = ctx.dx_select_resident_stable(layer, layer_budget, margin_q16=2 << 16)
+                    pro, dem = ctx.dx_plan_transitions(layer, target)
+                    ctx.dx_transitions_enqueue(layer, pro, dem)
+                armed = True
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            ctx.dx_migrate_poll(wait=True)
+            ms = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(len(ev) - 1)])
+            st1 = ctx.dx_get_stats()
+            return dict(wall_s=wall, steps=len(ms), p50_ms=float(np.percentile(ms, 50)), p99_ms=float(np.percentile(ms, 99)),
+                        max_ms=float(ms.max()), mean_ms=float(ms.mean()),
+                        promotions=st1["promotions_published"] - st0["promotions_published"],
+                        demotions=st1["demotions_published"] - st0["demotions_published"],
+                        h2d_bytes_per_step=(st1["h2d_bytes"] - st0["h2d_bytes"]) / len(ms),
+                        quantize_bytes_per_step=(st1["quantize_read_bytes"] + st1["quantize_write_bytes"]
+                                                 - st0["quantize_read_bytes"] - st0["quantize_write_bytes"]) / len(ms),
+                        steps_to_settle_after_redraw=settle, peak_in_flight=st1["peak_in_flight"],
+                        peak_reserved_bytes=st1["peak_reserved_bytes"])
+
+        run(False)                                                    # warm-up: reaches the epoch-0 resident sets
+        results["steady"] = run(False)
+        results["drift"] = run(True)
+        budget_ok = results["drift"]["peak_reserved_bytes"] <= L * layer_budget + spare * (b_hi + b_lo)
+    ctx.close()
+    dr = results["drift"]
+    out = {
+        "metric": "MoE-stack tokens/s (decode B=32) under hot-set drift with live promotion/demotion",
+        "value": T * dr["steps"] / dr["wall_s"], "unit": "tokens/s", "n_gpus": 1, "steps": dr["steps"], "warmup": dr["steps"],
+        "ms_per_step": dr["wall_s"] * 1e3 / dr["steps"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"C5: {L} 30B-A3B-shaped MoE layers per step (of the model's 48; pinned host masters "
+                               f"for all of them are {48 * E * b_hi / 2**30:.0f} GiB), decode T={T}, Zipf(s={wl.zipf_s}) permutation "
+                               f"re-drawn every {redraw} windows of {window} steps, EMA alpha 0.5, margin 2 counts, "
+                               f"{n} bf16 experts per layer, at most 8 transitions in flight, 4 issued per step",
+                   "step": "route + forward of every layer, stream synchronize, then one dx_transitions_pump"},
+        "drift": dr, "steady": results["steady"], "budget_respected": bool(budget_ok),
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     defaults = {"C2": dict(steps=960, warmup=96, layers=48, window=64),
-                "C3": dict(steps=48, warmup=8, layers=4, window=2)}[args.workload]
+                "C3": dict(steps=48, warmup=8, layers=4, window=2),
+                "C5": dict(steps=384, warmup=0, layers=8, window=32)}[args.workload]
     for key, val in defaults.items():
         if getattr(args, key) is None:
             setattr(args, key, val)
@@ -64,6 +192,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "C5":
+        return run_c5(args)
     torch.cuda.set_device(0)
     wl = W.WORKLOADS[args.workload]
     L, T, E, k, d, f = args.layers, wl.T, wl.E, wl.k, wl.d, wl.f

@@ -96,6 +96,9 @@ typedef struct {
     uint64_t reserved_bytes;       /* budget tracker: bytes currently reserved */
     uint64_t peak_reserved_bytes;
     uint64_t deferred;             /* transitions refused by admission control */
+    uint64_t in_flight;            /* transitions issued and not yet published */
+    uint64_t peak_in_flight;
+    uint64_t queued;               /* requests waiting in the update queue */
 } dx_stats;
 
 /* ------------------------------------------------------------------ context */
@@ -268,6 +271,40 @@ dx_status dx_demote_async(dx_ctx *ctx, int layer, int expert);
  * to its pool and is reused only after the compute stream has passed the
  * swap.  Call between forward passes. */
 dx_status dx_migrate_poll(dx_ctx *ctx, int wait, int *n_published);
+
+/* ---------------------------- transition queue and worker step (Sec. 3.4) */
+/* "Asynchronous queues and backpressure" as a deterministic step function the
+ * serving loop calls between forward passes (no thread of its own).
+ *
+ * dx_register_host_master: where the pre-packed bf16 master of (layer,
+ *   expert) lives in pinned host memory (gate [f,d], up [f,d], down [d,f]);
+ *   the pointers must stay valid while the context lives.  Queued promotions
+ *   copy from there.
+ * dx_transitions_limits: at most max_inflight transitions between issue and
+ *   publication (0 = no bound): bounds the migration traffic that competes
+ *   with the forward pass.
+ * dx_transitions_enqueue: append requests to the update queue, demotions
+ *   first, then promotions (ids of `layer`, host int32).  A request cancels a
+ *   queued request for the same expert in the other direction; duplicates are
+ *   dropped.
+ * dx_transitions_pump: (1) publish every completed transition
+ *   (dx_migrate_poll without waiting); (2) walk the queue in order and issue
+ *   up to max_issue requests, each only if its admission check passes now: a
+ *   promotion needs a free place among the layer's high-precision experts,
+ *   b_hi bytes under budget + transient and a free pool_hi block; a demotion
+ *   needs b_lo bytes and a free pool_lo block.  A request that does not pass
+ *   stays queued (backpressure) and later requests are considered, so that
+ *   when capacity is tight the demotions that free it overtake the
+ *   promotions that wait for it.  Requests whose expert is already in (or on
+ *   its way to) the requested precision are dropped; requests whose expert
+ *   is in the opposite transition wait.  Outputs may be NULL. */
+dx_status dx_register_host_master(dx_ctx *ctx, int layer, int expert,
+                                  const void *pinned_gate, const void *pinned_up, const void *pinned_down);
+dx_status dx_transitions_limits(dx_ctx *ctx, int max_inflight);
+dx_status dx_transitions_enqueue(dx_ctx *ctx, int layer, const int32_t *promote, int n_promote,
+                                 const int32_t *demote, int n_demote);
+dx_status dx_transitions_pump(dx_ctx *ctx, int max_issue, int32_t *n_issued, int32_t *n_published,
+                              int32_t *n_queued);
 
 #ifdef __cplusplus
 }

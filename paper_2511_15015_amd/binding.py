@@ -24,6 +24,7 @@ EXPORTS = [
     "dx_route", "dx_moe_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
     "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
+    "dx_register_host_master", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
     "dx_quantize_expert", "dx_swap_handle",
     "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats",
     "dx_set_profiling", "dx_get_profile",
@@ -49,7 +50,7 @@ class DxStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "promotions_issued", "promotions_published", "demotions_issued", "demotions_published",
         "h2d_bytes", "quantize_read_bytes", "quantize_write_bytes", "reserved_bytes",
-        "peak_reserved_bytes", "deferred")]
+        "peak_reserved_bytes", "deferred", "in_flight", "peak_in_flight", "queued")]
 
     def asdict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -116,6 +117,10 @@ def load():
     L.dx_set_profiling.argtypes = [vp, i32]
     L.dx_get_profile.argtypes = [vp, C.POINTER(DxProfile)]
     L.dx_pools_create.argtypes = [vp, i32, i32]
+    L.dx_register_host_master.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.dx_transitions_limits.argtypes = [vp, i32]
+    L.dx_transitions_enqueue.argtypes = [vp, i32, vp, i32, vp, i32]
+    L.dx_transitions_pump.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     L.dx_expert_install.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32]
     L.dx_promote_async.argtypes = [vp, i32, i32, vp, vp, vp]
     L.dx_demote_async.argtypes = [vp, i32, i32]
@@ -311,6 +316,26 @@ class Context:
 
     def dx_demote_async(self, layer, expert):
         self._chk(self.lib.dx_demote_async(self.h, layer, expert), "dx_demote_async")
+
+    def dx_register_host_master(self, layer, expert, pinned_gate, pinned_up, pinned_down):
+        self._chk(self.lib.dx_register_host_master(self.h, layer, expert, _ptr(pinned_gate), _ptr(pinned_up),
+                                                   _ptr(pinned_down)), "dx_register_host_master")
+
+    def dx_transitions_limits(self, max_inflight):
+        self._chk(self.lib.dx_transitions_limits(self.h, max_inflight), "dx_transitions_limits")
+
+    def dx_transitions_enqueue(self, layer, promote, demote):
+        pro = np.ascontiguousarray(promote, np.int32)
+        dem = np.ascontiguousarray(demote, np.int32)
+        self._chk(self.lib.dx_transitions_enqueue(self.h, layer, pro.ctypes.data, pro.size, dem.ctypes.data, dem.size),
+                  "dx_transitions_enqueue")
+
+    def dx_transitions_pump(self, max_issue):
+        """-> (issued, published, still queued)"""
+        a, b, q = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        self._chk(self.lib.dx_transitions_pump(self.h, max_issue, C.byref(a), C.byref(b), C.byref(q)),
+                  "dx_transitions_pump")
+        return a.value, b.value, q.value
 
     def dx_migrate_poll(self, wait=False) -> int:
         n = C.c_int(0)

@@ -610,6 +610,8 @@ extern "C" dx_status dx_get_states(dx_ctx *c, uint8_t *out)
 extern "C" dx_status dx_get_stats(dx_ctx *c, dx_stats *out)
 {
     if (!c || !out) return DX_ERR_INVALID;
+    c->stats.in_flight = c->inflight.size();
+    c->stats.queued = c->update_q.size();
     *out = c->stats;
     return DX_OK;
 }
@@ -789,6 +791,7 @@ extern "C" dx_status dx_promote_async(dx_ctx *c, int layer, int expert, const vo
     en.next_block = block;
     c->hi_count[layer]++;
     c->inflight.push_back({layer, expert, true, done});
+    c->stats.peak_in_flight = std::max<uint64_t>(c->stats.peak_in_flight, c->inflight.size());
     c->stats.promotions_issued++;
     c->stats.h2d_bytes += 3 * mat;
     return DX_OK;
@@ -842,6 +845,7 @@ extern "C" dx_status dx_demote_async(dx_ctx *c, int layer, int expert)
     en.state = DX_STATE_DEMOTING;
     en.next_block = block;
     c->inflight.push_back({layer, expert, false, done});
+    c->stats.peak_in_flight = std::max<uint64_t>(c->stats.peak_in_flight, c->inflight.size());
     c->stats.demotions_issued++;
     c->stats.quantize_read_bytes += c->b_hi;
     c->stats.quantize_write_bytes += c->b_lo;
@@ -892,5 +896,120 @@ extern "C" dx_status dx_migrate_poll(dx_ctx *c, int wait, int *n_published)
         ++n;
     }
     if (n_published) *n_published = n;
+    return DX_OK;
+}
+
+// ------------------------------------------------ transition queue and worker step
+extern "C" dx_status dx_register_host_master(dx_ctx *c, int layer, int expert, const void *pg, const void *pu,
+                                             const void *pd)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, false) || !pg || !pu || !pd)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_register_host_master: bad argument");
+    if (c->host_master.empty()) c->host_master.assign((size_t)c->cfg.L * c->cfg.E, {nullptr, nullptr, nullptr});
+    c->host_master[(size_t)layer * c->cfg.E + expert] = {pg, pu, pd};
+    return DX_OK;
+}
+
+extern "C" dx_status dx_transitions_limits(dx_ctx *c, int max_inflight)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (max_inflight < 0) DX_FAIL(c, DX_ERR_INVALID, "dx_transitions_limits: negative bound");
+    c->max_inflight = max_inflight;
+    return DX_OK;
+}
+
+extern "C" dx_status dx_transitions_enqueue(dx_ctx *c, int layer, const int32_t *promote, int n_promote,
+                                            const int32_t *demote, int n_demote)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer) || n_promote < 0 || n_demote < 0 || (n_promote && !promote) || (n_demote && !demote))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_transitions_enqueue: bad argument");
+    for (int pass = 0; pass < 2; ++pass) {
+        const int32_t *ids = pass ? promote : demote;
+        const int n = pass ? n_promote : n_demote;
+        for (int i = 0; i < n; ++i)
+            if (!valid_expert(c, ids[i], false))
+                DX_FAIL(c, DX_ERR_INVALID, "dx_transitions_enqueue: expert %d out of range", ids[i]);
+    }
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool is_promote = pass == 1;
+        const int32_t *ids = is_promote ? promote : demote;
+        const int n = is_promote ? n_promote : n_demote;
+        for (int i = 0; i < n; ++i) {
+            bool settled = false;
+            for (auto it = c->update_q.begin(); it != c->update_q.end(); ++it) {
+                if (it->layer != layer || it->expert != ids[i]) continue;
+                if (it->promote != is_promote) c->update_q.erase(it); // the newer target wins: both cancel
+                settled = true;                                      // (or the same request is already queued)
+                break;
+            }
+            if (!settled) c->update_q.push_back({layer, ids[i], is_promote});
+        }
+    }
+    return DX_OK;
+}
+
+extern "C" dx_status dx_transitions_pump(dx_ctx *c, int max_issue, int32_t *n_issued, int32_t *n_published,
+                                         int32_t *n_queued)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (n_issued) *n_issued = 0;
+    if (n_published) *n_published = 0;
+    if (n_queued) *n_queued = (int32_t)c->update_q.size();
+    if (max_issue < 0) DX_FAIL(c, DX_ERR_INVALID, "dx_transitions_pump: negative max_issue");
+    int published = 0;
+    dx_status s = dx_migrate_poll(c, 0, &published);
+    if (s != DX_OK) return s;
+    if (n_published) *n_published = published;
+    const dx_config &g = c->cfg;
+    const uint64_t cap = g.budget_bytes ? g.budget_bytes + g.transient_bytes : ~0ull;
+    int issued = 0;
+    for (auto it = c->update_q.begin(); it != c->update_q.end();) {
+        if (issued >= max_issue || (c->max_inflight && (int)c->inflight.size() >= c->max_inflight)) break;
+        const dx_request r = *it;
+        const uint8_t st = c->entries[entry_index(c, r.layer, r.expert)].state;
+        const uint8_t there = r.promote ? DX_STATE_RESIDENT_HI : DX_STATE_RESIDENT_LO;
+        const uint8_t going = r.promote ? DX_STATE_PROMOTING : DX_STATE_DEMOTING;
+        const uint8_t ready = r.promote ? DX_STATE_RESIDENT_LO : DX_STATE_RESIDENT_HI;
+        if (st == there || st == going || st == DX_STATE_EMPTY) { // nothing to do (any more)
+            it = c->update_q.erase(it);
+            continue;
+        }
+        if (st != ready) { // in the opposite transition: wait for its publication
+            ++it;
+            continue;
+        }
+        // admission, checked here so that a refusal is backpressure, not an error
+        bool admit;
+        if (r.promote) {
+            admit = !(g.budget_bytes && c->hi_count[r.layer] >= c->n_hi_cap) && c->reserved + c->b_hi <= cap &&
+                    !c->pool_hi.free_list.empty();
+        } else {
+            admit = c->reserved + c->b_lo <= cap && !c->pool_lo.free_list.empty();
+        }
+        if (!admit) {
+            c->stats.deferred++;
+            ++it;
+            continue;
+        }
+        if (r.promote) {
+            if (c->host_master.empty() || !c->host_master[(size_t)r.layer * g.E + r.expert][0])
+                DX_FAIL(c, DX_ERR_INVALID, "dx_transitions_pump: no host master registered for (%d,%d)", r.layer, r.expert);
+            const auto &m = c->host_master[(size_t)r.layer * g.E + r.expert];
+            s = dx_promote_async(c, r.layer, r.expert, m[0], m[1], m[2]);
+        } else {
+            s = dx_demote_async(c, r.layer, r.expert);
+        }
+        if (s == DX_ERR_BUDGET || s == DX_ERR_NOMEM) { // lost a race with nothing: treat as backpressure
+            ++it;
+            continue;
+        }
+        if (s != DX_OK) return s;
+        it = c->update_q.erase(it);
+        ++issued;
+    }
+    if (n_issued) *n_issued = issued;
+    if (n_queued) *n_queued = (int32_t)c->update_q.size();
     return DX_OK;
 }

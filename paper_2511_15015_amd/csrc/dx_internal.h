@@ -31,6 +31,11 @@ struct dx_entry {
     dx_handle h{};           // host mirror of the published handle
 };
 
+struct dx_request {
+    int layer, expert;
+    bool promote;
+};
+
 struct dx_transition {
     int layer, expert;
     bool promote;
@@ -75,6 +80,9 @@ struct dx_ctx {
     std::vector<int> hi_count; // per layer: Resident-Hi + Promoting
     int n_hi_cap = 0;          // per-layer capacity from the budget rule
     std::deque<dx_transition> inflight;
+    std::deque<dx_request> update_q;                       // waiting promotions and demotions, in arrival order
+    std::vector<std::array<const void *, 3>> host_master; // per routed entry: pinned bf16 gate/up/down or nulls
+    int max_inflight = 0;                                  // 0: unbounded
     std::vector<hipEvent_t> event_pool;
     dx_stats stats{};
 

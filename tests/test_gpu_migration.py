@@ -258,3 +258,60 @@ def test_pool_exhaustion_and_errors(B, LY, dxo):
             ctx.dx_demote_async(*bad)
         assert ei.value.status == B.DX_ERR_INVALID
     ctx.close()
+
+
+def test_transition_queue_backpressure_and_eviction_priority(B, LY, dxo):
+    """The queued worker step: promotions wait while the layer's high-precision places are taken,
+    the demotions that free them overtake them, at most `max_inflight` transitions are in flight,
+    opposite requests cancel, and every step in between computes with the published map."""
+    st = Stack(B, LY, dxo, L=2, n_hi=2, spare_hi=1, spare_lo=1)
+    wl, ctx = st.wl, st.ctx
+    st.install([{0, 1}, {2, 3}])
+    for l in range(2):
+        for e in range(wl.E):
+            ctx.dx_register_host_master(l, e, *st.pinned[l][e])
+    ctx.dx_transitions_limits(1)
+
+    # layer 0: {0,1} -> {4,5}; the promotions are queued first but cannot be admitted (both places taken)
+    ctx.dx_transitions_enqueue(0, promote=[4, 5], demote=[])
+    issued, published, queued = ctx.dx_transitions_pump(8)
+    assert (issued, published, queued) == (0, 0, 2)                  # backpressure: nothing started, nothing lost
+    assert ctx.dx_get_stats()["promotions_issued"] == 0
+    ctx.dx_transitions_enqueue(0, promote=[], demote=[0, 1])
+    issued, published, queued = ctx.dx_transitions_pump(8)
+    assert issued == 1 and queued == 3                               # a demotion overtook the waiting promotions;
+    s = ctx.dx_get_stats()                                           # max_inflight = 1 stopped the second one
+    assert s["demotions_issued"] == 1 and s["promotions_issued"] == 0 and s["in_flight"] == 1
+    st.check(0, 0)                                                   # forward while the demotion is in flight
+    # keep pumping between forward passes until the queue drains
+    for step in range(1, 40):
+        issued, published, queued = ctx.dx_transitions_pump(8)
+        s = ctx.dx_get_stats()
+        assert s["in_flight"] <= 1 and s["peak_in_flight"] <= 1
+        assert s["peak_reserved_bytes"] <= st.budget + st.transient
+        st.check(0, step)
+        if queued == 0 and s["in_flight"] == 0:
+            break
+        ctx.dx_migrate_poll(wait=True)                               # let the in-flight one finish
+    fm = ctx.dx_get_formats()
+    assert set(np.flatnonzero(fm[0] == B.DX_FMT_BF16)) == {4, 5}
+    assert set(np.flatnonzero(fm[1] == B.DX_FMT_BF16)) == {2, 3}
+    s = ctx.dx_get_stats()
+    assert s["promotions_published"] == 2 and s["demotions_published"] == 2 and s["queued"] == 0
+    assert s["reserved_bytes"] == st.budget
+    h = ctx.dx_get_handle(0, 5)                                      # promoted content = the registered master
+    assert np.array_equal(read_device(h.w_down, st.masters[0][2][5].nbytes).view(np.uint16), st.masters[0][2][5].ravel())
+
+    # opposite requests for one expert cancel; duplicates and requests already satisfied are dropped
+    ctx.dx_transitions_enqueue(1, promote=[6], demote=[2])
+    ctx.dx_transitions_enqueue(1, promote=[2, 6], demote=[6])        # 2: cancels its demotion; 6: demote cancels promote,
+    assert ctx.dx_get_stats()["queued"] == 1                         # then promote 6 is queued again
+    ctx.dx_transitions_enqueue(1, promote=[3], demote=[7])           # 3 is already bf16, 7 already int4
+    issued, published, queued = ctx.dx_transitions_pump(8)
+    assert issued == 0 and queued == 1                               # 3 and 7 dropped; 6 waits for a free place
+    with pytest.raises(B.DxError):
+        ctx.dx_transitions_enqueue(1, promote=[wl.E], demote=[])
+    with pytest.raises(B.DxError):
+        ctx.dx_transitions_limits(-1)
+    st.check(1, 0)
+    ctx.close()

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(B):
 def test_struct_sizes_match_the_header(B):
     assert C.sizeof(B.DxHandle) == 64
     assert C.sizeof(B.DxConfig) == 64
-    assert C.sizeof(B.DxStats) == 80
+    assert C.sizeof(B.DxStats) == 104
 
 
 def test_host_rules_agree_with_oracle(B, dxo):
