@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets to rotate over")
     ap.add_argument("--window", type=int, default=None, help="routing-only warm-up steps per layer for hotness")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the C2/C3 layer shape at T = 1, 2, 4, ... 8192 tokens per step (one JSON line)")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -170,8 +172,84 @@ def run_c5(args):
     print(json.dumps(out))
 
 
+def run_sweep(args):
+    """Tokens per step from 1 to 8192 on the 30B-shaped layer (the style of a prompt-length sweep): the
+    same route + forward step as the headline benchmark, rotating over 8 layers' weights."""
+    import dataclasses
+
+    import numpy as np
+    import torch
+
+    from paper_2511_15015_amd import binding as B
+    from paper_2511_15015_amd import layer as LY
+    from paper_2511_15015_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    base = W.WORKLOADS["C2"]
+    L, E, k, d, f, t_max = 8, base.E, base.k, base.d, base.f, 8192
+    stream = torch.cuda.Stream()
+    rows = []
+    with torch.cuda.stream(stream):
+        ctx = B.Context(L=L, E=E, d=d, f=f, top_k=k, group=base.group, max_tokens=t_max, route_updates_hotness=True,
+                        stream=stream.cuda_stream)
+        rb = LY.RoutingBuffers(t_max, E, k)
+        layers = []
+        for layer in range(L):
+            # resident set: the hottest experts of the layer's Zipf permutation (ranks 1..n_hi)
+            bias = W.zipf_bias(E, base.zipf_s, args.seed, base.config_id, layer)
+            resident = np.argsort(-bias, kind="stable")[:base.n_hi]
+            wg, wu, wd = W.device_masters(base, args.seed, layer)
+            layers.append(LY.LayerWeights(ctx, layer, wg, wu, wd, resident, base.group, keep_masters=False))
+            del wg, wu, wd
+        y = torch.empty((t_max, d), dtype=torch.bfloat16, device="cuda")
+        lib, h = ctx.lib, ctx.h
+        p_ids, p_w, p_counts, p_off, p_perm = (t.data_ptr() for t in (rb.ids, rb.w, rb.counts, rb.offsets, rb.perm))
+        T = 1
+        while T <= t_max:
+            wl = dataclasses.replace(base, T=T)
+            xs, lgs = [], []
+            for layer in range(L):
+                x, lg = W.layer_inputs(wl, args.seed, layer, step=0)
+                xs.append(LY.bits_to_device(x))
+                lgs.append(torch.from_numpy(lg).cuda())
+
+            def step_fn(i):
+                layer = i % L
+                if lib.dx_route(h, layer, lgs[layer].data_ptr(), T, p_ids, p_w, p_counts, p_off, p_perm) or \
+                   lib.dx_moe_forward(h, layer, None, xs[layer].data_ptr(), T, p_ids, p_w, p_off, p_perm, y.data_ptr()):
+                    raise RuntimeError(lib.dx_last_error(h).decode())
+
+            steps = 240 if T <= 256 else 48
+            for i in range(L):
+                step_fn(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                step_fn(i)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            rows.append({"T": T, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3)})
+            T *= 2
+    ctx.close()
+    at32 = next(r for r in rows if r["T"] == 32)
+    print(json.dumps({
+        "metric": "MoE-layer tokens/s against tokens per step", "value": at32["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": 240, "warmup": L, "ms_per_step": at32["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"30B-A3B-shaped MoE layer (d={d}, f={f}, E={E}, top-{k}, Zipf(s={base.zipf_s}) routing, "
+                               f"{base.n_hi} bf16 + {E - base.n_hi} int4-g{base.group} experts), T from 1 to {t_max}, "
+                               f"rotating over {L} layers' weights; value and ms_per_step are the T=32 row",
+                   "step": "dx_route + dx_moe_forward of one layer"},
+        "sweep": rows}))
+
+
 def main():
     args = parse()
+    if args.sweep:
+        if args.gpus != 1:
+            print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+            sys.exit(2)
+        return run_sweep(args)
     defaults = {"C2": dict(steps=960, warmup=96, layers=48, window=64),
                 "C3": dict(steps=48, warmup=8, layers=4, window=2),
                 "C5": dict(steps=384, warmup=0, layers=8, window=32)}[args.workload]

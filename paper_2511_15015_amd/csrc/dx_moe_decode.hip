@@ -641,15 +641,19 @@ void launch_stream(const dx_fwd_args &a, split_choice c, dim3 grid, hipStream_t 
     }
 }
 
+// Up to this many tokens per call the streaming kernels alone are faster than the three-chain prefill
+// pass (measured on the 30B-shaped layer: 140 us against 171 us at T = 128, equal at T = 256).
+constexpr int kStreamOnlyTokens = 128;
+
 template <int LK>
 hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks)
 {
     constexpr int CHUNK = 4 * LK;
     dx_fwd_args a = a_in;
-    // Few tokens per expert everywhere (decode): the streaming kernels take every expert.  Otherwise
-    // experts above 32 tokens go to the tiled MFMA kernels (when the shapes fit their tiles).
+    // Few tokens per call (decode): the streaming kernels take every expert.  Otherwise experts above
+    // 32 tokens go to the tiled MFMA kernels (when the shapes fit their tiles).
     const bool tiles_fit = a.d % 128 == 0 && a.f % 64 == 0 && (!a.shared || a.shared_f % 64 == 0);
-    const bool mixed = a.T > 64 && tiles_fit;
+    const bool mixed = a.T > kStreamOnlyTokens && tiles_fit;
     a.m_small = mixed ? 32 : 0x7fffffff;
     // the 256 x 256 kernel addresses rows with 32-bit byte offsets from the matrix base
     const uint64_t span_x = (uint64_t)a.T * a.d * 2, span_h = (uint64_t)a.T * (a.k + 1) * a.fmax * 2;
@@ -677,8 +681,9 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
     } else {
         // Three chains on three streams.  The streamed experts are bound by memory, the tiles by the
         // matrix cores, and the tail of each tiled grid leaves compute units idle: run together they
-        // fill each other's gaps.  The streaming grid is a quarter of the chip here so that the tile
-        // kernels (whose LDS footprint does not share a compute unit with it) keep the rest.
+        // fill each other's gaps.  Once the tiles carry most of the work the streaming grid shrinks to
+        // a quarter of the chip, so that the 256-row tile kernel (whose LDS footprint does not share a
+        // compute unit with it) keeps the rest; measured better from a mean segment of 256 tokens up.
         hipError_t e;
         if ((e = hipEventRecord(side->fork, s)) != hipSuccess) return e;
         for (int i = 0; i < 2; ++i)
@@ -687,7 +692,8 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
         hipStream_t s_tiled = a.m_big ? side->aux[1] : s;
         if ((e = dxk_moe_forward_tiled(a, s, s_tiled, marks ? &marks[1] : nullptr)) != hipSuccess) return e;
         if (marks) (void)hipEventRecord(marks[2], s);
-        const dim3 grid(n_cu >= 8 ? n_cu / 4 : n_cu);
+        const bool tiles_dominate = (long)a.T * a.k >= 256L * a.E; // mean segment of 256 tokens or more
+        const dim3 grid(tiles_dominate && n_cu >= 8 ? n_cu / 4 : n_cu);
         launch_stream<LK, false>(a, gu, grid, side->aux[0]);
         launch_stream<LK, true>(a, dn, grid, side->aux[0]);
         for (int i = 0; i < 2; ++i) {

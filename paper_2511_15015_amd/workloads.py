@@ -73,6 +73,9 @@ WORKLOADS = {
     # 30B-shaped 48-layer stack with the hot set re-drawn every 256 steps
     "C5": Workload("C5", 5, T=32, d=2048, f=768, E=128, k=8, group=128, n_hi=32, L=48,
                    zipf_s=1.1, redraw_every=256, steps=2048),
+    # Phi-3.5-MoE-shaped layer: few, very large experts, top-2 (a different tiling regime; not one of
+    # the baseline configurations, used by the shape tests and the token-count sweep)
+    "X1": Workload("X1", 6, T=32, d=4096, f=6400, E=16, k=2, group=128, n_hi=4, zipf_s=1.0),
 }
 
 # tensor ids for the seed sequence

@@ -371,14 +371,15 @@ def test_route_can_update_hotness_itself(B, LY, dxo):
 
 
 # ------------------------------------------------------- prefill-sized batches
-@pytest.mark.parametrize("T,E,k,resident", [(65, 4, 2, [0, 2]), (200, 4, 2, [1]), (300, 8, 3, [0, 5, 6]),
+@pytest.mark.parametrize("T,E,k,resident", [(65, 4, 2, [0, 2]), (128, 4, 2, [0, 2]), (200, 4, 2, [1]), (300, 8, 3, [0, 5, 6]),
                                             (129, 2, 2, [0]), (400, 4, 1, []),
                                             # bf16 segments of 256 rows and more: 256 x 256 tiles plus a remainder
                                             (700, 4, 2, [0, 2]), (1100, 2, 2, [0, 1]), (512, 2, 2, [1]),
                                             (256, 1, 1, [0])])
 def test_forward_prefill_tiles_small_shapes(B, LY, dxo, T, E, k, resident):
-    """Segments above 32 tokens take the tiled MFMA kernels (bf16 and int4), the others the streaming
-    ones; ragged row tiles; every token checked."""
+    """Up to 128 tokens per call the streaming kernels walk each segment in blocks of 32 tokens; above,
+    segments of more than 32 tokens take the tiled MFMA kernels (bf16 and int4), the others the
+    streaming ones; ragged row tiles; every token checked."""
     import dataclasses
     wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k)
     print(f"prefill tiles T={T} E={E} k={k} resident={resident}", flush=True)

@@ -264,3 +264,42 @@ def test_c5_churn_with_ema_and_hysteresis(B, LY, dxo):
     assert promotions["ema+slack8"] <= promotions["ema+slack4"] <= promotions["ema"]
     for ctx in ctxs.values():
         ctx.close()
+
+
+@pytest.mark.parametrize("T", [32, 1536])
+def test_phi35_shaped_layer(B, LY, dxo, T):
+    """16 experts of 4096 x 6400, top-2, 4 of them bf16: the decode batch runs the streaming kernels on
+    K = 4096 and 6400 (more K-chunks than wavefronts), the prefill batch the 256-row and 128-row tile
+    kernels with 50 column tiles; sampled tokens against the oracle, routing bit-exact."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["X1"], T=T)
+    print(f"X1 T={T}: drawing masters", flush=True)
+    dev = W.device_masters(wl, 0, 0)
+    x, lg = W.layer_inputs(wl, 0, 0, 0)
+    ids, w, counts, offsets, perm = dxo.route(lg, wl.k)
+    resident = set(int(e) for e in dxo.select_topn(counts.astype(np.uint64) << np.uint64(16), wl.n_hi))
+    ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=T)
+    lw = LY.LayerWeights(ctx, 0, *dev, resident, wl.group)
+    rb = LY.RoutingBuffers(T, wl.E, wl.k)
+    y = torch.empty((T, wl.d), dtype=torch.bfloat16, device="cuda")
+    print(f"X1 T={T}: running, segments {counts.tolist()}", flush=True)
+    rb.route(ctx, 0, torch.from_numpy(lg).cuda())
+    rb.forward(ctx, 0, LY.bits_to_device(x), y)
+    torch.cuda.synchronize()
+    assert np.array_equal(rb.ids.cpu().numpy(), ids) and np.array_equal(rb.perm.cpu().numpy(), perm)
+    g = np.random.default_rng(1)
+    tokens = np.sort(g.choice(T, 6, replace=False)).astype(np.int32)
+    needed = sorted(set(int(e) for e in ids[tokens].ravel()))
+    versions, filler = [None] * wl.E, None
+    for e in needed:
+        host = [LY.device_to_bits(m[e]) for m in dev]
+        versions[e] = (dxo.ExpertVersion.bf16(*host) if e in resident
+                       else dxo.ExpertVersion.int4_from_master(*host, wl.group))
+        filler = versions[e]
+    versions = [v if v is not None else filler for v in versions]
+    y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w, tokens=tokens)
+    err = rel_l2(LY.device_to_bits(y)[tokens], y_ref)
+    print(f"  X1 T={T} rel-L2 {err:.3e} over tokens {tokens.tolist()}", flush=True)
+    assert err <= REL_L2_TOL
+    del lw
+    ctx.close()
