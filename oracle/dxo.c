@@ -86,6 +86,26 @@ int dxo_threads(void)
 #endif
 }
 
+/* ------------------------------------------------- router: the logits   */
+/* The router of the MoE layer (Sec. 2.1 / 3.1: a learned linear gate scores
+ * every expert for every token): logits[t,e] = sum_c x[t,c] * W_r[e,c]
+ * (+ bias[e]), bf16 inputs, every sum in fp64, one rounding to fp32 at the
+ * end.  bias may be NULL. */
+int dxo_router_logits(const uint16_t *x, const uint16_t *w_r, const float *bias, int T, int E, int d,
+                      float *logits)
+{
+    if (T < 0 || E <= 0 || d <= 0) return 1;
+    for (int t = 0; t < T; ++t)
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c)
+                acc += (double)bf16_widen(x[(size_t)t * d + c]) * (double)bf16_widen(w_r[(size_t)e * d + c]);
+            if (bias) acc += (double)bias[e];
+            logits[(size_t)t * E + e] = (float)acc;
+        }
+    return 0;
+}
+
 /* ------------------------------------------------------- router: top-k  */
 /* Sec. 3.1: "the router [gives] top-k expert IDs".  ids[t,0..k) are the k
  * largest logits of token t, largest first, equal logits to the lower index.

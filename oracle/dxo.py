@@ -62,6 +62,22 @@ def threads() -> int:
 
 
 # ----------------------------------------------------------------- routing
+def router_logits(x_bits: np.ndarray, wr_bits: np.ndarray, bias=None) -> np.ndarray:
+    """fp32 logits [T,E] = x . W_r^T (+ bias) from bf16 bit patterns, fp64 sums."""
+    x = np.ascontiguousarray(x_bits, np.uint16)
+    wr = np.ascontiguousarray(wr_bits, np.uint16)
+    T, d = x.shape
+    E = wr.shape[0]
+    assert wr.shape[1] == d
+    b = None if bias is None else np.ascontiguousarray(bias, np.float32)
+    out = np.empty((T, E), np.float32)
+    rc = lib().dxo_router_logits(_p(x), _p(wr), _p(b) if b is not None else None, C.c_int(T), C.c_int(E), C.c_int(d),
+                                 _p(out))
+    if rc:
+        raise ValueError(f"dxo_router_logits rc={rc}")
+    return out
+
+
 def topk(logits: np.ndarray, k: int):
     """ids int32 [T,k] (descending logit, ties to the lower index), w fp64 [T,k]."""
     logits = np.ascontiguousarray(logits, np.float32)

@@ -444,6 +444,37 @@ def test_transition_sets_are_set_differences(dxo):
         assert pro.tolist() == sorted(H - Hc) and dem.tolist() == sorted(Hc - H)
 
 
+def test_router_logits_closed_forms(dxo):
+    g = np.random.default_rng(31)
+    T, E, d = 5, 7, 64
+    wr = wlmod.f32_to_bf16_bits(g.standard_normal((E, d)).astype(np.float32))
+    bias = g.standard_normal(E).astype(np.float32)
+    # one-hot tokens pick out a column of W_r: token t = unit vector c_t  ->  logits[t, e] = W_r[e, c_t] + bias[e]
+    cols = [3, 0, 63, 17, 17]
+    x = np.zeros((T, d), np.float32)
+    x[np.arange(T), cols] = 1.0
+    got = dxo.router_logits(wlmod.f32_to_bf16_bits(x), wr, bias)
+    want = (wlmod.bf16_bits_to_f32(wr)[:, cols].T.astype(np.float64) + bias.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(got, want)
+    # small integers: every product and sum is exact, the result is the integer dot product
+    xi = g.integers(-4, 5, (T, d)).astype(np.float32)
+    wi = g.integers(-4, 5, (E, d)).astype(np.float32)
+    got = dxo.router_logits(wlmod.f32_to_bf16_bits(xi), wlmod.f32_to_bf16_bits(wi))
+    assert np.array_equal(got, (xi.astype(np.int64) @ wi.astype(np.int64).T).astype(np.float32))
+    # x and W_r swap roles under transposition; doubling x doubles the bias-free logits exactly
+    xr = wlmod.f32_to_bf16_bits(g.standard_normal((T, d)).astype(np.float32))
+    a = dxo.router_logits(xr, wr)
+    assert np.array_equal(a, dxo.router_logits(wr, xr).T)
+    x2 = wlmod.f32_to_bf16_bits(2.0 * wlmod.bf16_bits_to_f32(xr))
+    assert np.array_equal(dxo.router_logits(x2, wr), 2.0 * a)
+    # the generator's fp32 logits of the workload recipe are the same numbers up to fp32 summation error
+    wl = WORKLOADS["C1"]
+    xb = wlmod.activations(wl, 0, 0, 0)
+    wrb = wlmod.router_matrix(wl, 0, 0)
+    zb = wlmod.zipf_bias(wl.E, wl.zipf_s, 0, wl.config_id, 0) if wl.zipf_s is not None else None
+    assert np.allclose(dxo.router_logits(xb, wrb, zb), wlmod.router_logits(wl, xb, wrb, 0, 0), rtol=0, atol=2e-5)
+
+
 def _rank_key(S):
     return lambda e: (-int(S[e]), e)
 
