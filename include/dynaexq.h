@@ -126,6 +126,15 @@ dx_status dx_route(dx_ctx *ctx, int layer, const float *logits, int T,
                    int32_t *topk_ids, float *topk_w,
                    int32_t *counts, int32_t *offsets, int32_t *perm);
 
+/* The router's linear gate in front of dx_route (Sec. 2.1: the router scores
+ * every expert for every token; Sec. 3.1 consumes its top-k):
+ *   logits[t,e] = sum_c x[t,c] * w_router[e,c] (+ bias[e])
+ * x_bf16 dev [T,d], w_router dev bf16 [E,d] row-major, bias dev fp32 [E] or
+ * NULL, logits dev fp32 [T,E].  bf16 products accumulated in fp32 on the
+ * matrix cores in a fixed order.  0 <= T <= max_tokens. */
+dx_status dx_router_logits(dx_ctx *ctx, const void *x_bf16, const void *w_router, const float *bias,
+                           int T, float *logits);
+
 /* Mixed-precision expert execution (Sec. 3.2: "The compute path resolves
  * the handle to obtain the active pointer and the associated quantization
  * parameters, then invokes the corresponding kernel").

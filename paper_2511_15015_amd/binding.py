@@ -21,7 +21,7 @@ DX_STATE_EMPTY, DX_STATE_RESIDENT_HI, DX_STATE_RESIDENT_LO, DX_STATE_PROMOTING, 
 
 EXPORTS = [
     "dx_create", "dx_destroy", "dx_last_error", "dx_status_str",
-    "dx_route", "dx_moe_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
+    "dx_route", "dx_router_logits", "dx_moe_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
     "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
     "dx_register_host_master", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
@@ -92,6 +92,7 @@ def load():
     L.dx_status_str.argtypes = [i32]
     L.dx_status_str.restype = C.c_char_p
     L.dx_route.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp]
+    L.dx_router_logits.argtypes = [vp, vp, vp, vp, i32, vp]
     L.dx_moe_forward.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
     L.dx_hotness_update.argtypes = [vp, i32, vp]
     L.dx_window_end.argtypes = [vp, vp]
@@ -221,6 +222,10 @@ class Context:
     def dx_route(self, layer, logits, T, topk_ids, topk_w, counts, offsets, perm):
         self._chk(self.lib.dx_route(self.h, layer, _ptr(logits), T, _ptr(topk_ids), _ptr(topk_w),
                                     _ptr(counts), _ptr(offsets), _ptr(perm)), "dx_route")
+
+    def dx_router_logits(self, x, w_router, bias, T, logits):
+        self._chk(self.lib.dx_router_logits(self.h, _ptr(x), _ptr(w_router), _ptr(bias), T, _ptr(logits)),
+                  "dx_router_logits")
 
     def dx_moe_forward(self, layer, handle_table, x, T, topk_ids, topk_w, offsets, perm, y):
         self._chk(self.lib.dx_moe_forward(self.h, layer, _ptr(handle_table), _ptr(x), T, _ptr(topk_ids),

@@ -424,6 +424,20 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
     return DX_OK;
 }
 
+extern "C" dx_status dx_router_logits(dx_ctx *c, const void *x, const void *w_router, const float *bias, int T,
+                                      float *logits)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (T < 0 || T > c->cfg.max_tokens) DX_FAIL(c, DX_ERR_INVALID, "dx_router_logits: T=%d outside 0..%d", T, c->cfg.max_tokens);
+    if (T == 0) return DX_OK;
+    if (!x || !w_router || !logits) DX_FAIL(c, DX_ERR_INVALID, "dx_router_logits: null pointer");
+    if (((uintptr_t)x & 15) || ((uintptr_t)w_router & 15) || ((uintptr_t)logits & 3) || ((uintptr_t)bias & 3))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_router_logits: misaligned pointer");
+    DX_HIP(c, dxk_router_gemm(static_cast<const dx_bf16 *>(x), static_cast<const dx_bf16 *>(w_router), bias, T, c->cfg.E,
+                              c->cfg.d, logits, c->compute));
+    return DX_OK;
+}
+
 extern "C" dx_status dx_hotness_update(dx_ctx *c, int layer, const int32_t *counts)
 {
     if (!c) return DX_ERR_INVALID;

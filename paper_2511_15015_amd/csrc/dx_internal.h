@@ -113,6 +113,8 @@ struct dx_ctx {
 hipError_t dxk_route(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
                      int32_t *offsets, int32_t *perm, unsigned long long *mask, int32_t *chunk_base,
                      unsigned long long *hotness /* window counters of the layer, or null */, hipStream_t s);
+hipError_t dxk_router_gemm(const dx_bf16 *x, const dx_bf16 *w_r, const float *bias, int T, int E, int d, float *logits,
+                           hipStream_t s);
 hipError_t dxk_hotness_add(unsigned long long *counters, const int32_t *counts, int E, hipStream_t s);
 hipError_t dxk_fill_u64(unsigned long long *p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t dxk_store_handle(dx_handle *slot, const dx_handle &h, hipStream_t s);

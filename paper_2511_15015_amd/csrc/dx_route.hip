@@ -231,6 +231,51 @@ __global__ void k_store_handle(dx_handle *slot, dx_handle h)
     if (threadIdx.x == 0 && blockIdx.x == 0) *slot = h;
 }
 
+// Router gate: logits = x . W_r^T (+ bias).  One block per 32 tokens x 32 experts; its 4 wavefronts
+// take the K-steps of 16 in turn (step s to wavefront s % 4), each multiplying with
+// v_mfma_f32_32x32x16_bf16 straight from global memory (lane l: row l % 32, 8 consecutive k from
+// 8 * (l / 32)); the four partial tiles meet in LDS and are added in wavefront order.
+typedef __attribute__((ext_vector_type(8))) __bf16 rt_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float rt_f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t rt_u32x4;
+
+__global__ __launch_bounds__(256) void k_router_gemm(const dx_bf16 *__restrict__ x, const dx_bf16 *__restrict__ w_r,
+                                                     const float *__restrict__ bias, int T, int E, int d,
+                                                     float *__restrict__ logits)
+{
+    __shared__ float part[4][32][33];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t0 = blockIdx.y * 32, e0 = blockIdx.x * 32;
+    const int r = lane & 31, kq = lane >> 5;
+    const int t = min(t0 + r, T - 1), e = min(e0 + r, E - 1); // rows past the end repeat the last one; never stored
+    const dx_bf16 *xrow = x + (size_t)t * d + kq * 8;
+    const dx_bf16 *wrow = w_r + (size_t)e * d + kq * 8;
+    rt_f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    union frag {
+        rt_u32x4 u;
+        rt_bf16x8 v;
+    };
+    for (int s = wave; s < d / 16; s += 4) {
+        frag a, b;
+        a.u = *reinterpret_cast<const rt_u32x4 *>(xrow + s * 16);
+        b.u = *reinterpret_cast<const rt_u32x4 *>(wrow + s * 16);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc, 0, 0, 0);
+    }
+    // accumulator element v: token row (v/4)*8 + (lane/32)*4 + v%4, expert column lane%32
+#pragma unroll
+    for (int v = 0; v < 16; ++v) part[wave][(v >> 2) * 8 + kq * 4 + (v & 3)][r] = acc[v];
+    __syncthreads();
+    for (int i = threadIdx.x; i < 32 * 32; i += 256) {
+        const int tr = i >> 5, ec = i & 31;
+        if (t0 + tr >= T || e0 + ec >= E) continue;
+        float v = ((part[0][tr][ec] + part[1][tr][ec]) + part[2][tr][ec]) + part[3][tr][ec];
+        if (bias) v += bias[e0 + ec];
+        logits[(size_t)(t0 + tr) * E + e0 + ec] = v;
+    }
+}
+
 template <int NV>
 hipError_t launch_topk(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
                        int32_t *offsets, int32_t *perm, unsigned long long *mask, unsigned long long *hotness,
@@ -263,6 +308,14 @@ hipError_t dxk_route(const float *logits, int T, int E, int k, int32_t *ids, flo
     const int P = T * k;
     hipLaunchKernelGGL(k_route_place, dim3((P + 255) / 256), dim3(256), 0, s, ids, P, E, k, mask, chunk_base,
                        offsets, perm);
+    return hipGetLastError();
+}
+
+hipError_t dxk_router_gemm(const dx_bf16 *x, const dx_bf16 *w_r, const float *bias, int T, int E, int d, float *logits,
+                           hipStream_t s)
+{
+    if (T == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_router_gemm, dim3((E + 31) / 32, (T + 31) / 32), dim3(256), 0, s, x, w_r, bias, T, E, d, logits);
     return hipGetLastError();
 }
 

@@ -135,6 +135,30 @@ def test_route_rejects_bad_arguments(B, LY):
     ctx.close()
 
 
+@pytest.mark.parametrize("T,E,d,with_bias", [(32, 128, 2048, True), (1, 8, 64, False), (33, 40, 96, True),
+                                             (4096, 128, 2048, True), (70, 512, 2048, False)])
+def test_router_logits_match_oracle(B, LY, dxo, T, E, d, with_bias):
+    """The router gate on the matrix cores against the fp64 oracle: fp32 accumulation of exact bf16
+    products, so the difference stays near d * 2^-24 of the largest partial sum."""
+    g = np.random.default_rng(T + E)
+    x = W.f32_to_bf16_bits(g.standard_normal((T, d)).astype(np.float32))
+    wr = W.f32_to_bf16_bits((0.02 * g.standard_normal((E, d))).astype(np.float32))
+    bias = (g.standard_normal(E) * 3).astype(np.float32) if with_bias else None
+    ctx = B.Context(L=1, E=E, d=d, f=64, top_k=2, group=32, max_tokens=T)
+    out = torch.full((T, E), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.dx_router_logits(LY.bits_to_device(x), LY.bits_to_device(wr),
+                         torch.from_numpy(bias).cuda() if with_bias else None, T, out)
+    sync()
+    ref = dxo.router_logits(x, wr, bias)
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    scale = float(np.abs(ref).max())
+    assert np.abs(got - ref).max() <= 2e-5 * max(scale, 1.0), np.abs(got - ref).max()
+    with pytest.raises(B.DxError):
+        ctx.dx_router_logits(LY.bits_to_device(x), LY.bits_to_device(wr), None, T + 1, out)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ the layer
 class Layer:
     """One layer set up on both sides from the same master bits."""
