@@ -96,10 +96,14 @@ constexpr int kThreads = 64 * kWaves; // 512
 constexpr int kMaxExperts = 1024 + 1; // routed + shared
 // Relative cost of a bf16 / int4 strip pair in the partition.  An int4 pair is a quarter of the bytes
 // but carries the same per-step work (barrier, reduction), so it is weighed by measured time, not
-// bytes: 3/8 of a bf16 pair when K is long (gate/up), 5/8 when it is short (down).
+// bytes: 4/8 of a bf16 pair when K is long (gate/up), 5/8 when it is short (down).
 constexpr int kHiUnits = 8;
 template <bool DOWN>
-constexpr int kLoUnits = DOWN ? 5 : 3;
+constexpr int kLoUnits = DOWN ? 5 : 4;
+// A block that starts on a new expert pays for the handle, the token rows and a cold pipeline (about
+// 3 us, one and a half bf16 pairs): every expert's range begins with this many units that carry no
+// strips, so the block that holds an expert boundary gets correspondingly fewer strips.
+constexpr uint32_t kRunUnits = 12;
 
 #ifdef DX_TRACE
 // Debug build only: per-block start/end time stamps (100 MHz wall clock).
@@ -455,7 +459,9 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             const int m = tokens_of(e);
             seg_tokens[e] = m;
             seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
-            if (m > 0) mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * (fmt_of(e) == DX_FMT_INT4G ? kLoUnits<DOWN> : kHiUnits);
+            if (m > 0)
+                mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * (fmt_of(e) == DX_FMT_INT4G ? kLoUnits<DOWN> : kHiUnits) +
+                          kRunUnits;
             local += mine[i];
         }
     }
@@ -522,9 +528,11 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             const uint32_t wgt = ex.int4 ? kLoUnits<DOWN> : kHiUnits;
             const uint32_t lo = (ub0 > cum[e] ? ub0 : cum[e]) - cum[e];
             const uint32_t hi = (ub1 < cum[e + 1] ? ub1 : cum[e + 1]) - cum[e];
-            // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi)
-            int i = (int)((lo + wgt - 1) / wgt);
-            const int i1 = (int)((hi + wgt - 1) / wgt);
+            // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi); pair i starts
+            // kRunUnits + i * wgt units into the expert's range
+            const uint32_t lo_p = lo > kRunUnits ? lo - kRunUnits : 0, hi_p = hi > kRunUnits ? hi - kRunUnits : 0;
+            int i = (int)((lo_p + wgt - 1) / wgt);
+            const int i1 = (int)((hi_p + wgt - 1) / wgt);
             while (i < i1) {
                 const int mb = i / spe;
                 const int iend = i1 < (mb + 1) * spe ? i1 : (mb + 1) * spe;
