@@ -258,16 +258,28 @@ struct expert_ctx {
 // Add up the partial sums of the strip pairs sb .. sb+live_groups-1 in a fixed order and finish them:
 // gate/up -> H = silu(gate) * up (bf16); down -> the two 16-row halves of O (fp32).  All threads.
 // Element (group gg, tile mt, accumulator lane L, component i) is token 4*(L/16)+i, column L%16.
+// (slot, row of O) of the output elements a thread finishes: idx = threadIdx.x + n * kThreads has the
+// same idx % (MT * 256) for every n, so both are fixed for a whole run and the row lookup in the
+// permutation happens once, off the critical path of the first finish.
 template <bool DOWN, int MT>
-__device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_ctx &ex, int mb, int sb,
+__device__ __forceinline__ void finish_target(const dx_fwd_args &a, const expert_ctx &ex, int mb, int &slot, int &orow)
+{
+    const int rem = threadIdx.x % (MT * 256);
+    const int mt = rem / 256, L = rem & 63, i = (rem >> 6) & 3;
+    slot = mb * 32 + 16 * mt + 4 * (L >> 4) + i;
+    orow = 0;
+    if (DOWN && slot < ex.m) orow = ex.shared ? ex.seg0 + slot : a.perm[ex.seg0 + slot];
+}
+
+template <bool DOWN, int MT>
+__device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_ctx &ex, int slot, int orow, int sb,
                                              int live_groups, int WPS, const float *redf)
 {
     const int rows_per_strip = DOWN ? 32 : 16;
+    if (slot >= ex.m) return;
     for (int idx = threadIdx.x; idx < live_groups * MT * 256; idx += kThreads) {
         const int gg = idx / (MT * 256), rem = idx % (MT * 256);
         const int mt = rem / 256, L = rem & 63, i = (rem >> 6) & 3;
-        const int slot = mb * 32 + 16 * mt + 4 * (L >> 4) + i;
-        if (slot >= ex.m) continue;
         float v0 = 0.f, v1 = 0.f;
         for (int w = 0; w < WPS; ++w) {
             const float *base = redf + (((gg * WPS + w) * 4) * 64 + L) * 4 + i;
@@ -276,7 +288,6 @@ __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_
         }
         const int n = (sb + gg) * rows_per_strip + (L & 15);
         if constexpr (DOWN) {
-            const int orow = ex.shared ? ex.seg0 + slot : a.perm[ex.seg0 + slot];
             if (a.o_bf16) {
                 dx_bf16 *ob = reinterpret_cast<dx_bf16 *>(a.o) + (size_t)orow * a.d + n;
                 ob[0] = (dx_bf16)float_to_bf16_rne(v0);
@@ -317,11 +328,14 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     const int nbatch = (s_hi - s_lo + SPP - 1) / SPP;
     const int nsteps = nbatch * rounds;
 
+    int fin_slot, fin_orow;
+    finish_target<DOWN, MT>(a, ex, mb, fin_slot, fin_orow);
     auto finish = [&](int batch) {
         __syncthreads();
         const int sb = s_lo + batch * SPP;
         const int live_groups = (s_hi - sb) < SPP ? (s_hi - sb) : SPP;
-        finish_batch<DOWN, MT>(a, ex, mb, sb, live_groups, WPS, reinterpret_cast<const float *>(&red[pb][0][0][0]));
+        finish_batch<DOWN, MT>(a, ex, fin_slot, fin_orow, sb, live_groups, WPS,
+                               reinterpret_cast<const float *>(&red[pb][0][0][0]));
         pb ^= 1; // the other half of `red` is free: its readers passed the barrier above
     };
 
