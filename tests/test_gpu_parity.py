@@ -478,3 +478,50 @@ def test_forward_c3_prefill_sampled_tokens(B, LY, dxo):
     assert tok.max() <= 2 * REL_L2_TOL
     del lw
     ctx.close()
+
+
+@pytest.mark.parametrize("T", [32, 300])
+def test_route_and_forward_replay_from_a_captured_graph(B, LY, dxo, T):
+    """dx_route + dx_moe_forward recorded into a HIP graph (the decode pass, and the prefill pass with
+    its fork/join over the side streams), replayed several times with eager work and synchronisations
+    in between: every replay reproduces the eager result bit for bit."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=4 if T > 64 else 8)
+    x, logits = W.layer_inputs(wl, seed=9)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ly = Layer(B, LY, dxo, wl, [0, 2], seed=9)
+        ctx, rb = ly.ctx, ly.rb
+        xd, ld = LY.bits_to_device(x), torch.from_numpy(logits).cuda()
+        y = torch.empty((T, wl.d), dtype=torch.bfloat16, device="cuda")
+        rb.route(ctx, 0, ld, T)
+        rb.forward(ctx, 0, xd, y, None, T)
+        stream.synchronize()
+        eager = y.clone()
+        ids, w, *_ = dxo.route(logits, wl.k)
+        y_ref = dxo.moe_forward(ly.versions, wl.d, wl.f, wl.group, x, ids, w)
+        assert rel_l2(LY.device_to_bits(eager), y_ref) <= REL_L2_TOL
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            rb.route(ctx, 0, ld, T)
+            rb.forward(ctx, 0, xd, y, None, T)
+        for rep in range(4):
+            y.zero_()                                  # eager work between the replays
+            rb.perm.zero_()
+            stream.synchronize()
+            g.replay()
+            stream.synchronize()
+            assert torch.equal(y, eager), rep
+        # new inputs in the same buffers: the replay follows them
+        x2, logits2 = W.layer_inputs(wl, seed=10)
+        xd.copy_(LY.bits_to_device(x2))
+        ld.copy_(torch.from_numpy(logits2).cuda())
+        stream.synchronize()
+        g.replay()
+        stream.synchronize()
+        ids2, w2, *_ = dxo.route(logits2, wl.k)
+        assert np.array_equal(rb.ids.cpu().numpy()[:T], ids2)
+        y_ref2 = dxo.moe_forward(ly.versions, wl.d, wl.f, wl.group, x2, ids2, w2)
+        assert rel_l2(LY.device_to_bits(y), y_ref2) <= REL_L2_TOL
+        del g
+    ly.ctx.close()
