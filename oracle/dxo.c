@@ -48,11 +48,13 @@
 
 #define DXO_FMT_BF16 0
 #define DXO_FMT_INT4 1
+#define DXO_FMT_INT2 2
 
 /* one stored expert version, host pointers */
 typedef struct {
-    const void *w_gate, *w_up, *w_down;   /* bf16 [f,d],[f,d],[d,f]  or packed u8 [f,d/2],[f,d/2],[d,f/2] */
-    const void *s_gate, *s_up, *s_down;   /* bf16 scales [rows, K/group] (int4 only) */
+    const void *w_gate, *w_up, *w_down;   /* bf16 [f,d],[f,d],[d,f]  or packed u8 [f,d/2],[f,d/2],[d,f/2] (int4),
+                                             [f,d/4],[f,d/4],[d,f/4] (int2) */
+    const void *s_gate, *s_up, *s_down;   /* bf16 scales [rows, K/group] (int4 and int2) */
     int32_t fmt;
     int32_t pad;
 } dxo_expert;
@@ -201,6 +203,53 @@ int dxo_quantize(const uint16_t *w, int rows, int K, int group, uint8_t *q, uint
     return 0;
 }
 
+/* The second precision pair of Sec. 4 (int4 as the high tier, int2 as the low
+ * one): the same symmetric group quantizer at 2 bits.  The paper names no
+ * format; this is the int4 rule with its constants moved to 2 bits:
+ * scale = bf16_rne(absmax / q_max) with q_max = 2^(b-1) - 1 = 1, code =
+ * clamp(rint(w / scale), -2, 1), two's complement, element i in bits
+ * 2*(i%4).. of byte i/4.  [rows, K] bf16 -> [rows, K/4] bytes + scales. */
+int dxo_quantize2(const uint16_t *w, int rows, int K, int group, uint8_t *q, uint16_t *s)
+{
+    if (rows < 0 || K <= 0 || group <= 0 || (K % group) || (group & 3)) return 1;
+    int G = K / group;
+    for (int r = 0; r < rows; ++r) {
+        for (int g = 0; g < G; ++g) {
+            const uint16_t *src = w + (size_t)r * K + (size_t)g * group;
+            float amax = 0.0f;
+            for (int i = 0; i < group; ++i) {
+                float a = fabsf(bf16_widen(src[i]));
+                if (a > amax) amax = a;
+            }
+            uint16_t sb = bf16_round(amax / 1.0f);
+            float sc = bf16_widen(sb);
+            s[(size_t)r * G + g] = sb;
+            for (int i = 0; i < group; i += 4) {
+                unsigned byte = 0;
+                for (int h = 0; h < 4; ++h) {
+                    int v = 0;
+                    if (sc != 0.0f) {
+                        float x = rintf(bf16_widen(src[i + h]) / sc);
+                        if (x < -2.0f) x = -2.0f;
+                        if (x > 1.0f) x = 1.0f;
+                        v = (int)x;
+                    }
+                    byte |= (unsigned)(v & 0x3) << (2 * h);
+                }
+                q[(size_t)r * (K / 4) + ((size_t)g * group + i) / 4] = (uint8_t)byte;
+            }
+        }
+    }
+    return 0;
+}
+
+/* signed value of the 2-bit code `idx` of a packed row */
+static int crumb_at(const uint8_t *row, int idx)
+{
+    int v = (row[idx >> 2] >> (2 * (idx & 3))) & 0x3;
+    return v >= 2 ? v - 4 : v;
+}
+
 /* signed value of nibble `idx` of a packed row */
 static int nibble_at(const uint8_t *row, int idx)
 {
@@ -214,9 +263,21 @@ static float weight_at(const void *wptr, const void *sptr, int fmt, int K, int g
 {
     if (fmt == DXO_FMT_BF16)
         return bf16_widen(((const uint16_t *)wptr)[(size_t)row * K + col]);
-    const uint8_t *qrow = (const uint8_t *)wptr + (size_t)row * (K / 2);
     uint16_t sb = ((const uint16_t *)sptr)[(size_t)row * (K / group) + col / group];
+    if (fmt == DXO_FMT_INT2)
+        return (float)crumb_at((const uint8_t *)wptr + (size_t)row * (K / 4), col) * bf16_widen(sb);
+    const uint8_t *qrow = (const uint8_t *)wptr + (size_t)row * (K / 2);
     return (float)nibble_at(qrow, col) * bf16_widen(sb);
+}
+
+/* packed int2 + scales -> fp32 matrix [rows, K] */
+int dxo_dequantize2(const uint8_t *q, const uint16_t *s, int rows, int K, int group, float *out)
+{
+    if (rows < 0 || K <= 0 || group <= 0 || (K % group) || (K & 3)) return 1;
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < K; ++c)
+            out[(size_t)r * K + c] = weight_at(q, s, DXO_FMT_INT2, K, group, r, c);
+    return 0;
 }
 
 /* packed int4 + scales -> fp32 matrix [rows, K] */
@@ -325,6 +386,7 @@ uint64_t dxo_expert_bytes(int d, int f, int group, int fmt)
 {
     uint64_t params = 3ull * (uint64_t)d * (uint64_t)f;
     if (fmt == DXO_FMT_BF16) return 2ull * params;
+    if (fmt == DXO_FMT_INT2) return params / 4ull + 2ull * (params / (uint64_t)group);
     return params / 2ull + 2ull * (params / (uint64_t)group);
 }
 

@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libdxo.so")
 
 FMT_BF16 = 0
 FMT_INT4 = 1
+FMT_INT2 = 2
 
 
 def build(force: bool = False) -> str:
@@ -133,6 +134,29 @@ def dequantize(q: np.ndarray, s: np.ndarray, group: int) -> np.ndarray:
     return out
 
 
+def quantize2(w_bits: np.ndarray, group: int):
+    """bf16 bits [rows,K] -> (packed 2-bit codes u8 [rows,K/4], bf16 scale bits [rows,K/group])."""
+    w_bits = np.ascontiguousarray(w_bits, np.uint16)
+    rows, K = w_bits.shape
+    q = np.empty((rows, K // 4), np.uint8)
+    s = np.empty((rows, K // group), np.uint16)
+    rc = lib().dxo_quantize2(_p(w_bits), C.c_int(rows), C.c_int(K), C.c_int(group), _p(q), _p(s))
+    if rc:
+        raise ValueError(f"dxo_quantize2 rc={rc}")
+    return q, s
+
+
+def dequantize2(q: np.ndarray, s: np.ndarray, group: int) -> np.ndarray:
+    q = np.ascontiguousarray(q, np.uint8)
+    s = np.ascontiguousarray(s, np.uint16)
+    rows, K = q.shape[0], q.shape[1] * 4
+    out = np.empty((rows, K), np.float32)
+    rc = lib().dxo_dequantize2(_p(q), _p(s), C.c_int(rows), C.c_int(K), C.c_int(group), _p(out))
+    if rc:
+        raise ValueError(f"dxo_dequantize2 rc={rc}")
+    return out
+
+
 # ------------------------------------------------------------------- layer
 class ExpertVersion:
     """One stored version of an expert: bf16 matrices, or int4 + scales."""
@@ -150,6 +174,11 @@ class ExpertVersion:
     def int4_from_master(cls, wg, wu, wd, group):
         (qg, sg), (qu, su), (qd, sd) = (quantize(m, group) for m in (wg, wu, wd))
         return cls(FMT_INT4, qg, qu, qd, sg, su, sd)
+
+    @classmethod
+    def int2_from_master(cls, wg, wu, wd, group):
+        (qg, sg), (qu, su), (qd, sd) = (quantize2(m, group) for m in (wg, wu, wd))
+        return cls(FMT_INT2, qg, qu, qd, sg, su, sd)
 
     def struct(self) -> _Expert:
         ptr = [a.ctypes.data if a is not None else None for a in self.arrays]

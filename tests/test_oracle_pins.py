@@ -183,6 +183,75 @@ def test_quantizer_numpy_fp32_cross_check(dxo):
     assert np.array_equal(_signed_nibbles(q), codes)
 
 
+def _signed_crumbs(q):
+    out = np.empty(q.shape[:-1] + (q.shape[-1] * 4,), np.int16)
+    for h in range(4):
+        out[..., h::4] = (q >> (2 * h)) & 0x3
+    return np.where(out >= 2, out - 4, out)
+
+
+def test_int2_quantizer_codes_packing_and_bounds(dxo):
+    # absmax 1 -> scale exactly 1; .5 ties go to the even code; the range is {-1, 0, 1} (q_max = 1)
+    row = np.zeros(32, np.float32)
+    vals = [1.0, 0.5, 0.75, -0.5, -0.75, -1.0, 0.25, 0.0]
+    row[:len(vals)] = vals
+    q, s = dxo.quantize2(_bits(row)[None, :], 32)
+    assert bf16_bits_to_f32(s)[0, 0] == 1.0
+    assert _signed_crumbs(q)[0, :len(vals)].tolist() == [1, 0, 1, 0, -1, -1, 0, 0]
+    # byte i holds elements 4i .. 4i+3, element 4i in the two low bits, two's complement
+    assert q[0, 0] == (1 & 3) | ((0 & 3) << 2) | ((1 & 3) << 4) | ((0 & 3) << 6)
+    assert q[0, 1] == ((-1) & 3) | (((-1) & 3) << 2)
+    g = np.random.default_rng(41)
+    group = 64
+    wb = _bits(0.02 * g.standard_normal((24, 512)))
+    wv = bf16_bits_to_f32(wb).astype(np.float64)
+    q, s = dxo.quantize2(wb, group)
+    sv = np.repeat(bf16_bits_to_f32(s).astype(np.float64), group, axis=1)
+    codes = _signed_crumbs(q).astype(np.float64)
+    assert set(np.unique(codes).tolist()) <= {-1.0, 0.0, 1.0}
+    deq = dxo.dequantize2(q, s, group).astype(np.float64)
+    assert np.array_equal(deq, codes * sv)
+    assert np.all(np.abs(deq - wv) <= sv / 2 + np.abs(wv) * 2.0 ** -23)      # half a step
+    amax = np.abs(wv).reshape(24, -1, group).max(2)
+    assert np.array_equal(bf16_bits_to_f32(s).astype(np.float64), amax)      # absmax / 1 is already bf16
+    assert np.all(np.abs(codes).reshape(24, -1, group).max(2) == 1)          # the absmax element maps to +-1
+    # independent numpy fp32 formulation
+    w3 = bf16_bits_to_f32(wb).reshape(24, -1, group)
+    sc = np.abs(w3).max(2)
+    ref = np.clip(np.rint(w3 / sc[:, :, None]), -2, 1).astype(np.int16).reshape(24, -1)
+    assert np.array_equal(_signed_crumbs(q), ref)
+    # on-grid weights come back exactly; an all-zero group has scale 0 and codes 0
+    c = g.integers(-1, 2, (4, 128)).astype(np.float32)
+    c[:, ::group] = 1.0
+    w = c * np.repeat((2.0 ** g.integers(-8, -2, (4, 2))).astype(np.float32), group, axis=1)
+    w[1, :group] = 0.0
+    q, s = dxo.quantize2(_bits(w), group)
+    assert np.array_equal(dxo.dequantize2(q, s, group), w)
+    assert bf16_bits_to_f32(s)[1, 0] == 0.0 and np.all(q[1, :group // 4] == 0)
+    with pytest.raises(ValueError):
+        dxo.quantize2(np.zeros((2, 96), np.uint16), 64)
+
+
+def test_int2_experts_in_the_layer_equal_dense_on_dequantised_weights(dxo):
+    """A table of int4 and int2 experts (the second precision pair): the layer output is the dense MoE
+    on the dequantised matrices; byte sizes follow the format."""
+    x, ids, w, masters, versions, (T, d, f, E, k, group) = _tiny_layer(dxo, 24, n_int4=2)
+    versions = [dxo.ExpertVersion.int2_from_master(*masters[e], group) if e % 2 else
+                dxo.ExpertVersion.int4_from_master(*masters[e], group) for e in range(E)]
+    y = dxo.moe_forward(versions, d, f, group, x, ids, w)
+    ref = np.zeros((T, d))
+    for t in range(T):
+        for j in range(k):
+            e = int(ids[t, j])
+            a = versions[e].arrays
+            deq = dxo.dequantize2 if versions[e].fmt == dxo.FMT_INT2 else dxo.dequantize
+            mats = [deq(a[i], a[3 + i], group) for i in range(3)]
+            ref[t] += w[t, j] * _torch_expert(*mats, bf16_bits_to_f32(x[t:t + 1])).numpy()[0]
+    assert np.allclose(y, ref, rtol=1e-11, atol=1e-13)
+    assert dxo.expert_bytes(2048, 512, 128, dxo.FMT_INT2) == 3 * 2048 * 512 // 4 + 2 * 3 * 2048 * 512 // 128
+    assert dxo.expert_bytes(2048, 512, 128, dxo.FMT_INT4) == 3 * 2048 * 512 // 2 + 2 * 3 * 2048 * 512 // 128
+
+
 def test_quantizer_rejects_bad_shapes(dxo):
     wb = np.zeros((2, 96), np.uint16)
     with pytest.raises(ValueError):
