@@ -26,7 +26,6 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-C2_LAYER_BUDGET = 535560192   # bytes: 32 bf16 + 96 int4 experts of the 30B shape
 
 
 def parse():
@@ -39,6 +38,8 @@ def parse():
                          "C5: a decode stack whose hot set drifts, with live promotions and demotions")
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets to rotate over")
     ap.add_argument("--window", type=int, default=None, help="routing-only warm-up steps per layer for hotness")
+    ap.add_argument("--pair", default="bf16-int4", choices=["bf16-int4", "int4-int2"],
+                    help="precision pair of the C2/C3 layer: high tier for the resident experts, low tier for the rest")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="time the C2/C3 layer shape at T = 1, 2, 4, ... 8192 tokens per step (one JSON line)")
@@ -276,14 +277,17 @@ def main():
     wl = W.WORKLOADS[args.workload]
     L, T, E, k, d, f = args.layers, wl.T, wl.E, wl.k, wl.d, wl.f
     seed = args.seed
-    b_hi = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_BF16)
-    b_lo = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_INT4G)
+    quant_pair = args.pair == "int4-int2"
+    hi_fmt = B.DX_FMT_INT4G if quant_pair else B.DX_FMT_BF16
+    b_hi = B.dx_expert_bytes(d, f, wl.group, hi_fmt)
+    b_lo = B.dx_expert_bytes(d, f, wl.group, hi_fmt + 1)
+    layer_budget = wl.n_hi * b_hi + (E - wl.n_hi) * b_lo       # 535560192 B for the bf16 / int4 pair
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         ctx = B.Context(L=L, E=E, d=d, f=f, top_k=k, group=wl.group, max_tokens=T,
-                        window_steps=args.window, budget_bytes=L * C2_LAYER_BUDGET,
-                        route_updates_hotness=True, stream=stream.cuda_stream)
+                        window_steps=args.window, budget_bytes=L * layer_budget,
+                        route_updates_hotness=True, stream=stream.cuda_stream, hi_fmt=hi_fmt)
         rb = LY.RoutingBuffers(T, E, k)
         # inputs of every layer: the measured batch plus the warm-up window's router traces
         xs, lgs = [], []
@@ -298,13 +302,16 @@ def main():
                 lg = torch.from_numpy(W.router_logits(wl, xw, wr[layer], seed, layer)).cuda()
                 rb.route(ctx, layer, lg)          # also counts the selections (route_updates_hotness)
         ctx.dx_window_end()
-        resident = [ctx.dx_select_resident(layer, C2_LAYER_BUDGET) for layer in range(L)]
+        resident = [ctx.dx_select_resident(layer, layer_budget) for layer in range(L)]
         assert all(len(r) == wl.n_hi for r in resident), [len(r) for r in resident]
         # weights: draw each layer's masters on the device, keep bf16 for the resident set, int4 for the rest
         layers = []
         for layer in range(L):
             wg, wu, wd = W.device_masters(wl, seed, layer)
-            layers.append(LY.LayerWeights(ctx, layer, wg, wu, wd, resident[layer], wl.group, keep_masters=False))
+            if quant_pair:
+                layers.append(LY.QuantPairLayerWeights(ctx, layer, wg, wu, wd, resident[layer], wl.group))
+            else:
+                layers.append(LY.LayerWeights(ctx, layer, wg, wu, wd, resident[layer], wl.group, keep_masters=False))
             del wg, wu, wd
         y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
         stream.synchronize()
@@ -344,7 +351,9 @@ def main():
                 alg_bytes += float((act & hi).sum() * (2 * b_hi // 3) + (act & ~hi).sum() * (2 * b_lo // 3) + T * d * 2)
                 # prefill: the 256-row tile kernel multiplies the leading multiple of 256 rows of every bf16
                 # segment: 2 * rows * d * 2f each
-                alg_flops += float((counts[hi] // 256 * 256).sum()) * 2.0 * d * 2 * f
+                # (no bf16 experts in the int4 / int2 pair: there the 128-row tile kernel takes every segment above 32)
+                rows = (counts[hi] // 256 * 256).sum() if not quant_pair else counts[counts > 32].sum()
+                alg_flops += float(rows) * 2.0 * d * 2 * f
         prof = ctx.dx_get_profile()
         ctx.dx_set_profiling(False)
         n_alg = min(args.steps, L)
@@ -361,7 +370,7 @@ def main():
     else:
         achieved = flops_per_launch / (gate_up_us * 1e-6) / 1e12
         step_flops = float(T * k) * 2.0 * d * 3 * f      # all routed pairs through gate, up and down
-        roofline = {"bound": "mfma", "kernel": "k_big<gate/up>", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+        roofline = {"bound": "mfma", "kernel": "k_tiled<gate/up>" if quant_pair else "k_big<gate/up>", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                     "algorithmic_flops_per_launch": flops_per_launch, "avg_launch_us": gate_up_us,
                     "note": "timed while the 128-row tile and streaming kernels of the same pass run beside it "
@@ -370,7 +379,7 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "k_stream_gate_up_C2_decode_pmc.txt" if decode
                          else "k_big_gate_up_C3_prefill_pmc.txt")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not quant_pair:
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
@@ -391,7 +400,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: 30B-A3B-shaped MoE layer, {'decode' if decode else 'prefill'} T={T}, d={d}, f={f}, E={E}, top-{k}, "
-                               f"Zipf(s={wl.zipf_s}) routing, {wl.n_hi} bf16 + {E - wl.n_hi} int4-g{wl.group} experts "
+                               f"Zipf(s={wl.zipf_s}) routing, {wl.n_hi} {'int4' if quant_pair else 'bf16'} + {E - wl.n_hi} "
+                               f"{'int2' if quant_pair else 'int4'}-g{wl.group} experts "
                                f"per layer, rotating over {L} layers' weights",
                    "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
@@ -405,8 +415,12 @@ def main():
         from oracle import dxo
         wg, wu, wd = (LY.device_to_bits(m) for m in W.device_masters(wl, seed, 0))
         res0 = set(int(e) for e in resident[0])
-        versions = [dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if e in res0
-                    else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(E)]
+        if quant_pair:
+            versions = [dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) if e in res0
+                        else dxo.ExpertVersion.int2_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(E)]
+        else:
+            versions = [dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if e in res0
+                        else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(E)]
         if decode:
             batches = [W.layer_inputs(wl, seed, 0, step=i) for i in range(400)]
             calls, y_ref0, ids0 = 0, None, None

@@ -41,7 +41,7 @@ typedef enum {
 
 /* numeric format of one stored expert version (Sec. 3.2: "multiple weight
  * versions that implement the same operator in different numeric formats") */
-typedef enum { DX_FMT_BF16 = 0, DX_FMT_INT4G = 1 } dx_fmt;
+typedef enum { DX_FMT_BF16 = 0, DX_FMT_INT4G = 1, DX_FMT_INT2G = 2 } dx_fmt;
 
 /* residency state of an expert entry (Sec. 3.2, "Residency states") */
 typedef enum {
@@ -65,7 +65,9 @@ typedef struct {
     uint32_t alpha_q16;   /* EMA factor alpha * 65536, 0 <= alpha_q16 < 65536 (Sec. 3.5) */
     int32_t route_updates_hotness; /* != 0: dx_route itself adds `counts` to the layer's window counters
                                       (the router trace tap of Sec. 4); do not also call dx_hotness_update */
-    int32_t reserved0;
+    int32_t hi_fmt;       /* precision pair (Sec. 4): DX_FMT_BF16 = bf16 high / int4 low (default),
+                             DX_FMT_INT4G = int4 high / int2 low (needs group 64 or 128).  Sets b_hi and
+                             b_lo of the budget rule and which formats count as Resident-Hi. */
     uint64_t budget_bytes;    /* expert-weight budget of the whole stack, steady state */
     uint64_t transient_bytes; /* extra bytes in-flight transitions may hold on top of it */
 } dx_config;
@@ -78,6 +80,8 @@ typedef struct {
  *   int4:  w_gate, w_up [f,d/2] u8, w_down [d,f/2] u8 (element 2i in the low
  *          nibble of byte i, two's complement), s_gate, s_up [f,d/group]
  *          bf16, s_down [d,f/group] bf16.
+ *   int2:  w_gate, w_up [f,d/4] u8, w_down [d,f/4] u8 (element 4i in the two
+ *          low bits of byte i, two's complement), scales as for int4.
  * All pointers 16-byte aligned. */
 typedef struct {
     const void *w_gate, *w_up, *w_down;
@@ -213,6 +217,13 @@ dx_status dx_plan_transitions(dx_ctx *ctx, int layer, const int32_t *target_ids,
  * hip_stream: hipStream_t to run on, NULL = the compute stream. */
 dx_status dx_quantize_expert(dx_ctx *ctx, const void *w_bf16, int rows, int K, int group,
                              void *q_out, void *s_out, void *hip_stream);
+
+/* The same for the low tier of the int4 / int2 pair (Sec. 4): packed 2-bit
+ * codes u8 [rows,K/4] + bf16 scales [rows,K/group]; scale =
+ * bf16_rne(absmax/1), q = clamp(rint(w/scale), -2, 1) -- the int4 rule with
+ * q_max = 2^(bits-1) - 1.  group 32, 64 or 128. */
+dx_status dx_quantize_expert_int2(dx_ctx *ctx, const void *w_bf16, int rows, int K, int group,
+                                  void *q_out, void *s_out, void *hip_stream);
 
 /* Publication (Sec. 3.2, "Non-blocking switching semantics"): replaces the
  * handle of (layer, expert) with *new_version (host pointer to a struct

@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DYNAEXQ_LIB", os.path.join(_PKG, "libdynaexq.so"))
 
 DX_OK, DX_ERR_INVALID, DX_ERR_BUDGET, DX_ERR_BUSY, DX_ERR_NOMEM, DX_ERR_HIP = range(6)
-DX_FMT_BF16, DX_FMT_INT4G = 0, 1
+DX_FMT_BF16, DX_FMT_INT4G, DX_FMT_INT2G = 0, 1, 2
 DX_STATE_EMPTY, DX_STATE_RESIDENT_HI, DX_STATE_RESIDENT_LO, DX_STATE_PROMOTING, DX_STATE_DEMOTING = range(5)
 
 EXPORTS = [
@@ -25,7 +25,7 @@ EXPORTS = [
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
     "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
     "dx_register_host_master", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
-    "dx_quantize_expert", "dx_swap_handle",
+    "dx_quantize_expert", "dx_quantize_expert_int2", "dx_swap_handle",
     "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats",
     "dx_set_profiling", "dx_get_profile",
     "dx_pools_create", "dx_expert_install", "dx_promote_async", "dx_demote_async", "dx_migrate_poll",
@@ -36,7 +36,7 @@ class DxConfig(C.Structure):
     _fields_ = [("L", C.c_int32), ("E", C.c_int32), ("d", C.c_int32), ("f", C.c_int32),
                 ("top_k", C.c_int32), ("group", C.c_int32), ("shared_f", C.c_int32),
                 ("max_tokens", C.c_int32), ("window_steps", C.c_int32), ("alpha_q16", C.c_uint32),
-                ("route_updates_hotness", C.c_int32), ("reserved0", C.c_int32),
+                ("route_updates_hotness", C.c_int32), ("hi_fmt", C.c_int32),
                 ("budget_bytes", C.c_uint64), ("transient_bytes", C.c_uint64)]
 
 
@@ -107,6 +107,7 @@ def load():
     L.dx_select_resident_stable.argtypes = [vp, i32, u64, u64, i32, vp, C.POINTER(C.c_int32)]
     L.dx_plan_transitions.argtypes = [vp, i32, vp, i32, vp, C.POINTER(C.c_int32), vp, C.POINTER(C.c_int32)]
     L.dx_quantize_expert.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+    L.dx_quantize_expert_int2.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     L.dx_swap_handle.argtypes = [vp, i32, i32, C.POINTER(DxHandle), vp]
     L.dx_handle_table.argtypes = [vp, i32]
     L.dx_handle_table.restype = vp
@@ -189,11 +190,12 @@ class Context:
     """Owns one dx_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, *, L, E, d, f, top_k, group, max_tokens, shared_f=0, window_steps=256,
-                 alpha_q16=0, budget_bytes=0, transient_bytes=0, route_updates_hotness=False, stream=None):
+                 alpha_q16=0, budget_bytes=0, transient_bytes=0, route_updates_hotness=False, stream=None,
+                 hi_fmt=DX_FMT_BF16):
         import torch
         self.lib = load()
         self.cfg = DxConfig(L, E, d, f, top_k, group, shared_f, max_tokens, window_steps, alpha_q16,
-                            1 if route_updates_hotness else 0, 0, budget_bytes, transient_bytes)
+                            1 if route_updates_hotness else 0, hi_fmt, budget_bytes, transient_bytes)
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
         self.stream = stream
@@ -265,6 +267,10 @@ class Context:
     def dx_quantize_expert(self, w_bf16, rows, K, group, q_out, s_out, stream=None):
         self._chk(self.lib.dx_quantize_expert(self.h, _ptr(w_bf16), rows, K, group, _ptr(q_out), _ptr(s_out),
                                               C.c_void_p(stream) if stream else None), "dx_quantize_expert")
+
+    def dx_quantize_expert_int2(self, w_bf16, rows, K, group, q_out, s_out, stream=None):
+        self._chk(self.lib.dx_quantize_expert_int2(self.h, _ptr(w_bf16), rows, K, group, _ptr(q_out), _ptr(s_out),
+                                                   C.c_void_p(stream) if stream else None), "dx_quantize_expert_int2")
 
     def dx_swap_handle(self, layer, expert, handle: DxHandle, producer_event=None):
         self._chk(self.lib.dx_swap_handle(self.h, layer, expert, C.byref(handle),

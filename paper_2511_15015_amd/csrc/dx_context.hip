@@ -123,6 +123,7 @@ extern "C" uint64_t dx_expert_bytes(int d, int f, int group, int fmt)
     if (d <= 0 || f <= 0 || group <= 0) return 0;
     const uint64_t params = 3ull * (uint64_t)d * (uint64_t)f;
     if (fmt == DX_FMT_BF16) return params * 2ull;
+    if (fmt == DX_FMT_INT2G) return params / 4ull + (params / (uint64_t)group) * 2ull;
     return params / 2ull + (params / (uint64_t)group) * 2ull;
 }
 
@@ -242,7 +243,8 @@ extern "C" dx_status dx_create(const dx_config *cfg, void *stream, dx_ctx **out)
     if (g.L <= 0 || g.E <= 0 || g.E > 1024 || g.d <= 0 || g.f <= 0 || g.top_k <= 0 || g.top_k > g.E ||
         g.top_k > 64 || !group_ok || g.d % g.group || g.f % g.group || g.d % 32 || g.f % 32 ||
         g.shared_f < 0 || g.shared_f % 32 || (g.shared_f && g.shared_f % g.group) || g.max_tokens <= 0 ||
-        g.alpha_q16 >= 65536u || (uint64_t)g.max_tokens * (uint64_t)(g.top_k + 1) > 0x7FFFFFFFull) {
+        g.alpha_q16 >= 65536u || (g.hi_fmt != DX_FMT_BF16 && g.hi_fmt != DX_FMT_INT4G) ||
+        (g.hi_fmt == DX_FMT_INT4G && g.group < 64) || (uint64_t)g.max_tokens * (uint64_t)(g.top_k + 1) > 0x7FFFFFFFull) {
         g_create_err = "dx_create: invalid configuration";
         return DX_ERR_INVALID;
     }
@@ -250,8 +252,8 @@ extern "C" dx_status dx_create(const dx_config *cfg, void *stream, dx_ctx **out)
     if (!c) return DX_ERR_NOMEM;
     c->cfg = g;
     c->compute = static_cast<hipStream_t>(stream);
-    c->b_hi = dx_expert_bytes(g.d, g.f, g.group, DX_FMT_BF16);
-    c->b_lo = dx_expert_bytes(g.d, g.f, g.group, DX_FMT_INT4G);
+    c->b_hi = dx_expert_bytes(g.d, g.f, g.group, g.hi_fmt);
+    c->b_lo = dx_expert_bytes(g.d, g.f, g.group, g.hi_fmt + 1);
     c->b_shared = g.shared_f ? dx_expert_bytes(g.d, g.shared_f, g.group, DX_FMT_BF16) : 0;
     c->fmax = std::max(g.f, g.shared_f);
     c->n_chunks_max = (g.max_tokens + 63) / 64;
@@ -557,15 +559,33 @@ extern "C" dx_status dx_quantize_expert(dx_ctx *c, const void *w, int rows, int 
     return DX_OK;
 }
 
+extern "C" dx_status dx_quantize_expert_int2(dx_ctx *c, const void *w, int rows, int K, int group, void *q, void *s,
+                                             void *stream)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (rows < 0 || K <= 0 || (group != 32 && group != 64 && group != 128) || K % group)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_quantize_expert_int2: rows=%d K=%d group=%d not supported", rows, K, group);
+    if (rows == 0) return DX_OK;
+    if (!w || !q || !s) DX_FAIL(c, DX_ERR_INVALID, "dx_quantize_expert_int2: null pointer");
+    if (((uintptr_t)w & 15) || ((uintptr_t)q & 1) || ((uintptr_t)s & 1))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_quantize_expert_int2: misaligned pointer");
+    hipStream_t st = stream ? static_cast<hipStream_t>(stream) : c->compute;
+    DX_HIP(c, dxk_quantize2(static_cast<const dx_bf16 *>(w), rows, K, group, static_cast<uint8_t *>(q),
+                            static_cast<dx_bf16 *>(s), st));
+    return DX_OK;
+}
+
 extern "C" dx_status dx_swap_handle(dx_ctx *c, int layer, int expert, const dx_handle *nv, void *producer_event)
 {
     if (!c) return DX_ERR_INVALID;
     if (!valid_layer(c, layer) || !valid_expert(c, expert, true) || !nv)
         DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: bad (layer, expert) = (%d, %d) or null handle", layer, expert);
-    const bool int4 = nv->fmt == DX_FMT_INT4G;
-    if (nv->fmt != DX_FMT_BF16 && !int4) DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: unknown format %u", nv->fmt);
-    if (expert == c->cfg.E && int4) DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: the shared expert is bf16 only");
-    if (!nv->w_gate || !nv->w_up || !nv->w_down || (int4 && (!nv->s_gate || !nv->s_up || !nv->s_down)))
+    const bool quant = nv->fmt == DX_FMT_INT4G || nv->fmt == DX_FMT_INT2G;
+    if (nv->fmt != DX_FMT_BF16 && !quant) DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: unknown format %u", nv->fmt);
+    if (nv->fmt == DX_FMT_INT2G && c->cfg.group < 64)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: the int2 format needs a group of 64 or 128");
+    if (expert == c->cfg.E && quant) DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: the shared expert is bf16 only");
+    if (!nv->w_gate || !nv->w_up || !nv->w_down || (quant && (!nv->s_gate || !nv->s_up || !nv->s_down)))
         DX_FAIL(c, DX_ERR_INVALID, "dx_swap_handle: null weight or scale pointer");
     const uintptr_t all = (uintptr_t)nv->w_gate | (uintptr_t)nv->w_up | (uintptr_t)nv->w_down |
                           (uintptr_t)nv->s_gate | (uintptr_t)nv->s_up | (uintptr_t)nv->s_down;
@@ -582,11 +602,13 @@ extern "C" dx_status dx_swap_handle(dx_ctx *c, int layer, int expert, const dx_h
     if (en.pool >= 0) DX_FAIL(c, DX_ERR_BUSY, "dx_swap_handle: expert (%d,%d) is pool-managed; use the transition calls", layer, expert);
     dx_status s = publish(c, idx, *nv);
     if (s != DX_OK) return s;
+    // high tier: the context's hi_fmt (or anything above it); everything below is the low tier
+    const bool is_hi = expert == c->cfg.E || (int)nv->fmt <= c->cfg.hi_fmt;
     if (expert < c->cfg.E) {
         if (en.state == DX_STATE_RESIDENT_HI) c->hi_count[layer]--;
-        if (!int4) c->hi_count[layer]++;
+        if (is_hi) c->hi_count[layer]++;
     }
-    en.state = int4 ? DX_STATE_RESIDENT_LO : DX_STATE_RESIDENT_HI;
+    en.state = is_hi ? DX_STATE_RESIDENT_HI : DX_STATE_RESIDENT_LO;
     return DX_OK;
 }
 
@@ -662,6 +684,8 @@ extern "C" dx_status dx_get_profile(dx_ctx *c, dx_profile *out)
 extern "C" dx_status dx_pools_create(dx_ctx *c, int hi_blocks, int lo_blocks)
 {
     if (!c) return DX_ERR_INVALID;
+    if (c->cfg.hi_fmt != DX_FMT_BF16)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: pools and transitions are built for the bf16 / int4 pair only");
     if (hi_blocks < 0 || lo_blocks < 0) DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: negative block count");
     if (c->pool_hi.base || c->pool_lo.base || c->staging) DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: pools already exist");
     const size_t hi_b = round256(std::max(c->b_hi, c->b_shared)), lo_b = round256(c->b_lo);

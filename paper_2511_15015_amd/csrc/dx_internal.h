@@ -121,6 +121,7 @@ hipError_t dxk_store_handle(dx_handle *slot, const dx_handle &h, hipStream_t s);
 
 // dx_quantize.hip
 hipError_t dxk_quantize(const dx_bf16 *w, int rows, int K, int group, uint8_t *q, dx_bf16 *sc, hipStream_t s);
+hipError_t dxk_quantize2(const dx_bf16 *w, int rows, int K, int group, uint8_t *q, dx_bf16 *sc, hipStream_t s); // 2-bit
 
 // dx_moe_decode.hip / dx_moe_prefill.hip
 struct dx_fwd_args {

@@ -84,6 +84,34 @@ __device__ __forceinline__ bf16x8 nibbles_to_biased_bf16(uint32_t word)
     return out.v;
 }
 
+// int2 (the low tier of the int4 / int2 pair): XOR with binary 10 turns a two's-complement code q in
+// [-2, 1] into u = q + 2 in [0, 3]; OR-ed into bf16 128.0 it is 130 + q.  A word holds 16 codes; one
+// shift and one and-or yield elements t and t+8, so the first MFMA step of a word takes elements
+// (0,8,1,9,2,10,3,11) (shifts 0,2,4,6) and the second (4,12,5,13,6,14,7,15) (shifts 8..14).
+constexpr float kCrumbBias = 130.f;
+
+template <int HALF>
+__device__ __forceinline__ bf16x8 crumbs_to_biased_bf16(uint32_t word)
+{
+    const uint32_t u = (word ^ 0xAAAAAAAAu) >> (8 * HALF);
+    frag8 out;
+    out.u = u32x4{(u & 0x00030003u) | 0x43004300u, ((u >> 2) & 0x00030003u) | 0x43004300u,
+                  ((u >> 4) & 0x00030003u) | 0x43004300u, ((u >> 6) & 0x00030003u) | 0x43004300u};
+    return out.v;
+}
+
+// the matching order for two consecutive token fragments a = (e0..e7), b = (e8..e15):
+// lo = (e0,e8,e1,e9,e2,e10,e3,e11), hi = (e4,e12,e5,e13,e6,e14,e7,e15)
+__device__ __forceinline__ void zip_fragments(u32x4 &a, u32x4 &b)
+{
+    const u32x4 lo = u32x4{(a.x & 0x0000FFFFu) | (b.x << 16), (a.x >> 16) | (b.x & 0xFFFF0000u),
+                           (a.y & 0x0000FFFFu) | (b.y << 16), (a.y >> 16) | (b.y & 0xFFFF0000u)};
+    const u32x4 hi = u32x4{(a.z & 0x0000FFFFu) | (b.z << 16), (a.z >> 16) | (b.z & 0xFFFF0000u),
+                           (a.w & 0x0000FFFFu) | (b.w << 16), (a.w >> 16) | (b.w & 0xFFFF0000u)};
+    a = lo;
+    b = hi;
+}
+
 // the same element order for a token fragment: (e0..e7) -> (e0,e4,e1,e5,e2,e6,e3,e7)
 __device__ __forceinline__ u32x4 interleave_halves(u32x4 v)
 {
@@ -104,6 +132,12 @@ constexpr int kLoUnits = DOWN ? 5 : 4;
 // 3 us, one and a half bf16 pairs): every expert's range begins with this many units that carry no
 // strips, so the block that holds an expert boundary gets correspondingly fewer strips.
 constexpr uint32_t kRunUnits = 12;
+// int2 pairs (an eighth of the bytes, the same per-step work) are taken one unit below the int4 ones
+template <bool DOWN>
+__device__ __forceinline__ uint32_t units_of(uint32_t fmt)
+{
+    return fmt == DX_FMT_BF16 ? kHiUnits : (fmt == DX_FMT_INT4G ? kLoUnits<DOWN> : kLoUnits<DOWN> - 1);
+}
 
 #ifdef DX_TRACE
 // Debug build only: per-block start/end time stamps (100 MHz wall clock).
@@ -111,23 +145,25 @@ __device__ unsigned long long g_trace[2][8192][4];
 #endif
 
 // element offset inside a chunk of MFMA step j for lane quarter q
-template <int LK, bool INT4>
+// FMT: 0 bf16, 1 int4, 2 int2 (the values of dx_fmt)
+template <int LK, int FMT>
 __device__ __forceinline__ int k_of(int j, int q)
 {
-    return INT4 ? q * LK + 8 * j : 32 * j + 8 * q;
+    return FMT ? q * LK + 8 * j : 32 * j + 8 * q;
 }
 
 // weight registers of one wavefront for one 16-row strip: CPW chunks
-template <int LK, int CPW, bool INT4>
+template <int LK, int CPW, int FMT>
 struct wstage {
     static constexpr int JN = LK / 8;
-    u32x4 w[CPW][INT4 ? 1 : JN];    // bf16: JN 16-byte pieces per chunk
-    uint32_t wq[CPW][INT4 ? JN : 1]; // int4: JN words of 8 nibbles
-    uint32_t sc[CPW];               // int4: bf16 bits of the chunk's group scale
+    static constexpr int NQ = FMT == 1 ? JN : (FMT == 2 ? (JN + 1) / 2 : 1);
+    u32x4 w[CPW][FMT ? 1 : JN]; // bf16: JN 16-byte pieces per chunk
+    uint32_t wq[CPW][NQ];       // int4: JN words of 8 nibbles; int2: JN/2 words of 16 codes
+    uint32_t sc[CPW];           // int4, int2: bf16 bits of the chunk's group scale
 };
 
-template <int LK, int CPW, bool INT4>
-__device__ __forceinline__ void issue_weights(wstage<LK, CPW, INT4> &st, gbytes row, gbf16 srow, int c0, int nc, int q,
+template <int LK, int CPW, int FMT>
+__device__ __forceinline__ void issue_weights(wstage<LK, CPW, FMT> &st, gbytes row, gbf16 srow, int c0, int nc, int q,
                                               int group)
 {
     constexpr int CHUNK = 4 * LK, JN = LK / 8;
@@ -135,7 +171,18 @@ __device__ __forceinline__ void issue_weights(wstage<LK, CPW, INT4> &st, gbytes 
     for (int i = 0; i < CPW; ++i) {
         const int c = c0 + i;
         if (c < nc) { // wavefront-uniform
-            if constexpr (INT4) {
+            if constexpr (FMT == 2) {
+                gbytes p = row + ((c * CHUNK + q * LK) >> 2);
+                if constexpr (LK == 32) {
+                    const u32x2 t = *reinterpret_cast<gvec8>(p);
+                    st.wq[i][0] = t.x; st.wq[i][1] = t.y;
+                } else if constexpr (LK == 16) {
+                    st.wq[i][0] = *reinterpret_cast<gvec4>(p);
+                } else { // 8 codes = 2 bytes (handles of this format are refused for group 32; kept in bounds)
+                    st.wq[i][0] = *reinterpret_cast<const DX_GLOBAL uint16_t *>(p);
+                }
+                st.sc[i] = srow[(c * CHUNK) / group];
+            } else if constexpr (FMT == 1) {
                 gbytes p = row + ((c * CHUNK + q * LK) >> 1);
                 if constexpr (LK == 32) {
                     const u32x4 t = *reinterpret_cast<gvec16>(p);
@@ -150,13 +197,13 @@ __device__ __forceinline__ void issue_weights(wstage<LK, CPW, INT4> &st, gbytes 
             } else {
 #pragma unroll
                 for (int j = 0; j < JN; ++j)
-                    st.w[i][j] = *reinterpret_cast<gvec16>(row + (size_t)(c * CHUNK + k_of<LK, false>(j, q)) * 2);
+                    st.w[i][j] = *reinterpret_cast<gvec16>(row + (size_t)(c * CHUNK + k_of<LK, 0>(j, q)) * 2);
             }
         }
     }
 }
 
-template <int LK, int CPW, bool INT4, int MT>
+template <int LK, int CPW, int FMT, int MT>
 __device__ __forceinline__ void load_tokens(u32x4 (&x)[CPW][MT][LK / 8], gbf16 arow0, gbf16 arow1, int c0, int nc,
                                             int q)
 {
@@ -169,7 +216,7 @@ __device__ __forceinline__ void load_tokens(u32x4 (&x)[CPW][MT][LK / 8], gbf16 a
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int j = 0; j < JN; ++j)
-                    x[i][mt][j] = *reinterpret_cast<gvec16>((mt ? arow1 : arow0) + c * CHUNK + k_of<LK, INT4>(j, q));
+                    x[i][mt][j] = *reinterpret_cast<gvec16>((mt ? arow1 : arow0) + c * CHUNK + k_of<LK, FMT>(j, q));
         }
     }
 }
@@ -177,8 +224,8 @@ __device__ __forceinline__ void load_tokens(u32x4 (&x)[CPW][MT][LK / 8], gbf16 a
 // int4 runs: bring the token fragments into the element order of nibbles_to_biased_bf16 and compute
 // bias[i][mt] = 136 * sum over chunk i of the token row (one MFMA against all-ones per step), laid out
 // like an accumulator (every column holds the row's sum).
-template <int LK, int CPW, int MT>
-__device__ __forceinline__ void prepare_int4_tokens(u32x4 (&x)[CPW][MT][LK / 8], f32x4 (&bias)[CPW][MT], int c0, int nc)
+template <int LK, int CPW, int MT, int FMT>
+__device__ __forceinline__ void prepare_quant_tokens(u32x4 (&x)[CPW][MT][LK / 8], f32x4 (&bias)[CPW][MT], int c0, int nc)
 {
     constexpr int JN = LK / 8;
     frag8 ones;
@@ -194,29 +241,35 @@ __device__ __forceinline__ void prepare_int4_tokens(u32x4 (&x)[CPW][MT][LK / 8],
                     frag8 a;
                     a.u = x[i][mt][j];
                     sum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, ones.v, sum, 0, 0, 0);
-                    x[i][mt][j] = interleave_halves(x[i][mt][j]);
+                    if constexpr (FMT == 1) x[i][mt][j] = interleave_halves(x[i][mt][j]);
                 }
-                bias[i][mt] = sum * kNibbleBias;
+                if constexpr (FMT == 2) {
+#pragma unroll
+                    for (int j = 0; j + 1 < JN; j += 2) zip_fragments(x[i][mt][j], x[i][mt][j + 1]);
+                }
+                bias[i][mt] = sum * (FMT == 1 ? kNibbleBias : kCrumbBias);
             }
         }
     }
 }
 
-template <int LK, int CPW, bool INT4, int MT>
-__device__ __forceinline__ void multiply(const wstage<LK, CPW, INT4> &st, const u32x4 (&x)[CPW][MT][LK / 8],
+template <int LK, int CPW, int FMT, int MT>
+__device__ __forceinline__ void multiply(const wstage<LK, CPW, FMT> &st, const u32x4 (&x)[CPW][MT][LK / 8],
                                          const f32x4 (&bias)[CPW][MT], int c0, int nc, f32x4 (&acc)[MT])
 {
     constexpr int JN = LK / 8;
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
         if (c0 + i < nc) {
-            if constexpr (INT4) {
+            if constexpr (FMT != 0) {
                 f32x4 part[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) part[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int j = 0; j < JN; ++j) {
-                    const bf16x8 wv = nibbles_to_biased_bf16(st.wq[i][j]);
+                    bf16x8 wv;
+                    if constexpr (FMT == 1) wv = nibbles_to_biased_bf16(st.wq[i][j]);
+                    else wv = (j & 1) ? crumbs_to_biased_bf16<1>(st.wq[i][j / 2]) : crumbs_to_biased_bf16<0>(st.wq[i][j / 2]);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         frag8 a;
@@ -252,7 +305,8 @@ struct expert_ctx {
     int K;           // contraction length
     int G;           // scale groups per row
     int seg0, m;     // segment in the H/O scratch, tokens
-    bool shared, int4;
+    bool shared;
+    int fmt;         // dx_fmt of the published version
 };
 
 // Add up the partial sums of the strip pairs sb .. sb+live_groups-1 in a fixed order and finish them:
@@ -310,7 +364,7 @@ __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_
 // is straight-line code -- every iteration issues the next strip pair's loads unconditionally (the
 // strip index is clamped, so the last iterations of a ragged run fetch a duplicate) -- which lets the
 // compiler wait for exactly the loads it is about to use and keep the prefetch in flight.
-template <int LK, int CPW, bool DOWN, bool INT4, int MT, bool FAST>
+template <int LK, int CPW, bool DOWN, int FMT, int MT, bool FAST>
 __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ctx &ex, int mb, int s_lo, int s_hi,
                                            f32x4 (*red)[kWaves][4][64], int &pb)
 {
@@ -350,25 +404,25 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     f32x4 bias[CPW][MT];
     gbf16 arow0 = nullptr, arow1 = nullptr; // token rows of this run, looked up after the weight prologue
     auto fetch_tokens = [&](int c0) {
-        load_tokens<LK, CPW, INT4, MT>(x, arow0, arow1, c0, ncp, q);
-        if constexpr (INT4) prepare_int4_tokens<LK, CPW, MT>(x, bias, c0, ncp);
+        load_tokens<LK, CPW, FMT, MT>(x, arow0, arow1, c0, ncp, q);
+        if constexpr (FMT != 0) prepare_quant_tokens<LK, CPW, MT, FMT>(x, bias, c0, ncp);
     };
 
     // A step is one 16-row strip: step t = (batch * rounds + round) * 2 + b, b = 0 the first strip of the
     // pair (gate rows / lower 16 down rows), b = 1 the second (up rows / upper 16 down rows).  NST
     // register stages: the strip of step t + NST - 1 is fetched while step t is multiplied.  An int4 strip
     // is a quarter of the bytes, so it gets a deeper pipeline for the same registers.
-    constexpr int NST = INT4 ? 6 : 2;
+    constexpr int NST = FMT ? 6 : 2;
     const int nhalf = 2 * nsteps;
-    wstage<LK, CPW, INT4> st[NST];
-    auto issue_step = [&](int t, wstage<LK, CPW, INT4> &dst) {
+    wstage<LK, CPW, FMT> st[NST];
+    auto issue_step = [&](int t, wstage<LK, CPW, FMT> &dst) {
         const int b = t & 1, sr = t >> 1;
         int s = s_lo + (sr / rounds) * SPP + g;
         s = s < s_hi ? s : s_hi - 1; // ragged tail: fetch a duplicate rather than branch
         const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
         const gbytes p = (b ? ex.w1 : ex.w0) + (size_t)n * ex.row_bytes;
-        const gbf16 sp = INT4 ? (b ? ex.s1 : ex.s0) + (size_t)n * ex.G : nullptr;
-        issue_weights<LK, CPW, INT4>(dst, p, sp, ((sr % rounds) * WPS + kw) * CPW, ncp, q, a.group);
+        const gbf16 sp = FMT ? (b ? ex.s1 : ex.s0) + (size_t)n * ex.G : nullptr;
+        issue_weights<LK, CPW, FMT>(dst, p, sp, ((sr % rounds) * WPS + kw) * CPW, ncp, q, a.group);
     };
 
     f32x4 acc[2][MT];
@@ -377,12 +431,12 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[b][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto do_step = [&](int t, const wstage<LK, CPW, INT4> &cur, int b /* = t & 1, compile-time at every call */) {
+    auto do_step = [&](int t, const wstage<LK, CPW, FMT> &cur, int b /* = t & 1, compile-time at every call */) {
         const int sr = t >> 1;
         const int batch = sr / rounds, rnd = sr % rounds;
         const int c0 = (rnd * WPS + kw) * CPW;
         if (rounds > 1 && b == 0) fetch_tokens(c0);
-        multiply<LK, CPW, INT4, MT>(cur, x, bias, c0, ncp, acc[b]);
+        multiply<LK, CPW, FMT, MT>(cur, x, bias, c0, ncp, acc[b]);
         if (b == 0 || rnd != rounds - 1) return;
         // the strip pairs of this batch are complete: park the partial sums (a clamped duplicate is dropped)
         const bool live = s_lo + batch * SPP + g < s_hi;
@@ -474,8 +528,7 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             seg_tokens[e] = m;
             seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
             if (m > 0)
-                mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * (fmt_of(e) == DX_FMT_INT4G ? kLoUnits<DOWN> : kHiUnits) +
-                          kRunUnits;
+                mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * units_of<DOWN>(fmt_of(e)) + kRunUnits;
             local += mine[i];
         }
     }
@@ -529,17 +582,17 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             ex.m = seg_tokens[e];
             ex.seg0 = seg_start[e];
             const dx_handle hd = ex.shared ? *a.shared : a.table[e];
-            ex.int4 = hd.fmt == DX_FMT_INT4G;
+            ex.fmt = (int)hd.fmt;
             const int fe = ex.shared ? a.shared_f : a.f;
             ex.K = DOWN ? fe : a.d;
             ex.G = ex.K / a.group;
-            ex.row_bytes = ex.int4 ? (size_t)ex.K / 2 : (size_t)ex.K * 2;
+            ex.row_bytes = ex.fmt == DX_FMT_BF16 ? (size_t)ex.K * 2 : (ex.fmt == DX_FMT_INT4G ? (size_t)ex.K / 2 : (size_t)ex.K / 4);
             ex.w0 = (gbytes)(DOWN ? hd.w_down : hd.w_gate);
             ex.w1 = (gbytes)(DOWN ? hd.w_down : hd.w_up);
             ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
             ex.s1 = (gbf16)(DOWN ? hd.s_down : hd.s_up);
             const int spe = strips_of(e);
-            const uint32_t wgt = ex.int4 ? kLoUnits<DOWN> : kHiUnits;
+            const uint32_t wgt = units_of<DOWN>((uint32_t)ex.fmt);
             const uint32_t lo = (ub0 > cum[e] ? ub0 : cum[e]) - cum[e];
             const uint32_t hi = (ub1 < cum[e + 1] ? ub1 : cum[e + 1]) - cum[e];
             // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi); pair i starts
@@ -552,12 +605,18 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
                 const int iend = i1 < (mb + 1) * spe ? i1 : (mb + 1) * spe;
                 const int s_lo = i - mb * spe, s_hi = iend - mb * spe;
                 const bool two = ex.m - mb * 32 > 16;
-                if (ex.int4) {
-                    if (two) run_strips<LK, CPW, DOWN, true, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                    else run_strips<LK, CPW, DOWN, true, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                if (ex.fmt == DX_FMT_INT4G) {
+                    if (two) run_strips<LK, CPW, DOWN, 1, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                    else run_strips<LK, CPW, DOWN, 1, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                } else if (ex.fmt == DX_FMT_INT2G) {
+                    // (16 codes per word: the library refuses int2 handles when the group is 32, i.e. LK = 8)
+                    if constexpr (LK >= 16) {
+                        if (two) run_strips<LK, CPW, DOWN, 2, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                        else run_strips<LK, CPW, DOWN, 2, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                    }
                 } else {
-                    if (two) run_strips<LK, CPW, DOWN, false, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                    else run_strips<LK, CPW, DOWN, false, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                    if (two) run_strips<LK, CPW, DOWN, 0, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                    else run_strips<LK, CPW, DOWN, 0, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
                 }
                 i = iend;
             }

@@ -73,6 +73,20 @@ __device__ __forceinline__ u32x4 dequant8(uint32_t word, float scale)
     return u32x4{p[0], p[1], p[2], p[3]};
 }
 
+// 8 two-bit codes (bits 16*half .. of `word`) times scale -> 8 bf16 in element order
+__device__ __forceinline__ u32x4 dequant8_crumbs(uint32_t word, int half, float scale)
+{
+    const uint32_t h = word >> (16 * half);
+    uint32_t p[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = (float)((int)(h << (30 - 4 * i)) >> 30) * scale;
+        const float hi = (float)((int)(h << (28 - 4 * i)) >> 30) * scale;
+        p[i] = float_to_bf16_rne(lo) | (float_to_bf16_rne(hi) << 16);
+    }
+    return u32x4{p[0], p[1], p[2], p[3]};
+}
+
 struct tile_id {
     int e, mt, nt; // expert (E = shared), row tile, column tile
     int seg0, m;   // first pair slot and number of rows of the part of the segment this kernel owns
@@ -197,16 +211,25 @@ __device__ __forceinline__ void store_a(const a_regs &r, char *tile)
     }
 }
 
-// B tile, bf16: same shape as A.  int4: 128 rows x 32 B: thread t takes row t / 2, half t % 2 (32 nibbles).
+// B tile, bf16: same shape as A.  int4: 128 rows x 32 B: thread t takes row t / 2, half t % 2 (32 nibbles);
+// int2: 128 rows x 16 B, the same split (32 codes = 8 bytes).  FMT: 0 bf16, 1 int4, 2 int2.
 struct b_regs {
-    u32x4 v[4]; // bf16: 4 pieces; int4: v[0] = 32 nibbles
+    u32x4 v[4]; // bf16: 4 pieces; int4: v[0] = 32 nibbles; int2: v[0].x, v[0].y = 32 codes
     uint32_t scale;
 };
 
-template <bool INT4>
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef const DX_GLOBAL u32x2 *gvec8;
+
+template <int FMT>
 __device__ __forceinline__ void load_b(b_regs &r, const gbytes (&rowp)[4], gbytes qrow, gbf16 srow, int k0, int group)
 {
-    if constexpr (INT4) {
+    if constexpr (FMT == 2) {
+        const int half = threadIdx.x & 1;
+        const u32x2 t = *reinterpret_cast<gvec8>(qrow + ((k0 + half * 32) >> 2));
+        r.v[0] = u32x4{t.x, t.y, 0u, 0u};
+        r.scale = srow[(k0 + half * 32) / group];
+    } else if constexpr (FMT == 1) {
         const int half = threadIdx.x & 1;
         r.v[0] = *reinterpret_cast<gvec16>(qrow + ((k0 + half * 32) >> 1));
         r.scale = srow[(k0 + half * 32) / group];
@@ -217,10 +240,18 @@ __device__ __forceinline__ void load_b(b_regs &r, const gbytes (&rowp)[4], gbyte
     }
 }
 
-template <bool INT4>
+template <int FMT>
 __device__ __forceinline__ void store_b(const b_regs &r, char *tile)
 {
-    if constexpr (INT4) {
+    if constexpr (FMT == 2) {
+        const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
+        const float s = bf16_bits_to_float(r.scale);
+        char *dst = tile + row * kRowBytes + half * 64;
+        *reinterpret_cast<u32x4 *>(dst) = dequant8_crumbs(r.v[0].x, 0, s);
+        *reinterpret_cast<u32x4 *>(dst + 16) = dequant8_crumbs(r.v[0].x, 1, s);
+        *reinterpret_cast<u32x4 *>(dst + 32) = dequant8_crumbs(r.v[0].y, 0, s);
+        *reinterpret_cast<u32x4 *>(dst + 48) = dequant8_crumbs(r.v[0].y, 1, s);
+    } else if constexpr (FMT == 1) {
         const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
         const float s = bf16_bits_to_float(r.scale);
         char *dst = tile + row * kRowBytes + half * 64;
@@ -266,14 +297,14 @@ __device__ __forceinline__ int acc_row(int v, int lane) { return (v >> 2) * 8 + 
 
 // One output tile.  INT4 selects the staging of the weight tile at compile time so that the bf16
 // loop carries no trace of the int4 expansion (and the other way round).
-template <bool DOWN, bool INT4>
+template <bool DOWN, int FMT>
 __device__ __forceinline__ void tile_main(const dx_fwd_args &a, const tile_id &t, const dx_handle &hd, char *lds)
 {
-    constexpr bool int4 = INT4;
+    constexpr bool quant = FMT != 0;
     const bool shared = t.e == a.E;
     const int fe = shared ? a.shared_f : a.f;
     const int K = DOWN ? fe : a.d;
-    const size_t wrow_bytes = int4 ? (size_t)K / 2 : (size_t)K * 2;
+    const size_t wrow_bytes = FMT == 0 ? (size_t)K * 2 : (FMT == 1 ? (size_t)K / 2 : (size_t)K / 4);
     const int G = K / a.group;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -320,7 +351,7 @@ __device__ __forceinline__ void tile_main(const dx_fwd_args &a, const tile_id &t
         int n;
         wrow_of(tid >> 1, mat, sc, n);
         qrow = mat + (size_t)n * wrow_bytes;
-        srow = int4 ? sc + (size_t)n * G : nullptr;
+        srow = quant ? sc + (size_t)n * G : nullptr;
     }
 
     f32x16 acc[2][2];
@@ -346,20 +377,20 @@ __device__ __forceinline__ void tile_main(const dx_fwd_args &a, const tile_id &t
     const int nk = K / BK;
     auto k_of = [&](int kt) { return (kt < nk ? kt : nk - 1) * BK; };
     load_a(ra[0], arow, 0);
-    load_b<INT4>(rb[0], brow, qrow, srow, 0, a.group);
+    load_b<FMT>(rb[0], brow, qrow, srow, 0, a.group);
     load_a(ra[1], arow, k_of(1));
-    load_b<INT4>(rb[1], brow, qrow, srow, k_of(1), a.group);
+    load_b<FMT>(rb[1], brow, qrow, srow, k_of(1), a.group);
     store_a(ra[0], ta(0));
-    store_b<INT4>(rb[0], tb(0));
+    store_b<FMT>(rb[0], tb(0));
     __syncthreads();
     auto step = [&](int kt, auto parity) {
         constexpr int P = decltype(parity)::value;
         load_a(ra[P], arow, k_of(kt + 2));
-        load_b<INT4>(rb[P], brow, qrow, srow, k_of(kt + 2), a.group);
+        load_b<FMT>(rb[P], brow, qrow, srow, k_of(kt + 2), a.group);
         mma_step(ta(P), tb(P), wm, brow0, brow1, acc);
         if (kt + 1 < nk) {
             store_a(ra[P ^ 1], ta(P ^ 1));
-            store_b<INT4>(rb[P ^ 1], tb(P ^ 1));
+            store_b<FMT>(rb[P ^ 1], tb(P ^ 1));
         }
         __syncthreads();
     };
@@ -404,8 +435,9 @@ __global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
     const tile_id t = find_tile<kThreads, BM, false>(a, ntn_routed, ntn_shared, cum, wave_tot);
     if (!t.valid) return; // block-uniform
     const dx_handle hd = t.e == a.E ? *a.shared : a.table[t.e];
-    if (hd.fmt == DX_FMT_INT4G) tile_main<DOWN, true>(a, t, hd, lds);
-    else tile_main<DOWN, false>(a, t, hd, lds);
+    if (hd.fmt == DX_FMT_INT4G) tile_main<DOWN, 1>(a, t, hd, lds);
+    else if (hd.fmt == DX_FMT_INT2G) tile_main<DOWN, 2>(a, t, hd, lds);
+    else tile_main<DOWN, 0>(a, t, hd, lds);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -75,6 +75,42 @@ class LayerWeights:
                              self.s[0][i], self.s[1][i], self.s[2][i])
 
 
+class QuantPairLayerWeights:
+    """Expert versions of one layer for the int4 (high tier) / int2 (low tier) pair, in caller-owned
+    memory: experts in ``hi_ids`` are published as int4, all others as int2, both produced by the
+    library's quantize kernels from the bf16 masters wg, wu [E,f,d], wd [E,d,f]."""
+
+    def __init__(self, ctx: B.Context, layer: int, wg, wu, wd, hi_ids, group: int):
+        E, f, d = wg.shape
+        assert wu.shape == (E, f, d) and wd.shape == (E, d, f) and wg.dtype == torch.bfloat16 and wg.is_cuda
+        dev = wg.device
+        self.is_hi = np.zeros(E, bool)
+        self.is_hi[np.asarray(sorted(int(e) for e in hi_ids), np.int64)] = True
+        self.sets = {}
+        for fmt, ids, div, quant in ((B.DX_FMT_INT4G, np.flatnonzero(self.is_hi), 2, ctx.dx_quantize_expert),
+                                     (B.DX_FMT_INT2G, np.flatnonzero(~self.is_hi), 4, ctx.dx_quantize_expert_int2)):
+            n = len(ids)
+            q = [torch.empty((n, f, d // div), dtype=torch.uint8, device=dev),
+                 torch.empty((n, f, d // div), dtype=torch.uint8, device=dev),
+                 torch.empty((n, d, f // div), dtype=torch.uint8, device=dev)]
+            sc = [torch.empty((n, f, d // group), dtype=torch.bfloat16, device=dev),
+                  torch.empty((n, f, d // group), dtype=torch.bfloat16, device=dev),
+                  torch.empty((n, d, f // group), dtype=torch.bfloat16, device=dev)]
+            if n:
+                idx = torch.from_numpy(ids).to(dev)
+                for i, m in enumerate((wg, wu, wd)):
+                    src = m.index_select(0, idx).contiguous()
+                    quant(src, src.shape[0] * src.shape[1], src.shape[2], group, q[i], sc[i])
+                    torch.cuda.current_stream().synchronize()
+                    del src
+            self.sets[fmt] = (q, sc, {int(e): i for i, e in enumerate(ids)})
+        for e in range(E):
+            fmt = B.DX_FMT_INT4G if self.is_hi[e] else B.DX_FMT_INT2G
+            q, sc, slot = self.sets[fmt]
+            i = slot[e]
+            ctx.dx_swap_handle(layer, e, B.make_handle(fmt, q[0][i], q[1][i], q[2][i], sc[0][i], sc[1][i], sc[2][i]))
+
+
 class RoutingBuffers:
     """Device buffers written by dx_route and read by dx_moe_forward."""
 

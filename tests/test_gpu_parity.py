@@ -525,3 +525,76 @@ def test_route_and_forward_replay_from_a_captured_graph(B, LY, dxo, T):
         assert rel_l2(LY.device_to_bits(y), y_ref2) <= REL_L2_TOL
         del g
     ly.ctx.close()
+
+
+# ------------------------------------------- the int4 (high) / int2 (low) precision pair
+@pytest.mark.parametrize("rows,K,group", [(128, 256, 64), (768, 2048, 128), (37, 128, 32), (2048, 768, 128)])
+def test_int2_quantize_bit_exact(B, LY, dxo, rows, K, group):
+    g = np.random.default_rng(rows + K)
+    w = (0.02 * g.standard_normal((rows, K))).astype(np.float32)
+    w[0, :group] = 0.0
+    wb = W.f32_to_bf16_bits(w)
+    ctx = B.Context(L=1, E=2, d=64, f=64, top_k=1, group=32, max_tokens=4)
+    q = torch.zeros((rows, K // 4), dtype=torch.uint8, device="cuda")
+    s = torch.zeros((rows, K // group), dtype=torch.bfloat16, device="cuda")
+    ctx.dx_quantize_expert_int2(LY.bits_to_device(wb), rows, K, group, q, s)
+    sync()
+    q_ref, s_ref = dxo.quantize2(wb, group)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(LY.device_to_bits(s), s_ref)
+    ctx.close()
+
+
+def _quant_pair_layer(B, LY, dxo, wl, hi_ids, seed, T):
+    masters = W.layer_masters(wl, seed, 0)
+    ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=max(T, 1), hi_fmt=B.DX_FMT_INT4G)
+    dev = [LY.bits_to_device(m) for m in masters]
+    lw = LY.QuantPairLayerWeights(ctx, 0, *dev, hi_ids, wl.group)
+    wg, wu, wd = masters
+    versions = [dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) if e in set(hi_ids)
+                else dxo.ExpertVersion.int2_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(wl.E)]
+    return ctx, lw, versions
+
+
+@pytest.mark.parametrize("T,E,k,d,f,group,hi_ids", [
+    (16, 8, 2, 256, 128, 64, [1, 6]),          # decode, K-chunks of 64 (16 codes per lane and chunk)
+    (40, 8, 2, 256, 128, 128, [0]),            # two token tiles, chunks of 128
+    (7, 4, 2, 512, 256, 128, []),              # every expert int2
+    (33, 16, 4, 2048, 768, 128, [2, 3, 5]),    # the 30B layer's K extents
+    (300, 4, 2, 256, 128, 64, [0, 2]),         # prefill-sized: 128-row tiles expand int2 on the way to LDS
+    (700, 4, 2, 256, 128, 128, [1]),
+])
+def test_forward_int4_int2_pair(B, LY, dxo, T, E, k, d, f, group, hi_ids):
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k, d=d, f=f, group=group)
+    print(f"int4/int2 pair T={T} E={E} k={k} d={d} f={f} g={group} hi={hi_ids}", flush=True)
+    x, logits = W.layer_inputs(wl, seed=13)
+    ctx, lw, versions = _quant_pair_layer(B, LY, dxo, wl, hi_ids, 13, T)
+    fm = ctx.dx_get_formats()[0]
+    st = ctx.dx_get_states()[0]
+    for e in range(E):
+        assert fm[e] == (B.DX_FMT_INT4G if e in hi_ids else B.DX_FMT_INT2G)
+        assert st[e] == (B.DX_STATE_RESIDENT_HI if e in hi_ids else B.DX_STATE_RESIDENT_LO)
+    rb = LY.RoutingBuffers(T, E, k)
+    y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    rb.route(ctx, 0, torch.from_numpy(logits).cuda())
+    rb.forward(ctx, 0, LY.bits_to_device(x), y)
+    sync()
+    ids, w, *_ = dxo.route(logits, k)
+    assert np.array_equal(rb.ids.cpu().numpy(), ids)
+    y_ref = dxo.moe_forward(versions, d, f, group, x, ids, w)
+    err = rel_l2(LY.device_to_bits(y), y_ref)
+    print("  rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    ctx.close()
+
+
+def test_int2_handles_need_a_group_of_64_or_more(B, LY):
+    with pytest.raises(B.DxError):
+        B.Context(L=1, E=4, d=64, f=64, top_k=2, group=32, max_tokens=4, hi_fmt=B.DX_FMT_INT4G)
+    ctx = B.Context(L=1, E=4, d=64, f=64, top_k=2, group=32, max_tokens=4)
+    buf = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    h = B.make_handle(B.DX_FMT_INT2G, buf, buf, buf, buf, buf, buf)
+    with pytest.raises(B.DxError):
+        ctx.dx_swap_handle(0, 0, h)
+    ctx.close()

@@ -303,3 +303,66 @@ def test_phi35_shaped_layer(B, LY, dxo, T):
     assert err <= REL_L2_TOL
     del lw
     ctx.close()
+
+
+def test_c4_layer_with_the_int4_int2_pair_under_a_budget(B, LY, dxo):
+    """The 80B-shaped layer with int4 as the high tier and int2 as the low one: a 24 GiB stack budget
+    leaves room for a three-digit number of int4 experts per layer next to the int2 rest; the shared
+    expert stays bf16.  Budget rule, selection and the layer output against the oracle."""
+    wl = WORKLOADS["C4"]
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, dxo.FMT_INT4), dxo.expert_bytes(wl.d, wl.f, wl.group, dxo.FMT_INT2)
+    b_sh = dxo.expert_bytes(wl.d, wl.shared_f, wl.group, 0)
+    assert b_hi == B.dx_expert_bytes(wl.d, wl.f, wl.group, B.DX_FMT_INT4G)
+    assert b_lo == B.dx_expert_bytes(wl.d, wl.f, wl.group, B.DX_FMT_INT2G)
+    stack_budget = 24 * 2 ** 30
+    layer_budget = (stack_budget - wl.L * b_sh) // wl.L
+    ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T, shared_f=wl.shared_f,
+                    route_updates_hotness=True, hi_fmt=B.DX_FMT_INT4G)
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    c = np.zeros(wl.E, np.int64)
+    for step in range(1, 17):
+        _, lg = W.layer_inputs(wl, 0, 0, step)
+        rb.route(ctx, 0, torch.from_numpy(lg).cuda())
+        dxo.hotness_update(c, dxo.route(lg, wl.k)[2])
+    S_gpu = ctx.dx_window_end()[0]
+    S = np.zeros(wl.E, np.uint64)
+    dxo.window_end(S, c, 0)
+    assert np.array_equal(S_gpu, S)
+    resident = ctx.dx_select_resident(0, layer_budget)              # uses the pair's b_hi / b_lo
+    n = dxo.budget_capacity(layer_budget, wl.E, b_hi, b_lo)
+    assert 100 < n < wl.E and np.array_equal(resident, dxo.select_topn(S, n))
+    assert wl.L * (n * b_hi + (wl.E - n) * b_lo + b_sh) <= stack_budget
+    assert wl.L * ((n + 1) * b_hi + (wl.E - n - 1) * b_lo + b_sh) > stack_budget
+    print(f"C4 int4/int2: n = {n} int4 experts per layer", flush=True)
+    wg, wu, wd = W.device_masters(wl, 0, 0)
+    lw = LY.QuantPairLayerWeights(ctx, 0, wg, wu, wd, resident, wl.group)
+    g = torch.Generator(device="cuda"); g.manual_seed(77)
+    shared = [(0.02 * torch.randn(s, generator=g, device="cuda")).to(torch.bfloat16)
+              for s in ((wl.shared_f, wl.d), (wl.shared_f, wl.d), (wl.d, wl.shared_f))]
+    ctx.dx_swap_handle(0, wl.E, B.make_handle(B.DX_FMT_BF16, *shared))
+    x, lg = W.layer_inputs(wl, 0, 0, 0)
+    y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+    rb.route(ctx, 0, torch.from_numpy(lg).cuda())
+    rb.forward(ctx, 0, LY.bits_to_device(x), y)
+    torch.cuda.synchronize()
+    ids, w, counts, offsets, perm = dxo.route(lg, wl.k)
+    assert np.array_equal(rb.ids.cpu().numpy(), ids)
+    res = set(int(e) for e in resident)
+    mh = [LY.device_to_bits(m) for m in (wg, wu, wd)]
+    versions, filler = [None] * wl.E, None
+    for e in np.flatnonzero(counts > 0):
+        e = int(e)
+        make = dxo.ExpertVersion.int4_from_master if e in res else dxo.ExpertVersion.int2_from_master
+        versions[e] = make(*(m[e] for m in mh), wl.group)
+        filler = versions[e]
+    versions = [v if v is not None else filler for v in versions]
+    sh = dxo.ExpertVersion.bf16(*(LY.device_to_bits(t) for t in shared))
+    y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w, shared=sh, shared_f=wl.shared_f)
+    err = rel_l2(LY.device_to_bits(y), y_ref)
+    on_hi = int(sum(counts[e] for e in res))
+    print(f"  C4 int4/int2: {on_hi}/{wl.T * wl.k} pairs on int4 experts, rel-L2 {err:.2e}", flush=True)
+    assert err <= REL_L2_TOL
+    with pytest.raises(B.DxError):                                   # pools are built for the bf16 / int4 pair only
+        ctx.dx_pools_create(4, 4)
+    del lw
+    ctx.close()
