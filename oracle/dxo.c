@@ -263,11 +263,17 @@ static float weight_at(const void *wptr, const void *sptr, int fmt, int K, int g
 {
     if (fmt == DXO_FMT_BF16)
         return bf16_widen(((const uint16_t *)wptr)[(size_t)row * K + col]);
-    uint16_t sb = ((const uint16_t *)sptr)[(size_t)row * (K / group) + col / group];
-    if (fmt == DXO_FMT_INT2)
-        return (float)crumb_at((const uint8_t *)wptr + (size_t)row * (K / 4), col) * bf16_widen(sb);
     const uint8_t *qrow = (const uint8_t *)wptr + (size_t)row * (K / 2);
+    uint16_t sb = ((const uint16_t *)sptr)[(size_t)row * (K / group) + col / group];
     return (float)nibble_at(qrow, col) * bf16_widen(sb);
+}
+
+/* the same for a matrix stored as 2-bit codes */
+static float weight_at_int2(const void *wptr, const void *sptr, int K, int group, int row, int col)
+{
+    const uint8_t *crow = (const uint8_t *)wptr + (size_t)row * (K / 4);
+    uint16_t sb = ((const uint16_t *)sptr)[(size_t)row * (K / group) + col / group];
+    return (float)crumb_at(crow, col) * bf16_widen(sb);
 }
 
 /* packed int2 + scales -> fp32 matrix [rows, K] */
@@ -276,7 +282,7 @@ int dxo_dequantize2(const uint8_t *q, const uint16_t *s, int rows, int K, int gr
     if (rows < 0 || K <= 0 || group <= 0 || (K % group) || (K & 3)) return 1;
     for (int r = 0; r < rows; ++r)
         for (int c = 0; c < K; ++c)
-            out[(size_t)r * K + c] = weight_at(q, s, DXO_FMT_INT2, K, group, r, c);
+            out[(size_t)r * K + c] = weight_at_int2(q, s, K, group, r, c);
     return 0;
 }
 
@@ -293,9 +299,34 @@ int dxo_dequantize(const uint8_t *q, const uint16_t *s, int rows, int K, int gro
 /* ------------------------------------------------------------ one expert */
 /* o = W_down ( silu(W_gate x) * (W_up x) ) on the stored (dequantised)
  * weights, all sums in fp64.  hbuf has room for f doubles. */
+/* the same expert on int2-stored matrices */
+static void expert_apply_int2(const dxo_expert *ex, int d, int f, int group,
+                              const float *x, double *hbuf, double *o)
+{
+    for (int n = 0; n < f; ++n) {
+        double g = 0.0, u = 0.0;
+        for (int c = 0; c < d; ++c) {
+            g += (double)weight_at_int2(ex->w_gate, ex->s_gate, d, group, n, c) * (double)x[c];
+            u += (double)weight_at_int2(ex->w_up, ex->s_up, d, group, n, c) * (double)x[c];
+        }
+        double silu = g / (1.0 + exp(-g));
+        hbuf[n] = silu * u;
+    }
+    for (int n = 0; n < d; ++n) {
+        double acc = 0.0;
+        for (int c = 0; c < f; ++c)
+            acc += (double)weight_at_int2(ex->w_down, ex->s_down, f, group, n, c) * hbuf[c];
+        o[n] = acc;
+    }
+}
+
 static void expert_apply(const dxo_expert *ex, int d, int f, int group,
                          const float *x, double *hbuf, double *o)
 {
+    if (ex->fmt == DXO_FMT_INT2) {
+        expert_apply_int2(ex, d, f, group, x, hbuf, o);
+        return;
+    }
     for (int n = 0; n < f; ++n) {
         double g = 0.0, u = 0.0;
         for (int c = 0; c < d; ++c) {
