@@ -109,7 +109,9 @@ typedef struct {
 /* Creates a context on the current HIP device.  `hip_compute_stream` is a
  * hipStream_t (NULL = the null stream).  Allocates the handle tables
  * (L*E routed + L shared entries), the window counters, the routing and
- * forward scratch for max_tokens, and a migration stream. */
+ * forward scratch for max_tokens, a migration stream and two side streams
+ * (all at default priority).  A context is not thread-safe: one host thread
+ * at a time. */
 dx_status dx_create(const dx_config *cfg, void *hip_compute_stream, dx_ctx **out);
 void dx_destroy(dx_ctx *ctx);
 const char *dx_last_error(const dx_ctx *ctx);
@@ -147,7 +149,13 @@ dx_status dx_router_logits(dx_ctx *ctx, const void *x_bf16, const void *w_router
  * handle_table: dev, E entries of this layer; NULL = the context's own table
  * for `layer`.  x_bf16 dev [T,d]; y_bf16 dev [T,d]; routing arrays as written
  * by dx_route for the same T.  Weights are read through the handles as they
- * are when the kernels run on the compute stream. */
+ * are when the kernels run on the compute stream.
+ * Stream order: the call is asynchronous and ordered on the compute stream.
+ * Above 128 tokens it forks part of its kernels onto two side streams of the
+ * context and joins them before the combine, so the work is still complete
+ * in compute-stream order (and can be captured in a HIP graph with the
+ * compute stream as origin).  The H and O scratch buffers belong to the
+ * context: calls on one context must not overlap. */
 dx_status dx_moe_forward(dx_ctx *ctx, int layer, const dx_handle *handle_table,
                          const void *x_bf16, int T,
                          const int32_t *topk_ids, const float *topk_w,

@@ -2,8 +2,8 @@
 // (decode): SwiGLU gate/up grouped GEMM, down grouped GEMM, weighted combine.
 //
 // Paper: Sec. 3.2 -- the compute path resolves each expert's stable handle to
-// the active version (bf16, or int4 with its quantization parameters) and runs
-// the matching kernel.  The paper gives no kernel; this one is built for
+// the active version (bf16, or int4 / int2 with its quantization parameters)
+// and runs the matching kernel.  The paper gives no kernel; this one is built for
 // gfx950.
 //
 // Regime: every activated expert's weights are streamed from HBM exactly once
@@ -12,29 +12,31 @@
 // every compute unit streams for the whole duration of the kernel, so:
 //   - Persistent grid, one block of 8 wavefronts per compute unit.  The work
 //     is the list of (activated expert, 32-token block, pair of 16-row weight
-//     strips); a bf16 strip pair weighs 4 units, an int4 one 1 unit, and block
-//     b takes the strips that start in units [b*U/G, (b+1)*U/G).  Every block
-//     derives the same partition from `offsets` and the handles' formats in
-//     its prologue (a block-wide scan): no atomics, no work queue.
-//   - The 8 wavefronts of a block split the K extent of a strip pair between
-//     them (wavefront kw owns CPW consecutive K-chunks of 4*LK elements), so a
-//     whole strip pair is in flight at once and the next one is prefetched
-//     into a second register stage while this one is multiplied.  When K is
-//     short (down projection), the block works on several strip pairs side by
-//     side.  Partial sums meet in LDS, are added in a fixed order and finished
-//     (SwiGLU, or the store of the down output) by all threads of the block.
+//     strips), weighed in cost units (kHiUnits, kLoUnits, kRunUnits below);
+//     block b takes the pairs that start in units [b*U/G, (b+1)*U/G).  Every
+//     block derives the same partition from `offsets` and the handles'
+//     formats in its prologue (a block-wide scan): no atomics, no work queue.
+//   - The 8 wavefronts of a block split the K extent of a strip between them
+//     (wavefront kw owns CPW consecutive K-chunks of 4*LK elements), so a
+//     whole strip is in flight at once and the following ones are prefetched
+//     into further register stages while this one is multiplied.  When K is
+//     short, the block works on several strip pairs side by side.  Partial
+//     sums meet in LDS, are added in a fixed order and finished (SwiGLU, or
+//     the store of the down output) by all threads of the block.
 //   - The token rows (A operand of v_mfma_f32_16x16x32_bf16) only depend on
 //     the expert and the K-chunk, so each wavefront keeps its fragments in
 //     registers for all strips of a run: after the first strip, weights are
 //     the only global traffic.
 //   - Lane (r = lane%16, q = lane/16) owns weight row r.  bf16: step j of a
 //     chunk takes elements 32j + 8q .. +7 (four lanes of a row read 64
-//     contiguous bytes per instruction).  int4: the lane takes the LK
-//     consecutive elements at q*LK (one 16-byte load of nibbles for LK = 32).
+//     contiguous bytes per instruction).  int4 / int2: the lane takes the LK
+//     consecutive elements at q*LK (one 16-byte / 8-byte load for LK = 32).
 //     Token fragments use the same K ownership, which makes either order valid.
-//   - int4 weights are expanded to exact small bf16 integers; a K-chunk never
-//     crosses a quantization group, so the group's scale multiplies the chunk's
-//     fp32 partial sums once (q*s is never rounded).
+//   - Quantized weights are expanded to exact small bf16 integers; a K-chunk
+//     never crosses a quantization group, so the group's scale multiplies the
+//     chunk's fp32 partial sums once (q*s is never rounded).
+// Batches of up to 128 tokens run here alone (segments above 32 tokens in
+// blocks of 32); larger ones hand the big segments to the tile kernels.
 #include "dx_internal.h"
 
 namespace {
