@@ -433,10 +433,13 @@ def test_forward_prefill_with_shared_expert(B, LY, dxo, T):
     ly.ctx.close()
 
 
-def test_forward_c3_prefill_sampled_tokens(B, LY, dxo):
-    """The 30B-shaped prefill layer at full size (T=4096): routing bit-exact on all tokens, layer output
-    checked on sampled tokens the oracle computes one by one."""
-    wl = WORKLOADS["C3"]
+@pytest.mark.parametrize("T", [4096, 8192])
+def test_forward_c3_prefill_sampled_tokens(B, LY, dxo, T):
+    """The 30B-shaped prefill layer at full size (T=4096) and at twice that (the largest batch the
+    benchmarks use): routing bit-exact on all tokens, layer output checked on sampled tokens the oracle
+    computes one by one."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C3"], T=T)
     print("forward C3: drawing masters", flush=True)
     masters = W.layer_masters(wl, 0, 0)
     x, logits = W.layer_inputs(wl, seed=0)
