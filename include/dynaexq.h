@@ -274,23 +274,38 @@ dx_status dx_pools_create(dx_ctx *ctx, int hi_blocks, int lo_blocks);
 /* Synchronous set-up: materialise (layer, expert) in `fmt` from bf16 master
  * matrices gate [f,d], up [f,d], down [d,f] (`src_on_device` != 0: dev
  * pointers, else host) into a pool block and publish it.  For int4 the
- * masters are quantized on device.  expert == E installs the shared expert
- * (bf16 only, intermediate size shared_f). */
+ * masters are quantized on device.  fmt is one of the two tiers of the
+ * context's precision pair.  expert == E installs the shared expert (bf16
+ * only, intermediate size shared_f). */
 dx_status dx_expert_install(dx_ctx *ctx, int layer, int expert, int fmt,
                             const void *gate, const void *up, const void *down, int src_on_device);
+
+/* Quantized precision pair (hi_fmt = DX_FMT_INT4G): where the pre-packed
+ * version of (layer, expert) in `fmt` (the pair's high or low tier) lives in
+ * pinned host memory: packed codes of gate, up, down and their bf16 scales, in
+ * the layouts of dx_handle.  Promotions and demotions of such a context copy
+ * these versions (no repacking on the way, Sec. 3.4); the pointers must stay
+ * valid while the context lives. */
+dx_status dx_register_host_packed(dx_ctx *ctx, int layer, int expert, int fmt,
+                                  const void *q_gate, const void *q_up, const void *q_down,
+                                  const void *s_gate, const void *s_up, const void *s_down);
 
 /* Promotion (Sec. 3.4, "Update/Evict procedure"): reserve b_hi from the
  * budget tracker, take a block of pool_hi, copy the bf16 masters from pinned
  * host memory on the migration stream, record a completion event.  The
  * handle keeps resolving to the int4 version until dx_migrate_poll publishes.
  * DX_ERR_BUDGET: reservation refused (nothing started); DX_ERR_BUSY: the
- * expert is not Resident-Lo; DX_ERR_NOMEM: pool_hi has no free block. */
+ * expert is not Resident-Lo; DX_ERR_NOMEM: pool_hi has no free block.
+ * With a quantized precision pair the three pointers are ignored (may be
+ * NULL) and the registered packed high-tier version is copied instead. */
 dx_status dx_promote_async(dx_ctx *ctx, int layer, int expert,
                            const void *pinned_gate, const void *pinned_up, const void *pinned_down);
 
 /* Demotion: take a block of pool_lo and run the quantizer on the migration
  * stream over the resident bf16 version; the handle keeps resolving to bf16
- * until published.  DX_ERR_BUSY: the expert is not Resident-Hi. */
+ * until published.  DX_ERR_BUSY: the expert is not Resident-Hi.  With a
+ * quantized precision pair no bf16 version is resident: the registered
+ * packed low-tier version is copied from pinned host memory instead. */
 dx_status dx_demote_async(dx_ctx *ctx, int layer, int expert);
 
 /* Publish every transition whose completion event has fired, in issue order

@@ -24,7 +24,7 @@ EXPORTS = [
     "dx_route", "dx_router_logits", "dx_moe_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
     "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
-    "dx_register_host_master", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
+    "dx_register_host_master", "dx_register_host_packed", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
     "dx_quantize_expert", "dx_quantize_expert_int2", "dx_swap_handle",
     "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats",
     "dx_set_profiling", "dx_get_profile",
@@ -120,6 +120,7 @@ def load():
     L.dx_get_profile.argtypes = [vp, C.POINTER(DxProfile)]
     L.dx_pools_create.argtypes = [vp, i32, i32]
     L.dx_register_host_master.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.dx_register_host_packed.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     L.dx_transitions_limits.argtypes = [vp, i32]
     L.dx_transitions_enqueue.argtypes = [vp, i32, vp, i32, vp, i32]
     L.dx_transitions_pump.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -321,7 +322,7 @@ class Context:
         self._chk(self.lib.dx_expert_install(self.h, layer, expert, fmt, _ptr(gate), _ptr(up), _ptr(down),
                                              1 if src_on_device else 0), "dx_expert_install")
 
-    def dx_promote_async(self, layer, expert, pinned_gate, pinned_up, pinned_down):
+    def dx_promote_async(self, layer, expert, pinned_gate=None, pinned_up=None, pinned_down=None):
         self._chk(self.lib.dx_promote_async(self.h, layer, expert, _ptr(pinned_gate), _ptr(pinned_up),
                                             _ptr(pinned_down)), "dx_promote_async")
 
@@ -331,6 +332,10 @@ class Context:
     def dx_register_host_master(self, layer, expert, pinned_gate, pinned_up, pinned_down):
         self._chk(self.lib.dx_register_host_master(self.h, layer, expert, _ptr(pinned_gate), _ptr(pinned_up),
                                                    _ptr(pinned_down)), "dx_register_host_master")
+
+    def dx_register_host_packed(self, layer, expert, fmt, q_gate, q_up, q_down, s_gate, s_up, s_down):
+        self._chk(self.lib.dx_register_host_packed(self.h, layer, expert, fmt, _ptr(q_gate), _ptr(q_up), _ptr(q_down),
+                                                   _ptr(s_gate), _ptr(s_up), _ptr(s_down)), "dx_register_host_packed")
 
     def dx_transitions_limits(self, max_inflight):
         self._chk(self.lib.dx_transitions_limits(self.h, max_inflight), "dx_transitions_limits")

@@ -53,7 +53,7 @@ dx_handle handle_in_block(const dx_ctx *c, void *block, int fmt, int f)
         h.w_up = p + ff * d * 2;
         h.w_down = p + 2 * ff * d * 2;
     } else {
-        const size_t qm = ff * d / 2, sm = ff * d / g * 2;
+        const size_t qm = ff * d / (fmt == DX_FMT_INT2G ? 4 : 2), sm = ff * d / g * 2;
         h.w_gate = p;
         h.w_up = p + qm;
         h.w_down = p + 2 * qm;
@@ -680,15 +680,49 @@ extern "C" dx_status dx_get_profile(dx_ctx *c, dx_profile *out)
     return DX_OK;
 }
 
+namespace {
+
+// the six pieces of a pre-packed quantized version, pinned host memory -> a pool block, migration stream
+hipError_t copy_packed(dx_ctx *c, const dx_handle &dst, const dx_packed_host &src, int fmt)
+{
+    const dx_config &g = c->cfg;
+    const size_t div = fmt == DX_FMT_INT2G ? 4 : 2;
+    const size_t qm = (size_t)g.f * g.d / div, sm = (size_t)g.f * g.d / g.group * 2;
+    void *d[6] = {const_cast<void *>(dst.w_gate), const_cast<void *>(dst.w_up), const_cast<void *>(dst.w_down),
+                  const_cast<void *>(dst.s_gate), const_cast<void *>(dst.s_up), const_cast<void *>(dst.s_down)};
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < 6 && e == hipSuccess; ++i)
+        e = hipMemcpyAsync(d[i], src.p[i], i < 3 ? qm : sm, hipMemcpyHostToDevice, c->mig);
+    return e;
+}
+
+} // namespace
+
+extern "C" dx_status dx_register_host_packed(dx_ctx *c, int layer, int expert, int fmt, const void *q_gate, const void *q_up,
+                                             const void *q_down, const void *s_gate, const void *s_up, const void *s_down)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (c->cfg.hi_fmt == DX_FMT_BF16)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_register_host_packed: only for a context with a quantized precision pair");
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, false) || (fmt != c->cfg.hi_fmt && fmt != c->cfg.hi_fmt + 1) ||
+        !q_gate || !q_up || !q_down || !s_gate || !s_up || !s_down)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_register_host_packed: bad argument");
+    auto &reg = c->host_packed[fmt == c->cfg.hi_fmt ? 0 : 1];
+    if (reg.empty()) reg.assign((size_t)c->cfg.L * c->cfg.E, dx_packed_host{});
+    reg[(size_t)layer * c->cfg.E + expert] = dx_packed_host{{q_gate, q_up, q_down, s_gate, s_up, s_down}};
+    return DX_OK;
+}
+
 // ------------------------------------------------------ pools and transitions
 extern "C" dx_status dx_pools_create(dx_ctx *c, int hi_blocks, int lo_blocks)
 {
     if (!c) return DX_ERR_INVALID;
-    if (c->cfg.hi_fmt != DX_FMT_BF16)
-        DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: pools and transitions are built for the bf16 / int4 pair only");
     if (hi_blocks < 0 || lo_blocks < 0) DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: negative block count");
     if (c->pool_hi.base || c->pool_lo.base || c->staging) DX_FAIL(c, DX_ERR_INVALID, "dx_pools_create: pools already exist");
     const size_t hi_b = round256(std::max(c->b_hi, c->b_shared)), lo_b = round256(c->b_lo);
+    // staging holds the bf16 master of one expert (routed or shared) on its way to a quantizer
+    const size_t staging_b = round256(std::max<uint64_t>(
+        dx_expert_bytes(c->cfg.d, std::max(c->cfg.f, c->cfg.shared_f), c->cfg.group, DX_FMT_BF16), hi_b));
     auto make = [&](dx_block_pool &p, size_t bytes, int n) -> hipError_t {
         p.block_bytes = bytes;
         p.n_blocks = n;
@@ -701,7 +735,7 @@ extern "C" dx_status dx_pools_create(dx_ctx *c, int hi_blocks, int lo_blocks)
     hipError_t e;
     if ((e = make(c->pool_hi, hi_b, hi_blocks)) != hipSuccess ||
         (e = make(c->pool_lo, lo_b, lo_blocks)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void **>(&c->staging), hi_b)) != hipSuccess) {
+        (e = hipMalloc(reinterpret_cast<void **>(&c->staging), staging_b)) != hipSuccess) {
         for (dx_block_pool *p : {&c->pool_hi, &c->pool_lo}) {
             if (p->base) (void)hipFree(p->base);
             *p = dx_block_pool{};
@@ -718,28 +752,31 @@ extern "C" dx_status dx_expert_install(dx_ctx *c, int layer, int expert, int fmt
 {
     if (!c) return DX_ERR_INVALID;
     if (!valid_layer(c, layer) || !valid_expert(c, expert, true) || !gate || !up || !down ||
-        (fmt != DX_FMT_BF16 && fmt != DX_FMT_INT4G))
+        (fmt != DX_FMT_BF16 && fmt != DX_FMT_INT4G && fmt != DX_FMT_INT2G))
         DX_FAIL(c, DX_ERR_INVALID, "dx_expert_install: bad argument");
     const bool shared = expert == c->cfg.E;
     if (shared && fmt != DX_FMT_BF16) DX_FAIL(c, DX_ERR_INVALID, "dx_expert_install: the shared expert is bf16 only");
+    if (!shared && fmt != c->cfg.hi_fmt && fmt != c->cfg.hi_fmt + 1)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_expert_install: format %d is not a tier of this context's precision pair", fmt);
+    const bool is_hi = shared || fmt == c->cfg.hi_fmt;
     if (!c->staging) DX_FAIL(c, DX_ERR_INVALID, "dx_expert_install: call dx_pools_create first");
     const int idx = entry_index(c, layer, expert);
     dx_entry &en = c->entries[idx];
     if (en.state != DX_STATE_EMPTY) DX_FAIL(c, DX_ERR_BUSY, "dx_expert_install: expert (%d,%d) already installed", layer, expert);
     const dx_config &g = c->cfg;
     const int f = shared ? g.shared_f : g.f;
-    const uint64_t bytes = shared ? c->b_shared : (fmt == DX_FMT_BF16 ? c->b_hi : c->b_lo);
+    const uint64_t bytes = shared ? c->b_shared : (is_hi ? c->b_hi : c->b_lo);
     const uint64_t cap = g.budget_bytes ? g.budget_bytes + g.transient_bytes : ~0ull;
     if (c->reserved + bytes > cap) {
         c->stats.deferred++;
         DX_FAIL(c, DX_ERR_BUDGET, "dx_expert_install: %llu B reserved + %llu B exceeds the budget", (unsigned long long)c->reserved,
                 (unsigned long long)bytes);
     }
-    if (!shared && fmt == DX_FMT_BF16 && g.budget_bytes && c->hi_count[layer] >= c->n_hi_cap) {
+    if (!shared && is_hi && g.budget_bytes && c->hi_count[layer] >= c->n_hi_cap) {
         c->stats.deferred++;
         DX_FAIL(c, DX_ERR_BUDGET, "dx_expert_install: layer %d already holds its %d high-precision experts", layer, c->n_hi_cap);
     }
-    dx_block_pool &pool = fmt == DX_FMT_BF16 ? c->pool_hi : c->pool_lo;
+    dx_block_pool &pool = is_hi ? c->pool_hi : c->pool_lo;
     int block;
     dx_status s = pool_take(c, pool, c->compute, &block);
     if (s != DX_OK) return s;
@@ -763,8 +800,9 @@ extern "C" dx_status dx_expert_install(dx_ctx *c, int layer, int expert, int fmt
                 e = hipMemcpyAsync(c->staging + (size_t)i * mat, src[i], mat, hipMemcpyHostToDevice, c->compute);
             }
             if (e == hipSuccess)
-                e = dxk_quantize(static_cast<const dx_bf16 *>(dev_src), rows[i], Ks[i], g.group,
-                                 static_cast<uint8_t *>(qd[i]), static_cast<dx_bf16 *>(sd[i]), c->compute);
+                e = (fmt == DX_FMT_INT2G ? dxk_quantize2 : dxk_quantize)(static_cast<const dx_bf16 *>(dev_src), rows[i], Ks[i],
+                                                                       g.group, static_cast<uint8_t *>(qd[i]),
+                                                                       static_cast<dx_bf16 *>(sd[i]), c->compute);
         }
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
@@ -778,18 +816,25 @@ extern "C" dx_status dx_expert_install(dx_ctx *c, int layer, int expert, int fmt
         return s;
     }
     track_reserve(c, bytes);
-    en.pool = fmt == DX_FMT_BF16 ? 0 : 1;
+    en.pool = is_hi ? 0 : 1;
     en.block = block;
-    en.state = fmt == DX_FMT_BF16 ? DX_STATE_RESIDENT_HI : DX_STATE_RESIDENT_LO;
-    if (!shared && fmt == DX_FMT_BF16) c->hi_count[layer]++;
+    en.state = is_hi ? DX_STATE_RESIDENT_HI : DX_STATE_RESIDENT_LO;
+    if (!shared && is_hi) c->hi_count[layer]++;
     return DX_OK;
 }
 
 extern "C" dx_status dx_promote_async(dx_ctx *c, int layer, int expert, const void *pg, const void *pu, const void *pd)
 {
     if (!c) return DX_ERR_INVALID;
-    if (!valid_layer(c, layer) || !valid_expert(c, expert, false) || !pg || !pu || !pd)
+    const bool quant_pair = c->cfg.hi_fmt != DX_FMT_BF16;
+    if (!valid_layer(c, layer) || !valid_expert(c, expert, false) || (!quant_pair && (!pg || !pu || !pd)))
         DX_FAIL(c, DX_ERR_INVALID, "dx_promote_async: bad argument");
+    const dx_packed_host *packed = nullptr;
+    if (quant_pair) { // the pre-packed high-tier version registered for this expert
+        if (c->host_packed[0].empty() || !c->host_packed[0][(size_t)layer * c->cfg.E + expert].p[0])
+            DX_FAIL(c, DX_ERR_INVALID, "dx_promote_async: no packed high-tier version registered for (%d,%d)", layer, expert);
+        packed = &c->host_packed[0][(size_t)layer * c->cfg.E + expert];
+    }
     const int idx = entry_index(c, layer, expert);
     dx_entry &en = c->entries[idx];
     if (en.state != DX_STATE_RESIDENT_LO || en.pool != 1)
@@ -813,10 +858,15 @@ extern "C" dx_status dx_promote_async(dx_ctx *c, int layer, int expert, const vo
         return s;
     }
     const size_t mat = (size_t)g.f * g.d * 2;
-    dx_handle h = handle_in_block(c, c->pool_hi.block_ptr(block), DX_FMT_BF16, g.f);
-    hipError_t e = hipMemcpyAsync(const_cast<void *>(h.w_gate), pg, mat, hipMemcpyHostToDevice, c->mig);
-    if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_up), pu, mat, hipMemcpyHostToDevice, c->mig);
-    if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_down), pd, mat, hipMemcpyHostToDevice, c->mig);
+    dx_handle h = handle_in_block(c, c->pool_hi.block_ptr(block), g.hi_fmt, g.f);
+    hipError_t e;
+    if (quant_pair) {
+        e = copy_packed(c, h, *packed, g.hi_fmt);
+    } else {
+        e = hipMemcpyAsync(const_cast<void *>(h.w_gate), pg, mat, hipMemcpyHostToDevice, c->mig);
+        if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_up), pu, mat, hipMemcpyHostToDevice, c->mig);
+        if (e == hipSuccess) e = hipMemcpyAsync(const_cast<void *>(h.w_down), pd, mat, hipMemcpyHostToDevice, c->mig);
+    }
     if (e == hipSuccess) e = hipEventRecord(done, c->mig);
     if (e != hipSuccess) {
         (void)hipStreamSynchronize(c->mig);
@@ -831,7 +881,7 @@ extern "C" dx_status dx_promote_async(dx_ctx *c, int layer, int expert, const vo
     c->inflight.push_back({layer, expert, true, done});
     c->stats.peak_in_flight = std::max<uint64_t>(c->stats.peak_in_flight, c->inflight.size());
     c->stats.promotions_issued++;
-    c->stats.h2d_bytes += 3 * mat;
+    c->stats.h2d_bytes += quant_pair ? c->b_hi : 3 * mat;
     return DX_OK;
 }
 
@@ -842,8 +892,15 @@ extern "C" dx_status dx_demote_async(dx_ctx *c, int layer, int expert)
     const int idx = entry_index(c, layer, expert);
     dx_entry &en = c->entries[idx];
     if (en.state != DX_STATE_RESIDENT_HI || en.pool != 0)
-        DX_FAIL(c, DX_ERR_BUSY, "dx_demote_async: expert (%d,%d) is not a pool-resident bf16 expert", layer, expert);
+        DX_FAIL(c, DX_ERR_BUSY, "dx_demote_async: expert (%d,%d) is not a pool-resident high-tier expert", layer, expert);
     const dx_config &g = c->cfg;
+    const bool quant_pair = g.hi_fmt != DX_FMT_BF16;
+    const dx_packed_host *packed_lo = nullptr;
+    if (quant_pair) { // no bf16 version is resident to quantize from: the pre-packed low-tier version is copied in
+        if (c->host_packed[1].empty() || !c->host_packed[1][(size_t)layer * g.E + expert].p[0])
+            DX_FAIL(c, DX_ERR_INVALID, "dx_demote_async: no packed low-tier version registered for (%d,%d)", layer, expert);
+        packed_lo = &c->host_packed[1][(size_t)layer * g.E + expert];
+    }
     const uint64_t cap = g.budget_bytes ? g.budget_bytes + g.transient_bytes : ~0ull;
     if (c->reserved + c->b_lo > cap) {
         c->stats.deferred++;
@@ -859,16 +916,18 @@ extern "C" dx_status dx_demote_async(dx_ctx *c, int layer, int expert)
         if (s == DX_ERR_NOMEM) c->stats.deferred++;
         return s;
     }
-    dx_handle lo = handle_in_block(c, c->pool_lo.block_ptr(block), DX_FMT_INT4G, g.f);
+    dx_handle lo = handle_in_block(c, c->pool_lo.block_ptr(block), g.hi_fmt + 1, g.f);
     const dx_handle &hi = en.h;
-    hipError_t e = dxk_quantize(static_cast<const dx_bf16 *>(hi.w_gate), g.f, g.d, g.group,
-                                static_cast<uint8_t *>(const_cast<void *>(lo.w_gate)),
-                                static_cast<dx_bf16 *>(const_cast<void *>(lo.s_gate)), c->mig);
-    if (e == hipSuccess)
+    hipError_t e = hipSuccess;
+    if (quant_pair) e = copy_packed(c, lo, *packed_lo, g.hi_fmt + 1);
+    else e = dxk_quantize(static_cast<const dx_bf16 *>(hi.w_gate), g.f, g.d, g.group,
+                          static_cast<uint8_t *>(const_cast<void *>(lo.w_gate)),
+                          static_cast<dx_bf16 *>(const_cast<void *>(lo.s_gate)), c->mig);
+    if (e == hipSuccess && !quant_pair)
         e = dxk_quantize(static_cast<const dx_bf16 *>(hi.w_up), g.f, g.d, g.group,
                          static_cast<uint8_t *>(const_cast<void *>(lo.w_up)),
                          static_cast<dx_bf16 *>(const_cast<void *>(lo.s_up)), c->mig);
-    if (e == hipSuccess)
+    if (e == hipSuccess && !quant_pair)
         e = dxk_quantize(static_cast<const dx_bf16 *>(hi.w_down), g.d, g.f, g.group,
                          static_cast<uint8_t *>(const_cast<void *>(lo.w_down)),
                          static_cast<dx_bf16 *>(const_cast<void *>(lo.s_down)), c->mig);
@@ -885,8 +944,12 @@ extern "C" dx_status dx_demote_async(dx_ctx *c, int layer, int expert)
     c->inflight.push_back({layer, expert, false, done});
     c->stats.peak_in_flight = std::max<uint64_t>(c->stats.peak_in_flight, c->inflight.size());
     c->stats.demotions_issued++;
-    c->stats.quantize_read_bytes += c->b_hi;
-    c->stats.quantize_write_bytes += c->b_lo;
+    if (quant_pair) {
+        c->stats.h2d_bytes += c->b_lo;
+    } else {
+        c->stats.quantize_read_bytes += c->b_hi;
+        c->stats.quantize_write_bytes += c->b_lo;
+    }
     return DX_OK;
 }
 
@@ -905,7 +968,8 @@ extern "C" dx_status dx_migrate_poll(dx_ctx *c, int wait, int *n_published)
         dx_block_pool &new_pool = t.promote ? c->pool_hi : c->pool_lo;
         dx_block_pool &old_pool = t.promote ? c->pool_lo : c->pool_hi;
         const int old_block = en.block;
-        dx_handle h = handle_in_block(c, new_pool.block_ptr(en.next_block), t.promote ? DX_FMT_BF16 : DX_FMT_INT4G, c->cfg.f);
+        dx_handle h = handle_in_block(c, new_pool.block_ptr(en.next_block), t.promote ? c->cfg.hi_fmt : c->cfg.hi_fmt + 1,
+                                      c->cfg.f);
         // an event on the compute stream right after the swap: once it has fired, no
         // forward pass can still read the old version, so its block may be rewritten
         hipEvent_t after;
@@ -1031,7 +1095,9 @@ extern "C" dx_status dx_transitions_pump(dx_ctx *c, int max_issue, int32_t *n_is
             ++it;
             continue;
         }
-        if (r.promote) {
+        if (r.promote && g.hi_fmt != DX_FMT_BF16) {
+            s = dx_promote_async(c, r.layer, r.expert, nullptr, nullptr, nullptr); // copies the registered packed version
+        } else if (r.promote) {
             if (c->host_master.empty() || !c->host_master[(size_t)r.layer * g.E + r.expert][0])
                 DX_FAIL(c, DX_ERR_INVALID, "dx_transitions_pump: no host master registered for (%d,%d)", r.layer, r.expert);
             const auto &m = c->host_master[(size_t)r.layer * g.E + r.expert];

@@ -31,6 +31,10 @@ struct dx_entry {
     dx_handle h{};           // host mirror of the published handle
 };
 
+struct dx_packed_host {
+    const void *p[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr}; // q_gate q_up q_down s_gate s_up s_down
+};
+
 struct dx_request {
     int layer, expert;
     bool promote;
@@ -83,6 +87,8 @@ struct dx_ctx {
     std::deque<dx_request> update_q;                       // waiting promotions and demotions, in arrival order
     std::vector<std::array<const void *, 3>> host_master; // per routed entry: pinned bf16 gate/up/down or nulls
     int max_inflight = 0;                                  // 0: unbounded
+    // quantized precision pair: pre-packed versions in pinned host memory, [0] high tier, [1] low tier
+    std::vector<dx_packed_host> host_packed[2];
     std::vector<hipEvent_t> event_pool;
     dx_stats stats{};
 

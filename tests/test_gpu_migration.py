@@ -315,3 +315,89 @@ def test_transition_queue_backpressure_and_eviction_priority(B, LY, dxo):
         ctx.dx_transitions_limits(-1)
     st.check(1, 0)
     ctx.close()
+
+
+def test_int4_int2_pair_through_the_pools_and_the_queue(B, LY, dxo):
+    """The quantized precision pair (int4 high tier, int2 low tier) through the same machinery: install
+    quantizes the bf16 masters into pool blocks, promotions and demotions copy the pre-packed versions
+    registered in pinned host memory, publication and the budget tracker work as for bf16/int4."""
+    wl = WORKLOADS["C1"]                                              # group 64
+    L, n_hi = 1, 2
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, dxo.FMT_INT4), dxo.expert_bytes(wl.d, wl.f, wl.group, dxo.FMT_INT2)
+    budget = n_hi * b_hi + (wl.E - n_hi) * b_lo
+    ctx = B.Context(L=L, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T,
+                    budget_bytes=budget, transient_bytes=b_hi + b_lo, hi_fmt=B.DX_FMT_INT4G)
+    ctx.dx_pools_create(n_hi + 1, wl.E - n_hi + 1)
+    masters = W.layer_masters(wl, 5, 0)
+    wg, wu, wd = masters
+    v4 = [dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(wl.E)]
+    v2 = [dxo.ExpertVersion.int2_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(wl.E)]
+    hi0 = {1, 6}
+    for e in range(wl.E):
+        fmt = B.DX_FMT_INT4G if e in hi0 else B.DX_FMT_INT2G
+        if e % 2:
+            ctx.dx_expert_install(0, e, fmt, *(LY.bits_to_device(m[e]) for m in masters), src_on_device=True)
+        else:
+            ctx.dx_expert_install(0, e, fmt, *(torch.from_numpy(m[e].view(np.int16)).pin_memory() for m in masters),
+                                  src_on_device=False)
+    with pytest.raises(B.DxError):
+        ctx.dx_expert_install(0, 0, B.DX_FMT_BF16, *(LY.bits_to_device(m[0]) for m in masters), src_on_device=True)
+    assert ctx.dx_get_stats()["reserved_bytes"] == budget
+
+    def device_version_equals(e, ref):
+        h = ctx.dx_get_handle(0, e)
+        a = ref.arrays
+        for ptr, arr in ((h.w_gate, a[0]), (h.w_up, a[1]), (h.w_down, a[2]), (h.s_gate, a[3]), (h.s_up, a[4]), (h.s_down, a[5])):
+            assert np.array_equal(read_device(ptr, arr.nbytes), arr.ravel().view(np.uint8))
+
+    device_version_equals(1, v4[1])                                   # installed = the oracle's quantization
+    device_version_equals(0, v2[0])
+    device_version_equals(3, v2[3])
+
+    # pre-packed versions of both tiers in pinned host memory (what transitions copy)
+    keep = []
+    for e in range(wl.E):
+        for fmt, ver in ((B.DX_FMT_INT4G, v4[e]), (B.DX_FMT_INT2G, v2[e])):
+            pinned = [torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).pin_memory() for a in ver.arrays]
+            keep.append(pinned)
+            ctx.dx_register_host_packed(0, e, fmt, *pinned)
+
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+
+    def check(step):
+        fm = ctx.dx_get_formats()[0]
+        x, lg = W.layer_inputs(wl, 5, 0, step)
+        rb.route(ctx, 0, torch.from_numpy(lg).cuda())
+        rb.forward(ctx, 0, LY.bits_to_device(x), y)
+        torch.cuda.synchronize()
+        ids, w, *_ = dxo.route(lg, wl.k)
+        versions = [v4[e] if fm[e] == B.DX_FMT_INT4G else v2[e] for e in range(wl.E)]
+        y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w)
+        yb = bf16_bits_to_f32(LY.device_to_bits(y)).astype(np.float64)
+        err = float(np.linalg.norm(yb - y_ref) / np.linalg.norm(y_ref))
+        assert err <= REL_L2_TOL, (step, err)
+        return fm
+
+    fm = check(0)
+    assert set(np.flatnonzero(fm == B.DX_FMT_INT4G)) == hi0
+    # {1, 6} -> {4, 6} through the queue: the promotion of 4 waits for the demotion of 1
+    ctx.dx_transitions_enqueue(0, promote=[4], demote=[1])
+    for step in range(1, 20):
+        issued, published, queued = ctx.dx_transitions_pump(4)
+        check(step)
+        st = ctx.dx_get_stats()
+        assert st["peak_reserved_bytes"] <= budget + b_hi + b_lo
+        if queued == 0 and st["in_flight"] == 0:
+            break
+        ctx.dx_migrate_poll(wait=True)
+    fm = check(20)
+    assert set(np.flatnonzero(fm == B.DX_FMT_INT4G)) == {4, 6}
+    assert ctx.dx_get_states()[0, 1] == B.DX_STATE_RESIDENT_LO and ctx.dx_get_states()[0, 4] == B.DX_STATE_RESIDENT_HI
+    device_version_equals(4, v4[4])                                   # the copied packed versions, bit for bit
+    device_version_equals(1, v2[1])
+    st = ctx.dx_get_stats()
+    assert st["promotions_published"] == 1 and st["demotions_published"] == 1
+    assert st["h2d_bytes"] == b_hi + b_lo and st["quantize_read_bytes"] == 0
+    assert st["reserved_bytes"] == budget
+    ctx.close()
