@@ -601,3 +601,30 @@ def test_int2_handles_need_a_group_of_64_or_more(B, LY):
     with pytest.raises(B.DxError):
         ctx.dx_swap_handle(0, 0, h)
     ctx.close()
+
+
+@pytest.mark.parametrize("T,E,k,d,f,shared_f,resident", [
+    (1, 8, 2, 256, 128, 0, [0, 3]), (7, 8, 2, 256, 128, 0, []), (16, 8, 4, 512, 384, 0, list(range(8))),
+    (17, 4, 2, 256, 256, 0, [1]), (32, 4, 3, 512, 384, 0, [0, 2]), (32, 2, 2, 256, 128, 0, [0]),
+    (32, 16, 4, 256, 128, 256, [0, 5, 9]), (9, 16, 4, 512, 256, 128, []), (32, 128, 8, 256, 128, 0, list(range(0, 128, 3))),
+])
+def test_forward_decode_group128_small_shapes(B, LY, dxo, T, E, k, d, f, shared_f, resident):
+    """Decode batches of up to 32 tokens with group 128 (K-chunks of 128): one and two token tiles per
+    expert, one to three K-chunks, all-bf16 / all-int4 / mixed tables, the shared expert; every token,
+    and the same bits on a second run (every sum has a fixed order)."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k, d=d, f=f, group=128, shared_f=shared_f)
+    print(f"decode g128 T={T} E={E} k={k} d={d} f={f} shared_f={shared_f}", flush=True)
+    x, logits = W.layer_inputs(wl, seed=21)
+    shared = W.shared_master(wl, 21, 0) if shared_f else None
+    ly = Layer(B, LY, dxo, wl, resident, seed=21, shared=shared)
+    y_gpu, y_ref = ly.run(x, logits)
+    err = rel_l2(y_gpu, y_ref)
+    print("  rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    yg = bf16_bits_to_f32(y_gpu).astype(np.float64)
+    tok = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
+    assert tok.max() <= 2 * REL_L2_TOL
+    again, _ = ly.run(x, logits)
+    assert np.array_equal(again, y_gpu)                              # a fixed summation order: bit-reproducible
+    ly.ctx.close()
