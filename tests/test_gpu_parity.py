@@ -628,3 +628,41 @@ def test_forward_decode_group128_small_shapes(B, LY, dxo, T, E, k, d, f, shared_
     again, _ = ly.run(x, logits)
     assert np.array_equal(again, y_gpu)                              # a fixed summation order: bit-reproducible
     ly.ctx.close()
+
+
+@pytest.mark.parametrize("T", [16, 200])
+def test_forward_with_a_caller_owned_handle_table(B, LY, dxo, T):
+    """dx_moe_forward(handle_table, ...): a table in caller memory (here with the opposite format of
+    every expert) is used instead of the context's own; passing the context's table address is the
+    same as passing none."""
+    import ctypes as C
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T)
+    x, logits = W.layer_inputs(wl, seed=17)
+    ly = Layer(B, LY, dxo, wl, [0, 2], seed=17)
+    ctx, rb = ly.ctx, ly.rb
+    xd, ld = LY.bits_to_device(x), torch.from_numpy(logits).cuda()
+    y0 = torch.empty((T, wl.d), dtype=torch.bfloat16, device="cuda")
+    y1, y2 = torch.empty_like(y0), torch.empty_like(y0)
+    rb.route(ctx, 0, ld, T)
+    rb.forward(ctx, 0, xd, y0, None, T)
+    rb.forward(ctx, 0, xd, y1, ctx.dx_handle_table(0), T)
+    # a second set of versions, formats flipped, in a table the caller owns
+    flipped = [e for e in range(wl.E) if e not in (0, 2)]
+    lw2 = LY.LayerWeights(ctx, 0, *ly.dev, flipped, wl.group, publish=False)
+    raw = b"".join(bytes(lw2.handle(e)) for e in range(wl.E))
+    assert len(raw) == 64 * wl.E
+    table = torch.frombuffer(bytearray(raw), dtype=torch.uint8).cuda()
+    rb.forward(ctx, 0, xd, y2, table, T)
+    sync()
+    assert torch.equal(y0, y1)
+    ids, w, *_ = dxo.route(logits, wl.k)
+    wg, wu, wd = ly.masters
+    v_flip = [dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if e in flipped
+              else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(wl.E)]
+    assert rel_l2(LY.device_to_bits(y0), dxo.moe_forward(ly.versions, wl.d, wl.f, wl.group, x, ids, w)) <= REL_L2_TOL
+    assert rel_l2(LY.device_to_bits(y2), dxo.moe_forward(v_flip, wl.d, wl.f, wl.group, x, ids, w)) <= REL_L2_TOL
+    assert not torch.equal(y0, y2)
+    assert np.array_equal(ctx.dx_get_formats()[0], [0 if e in (0, 2) else 1 for e in range(wl.E)])   # own table untouched
+    del lw2
+    ctx.close()
