@@ -90,6 +90,9 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = blockIdx.x;
     for (int e = threadIdx.x; e < E; e += kRouteThreads) lds_mask[e] = 0ull;
+    // single-chunk launch with the hotness update inside: fetch the counter now, it is added to at the end
+    unsigned long long hot_before = 0ull;
+    if (fused && hotness && (int)threadIdx.x < E) hot_before = hotness[threadIdx.x];
     __syncthreads();
 
     for (int tt = wave; tt < kChunk; tt += kWaves) {
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
     if (e < E) {
         counts[e] = c;
         offsets[e] = off;
-        if (hotness) hotness[e] += (unsigned long long)c;
+        if (hotness) hotness[e] = hot_before + (unsigned long long)c;
         lds_ids[kChunk * k + kWaves + e] = off; // offsets kept in LDS after the wave totals
     }
     if (e == 0) offsets[E] = total;
