@@ -126,19 +126,23 @@ constexpr int kThreads = 64 * kWaves; // 512
 constexpr int kMaxExperts = 1024 + 1; // routed + shared
 // Relative cost of a bf16 / int4 strip pair in the partition.  An int4 pair is a quarter of the bytes
 // but carries the same per-step work (barrier, reduction), so it is weighed by measured time, not
-// bytes: 4/8 of a bf16 pair when K is long (gate/up), 5/8 when it is short (down).
-constexpr int kHiUnits = 8;
+// bytes: 8/16 of a bf16 pair when K is long (gate/up), 10/16 when it is short (down).
+constexpr int kHiUnits = 16;
 template <bool DOWN>
-constexpr int kLoUnits = DOWN ? 5 : 4;
+constexpr int kLoUnits = DOWN ? 10 : 8;
 // A block that starts on a new expert pays for the handle, the token rows and a cold pipeline (about
 // 3 us, one and a half bf16 pairs): every expert's range begins with this many units that carry no
 // strips, so the block that holds an expert boundary gets correspondingly fewer strips.
-constexpr uint32_t kRunUnits = 12;
-// int2 pairs (an eighth of the bytes, the same per-step work) are taken one unit below the int4 ones
+constexpr uint32_t kRunUnits = 24;
+// int2 pairs (an eighth of the bytes, the same per-step work) are taken a little below the int4 ones.
+// Experts with more than 16 tokens multiply two token tiles per strip and finish twice the outputs:
+// blocks on such experts were measured 9 % (gate/up) and 19 % (down) slower; 3 and 5 extra units per
+// pair gave the shortest kernels.
 template <bool DOWN>
-__device__ __forceinline__ uint32_t units_of(uint32_t fmt)
+__device__ __forceinline__ uint32_t units_of(uint32_t fmt, int m)
 {
-    return fmt == DX_FMT_BF16 ? kHiUnits : (fmt == DX_FMT_INT4G ? kLoUnits<DOWN> : kLoUnits<DOWN> - 1);
+    const uint32_t base = fmt == DX_FMT_BF16 ? kHiUnits : (fmt == DX_FMT_INT4G ? kLoUnits<DOWN> : kLoUnits<DOWN> - 2);
+    return base + (m > 16 ? (DOWN ? 5 : 3) : 0);
 }
 
 #ifdef DX_TRACE
@@ -530,7 +534,7 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             seg_tokens[e] = m;
             seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
             if (m > 0)
-                mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * units_of<DOWN>(fmt_of(e)) + kRunUnits;
+                mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * units_of<DOWN>(fmt_of(e), m) + kRunUnits;
             local += mine[i];
         }
     }
@@ -594,7 +598,7 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
             ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
             ex.s1 = (gbf16)(DOWN ? hd.s_down : hd.s_up);
             const int spe = strips_of(e);
-            const uint32_t wgt = units_of<DOWN>((uint32_t)ex.fmt);
+            const uint32_t wgt = units_of<DOWN>((uint32_t)ex.fmt, ex.m);
             const uint32_t lo = (ub0 > cum[e] ? ub0 : cum[e]) - cum[e];
             const uint32_t hi = (ub1 < cum[e + 1] ? ub1 : cum[e + 1]) - cum[e];
             // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi); pair i starts
