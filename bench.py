@@ -405,7 +405,8 @@ def main():
                                f"per layer, rotating over {L} layers' weights",
                    "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
-                      "combine": prof["combine_ms"] * 1e3 / prof["calls"]},
+                      "combine": prof["combine_ms"] * 1e3 / prof["calls"],
+                      "empty_event_pair": prof["empty_ms"] * 1e3 / prof["calls"]},
         "roofline": roofline,
     }
 

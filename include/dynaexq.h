@@ -261,6 +261,8 @@ typedef struct {
     double gate_up_ms;  /* summed duration of the gate/up + SwiGLU kernel */
     double down_ms;     /* summed duration of the down-projection kernel */
     double combine_ms;  /* summed duration of the combine kernel (0 when fused away) */
+    double empty_ms;    /* summed elapsed time between two events recorded back to back with nothing
+                           between them: what an event pair itself adds to each figure above */
 } dx_profile;
 dx_status dx_set_profiling(dx_ctx *ctx, int enable);
 dx_status dx_get_profile(dx_ctx *ctx, dx_profile *out);

@@ -58,7 +58,7 @@ class DxStats(C.Structure):
 
 class DxProfile(C.Structure):
     _fields_ = [("calls", C.c_uint64), ("gate_up_ms", C.c_double), ("down_ms", C.c_double),
-                ("combine_ms", C.c_double)]
+                ("combine_ms", C.c_double), ("empty_ms", C.c_double)]
 
 
 class DxError(RuntimeError):
@@ -312,7 +312,8 @@ class Context:
     def dx_get_profile(self) -> dict:
         p = DxProfile()
         self._chk(self.lib.dx_get_profile(self.h, C.byref(p)), "dx_get_profile")
-        return {"calls": int(p.calls), "gate_up_ms": p.gate_up_ms, "down_ms": p.down_ms, "combine_ms": p.combine_ms}
+        return {"calls": int(p.calls), "gate_up_ms": p.gate_up_ms, "down_ms": p.down_ms, "combine_ms": p.combine_ms,
+                "empty_ms": p.empty_ms}
 
     # pools and transitions
     def dx_pools_create(self, hi_blocks, lo_blocks):

@@ -407,8 +407,8 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
         DX_HIP(c, dxk_moe_forward(a, c->n_cu, c->compute, &side, nullptr));
         return DX_OK;
     }
-    std::array<hipEvent_t, 4> m;
-    for (int i = 0; i < 4; ++i) {
+    std::array<hipEvent_t, 5> m;
+    for (int i = 0; i < 5; ++i) {
         if (!c->timing_pool.empty()) {
             m[i] = c->timing_pool.back();
             c->timing_pool.pop_back();
@@ -665,8 +665,8 @@ extern "C" dx_status dx_get_profile(dx_ctx *c, dx_profile *out)
     *out = dx_profile{};
     DX_HIP(c, hipStreamSynchronize(c->compute));
     for (auto &m : c->marks) {
-        float t[3] = {0.f, 0.f, 0.f};
-        for (int i = 0; i < 3; ++i) {
+        float t[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < 4; ++i) {
             hipError_t e = hipEventElapsedTime(&t[i], m[i], m[i + 1]);
             if (e != hipSuccess) t[i] = 0.f; // a call that recorded nothing (T == 0)
         }
@@ -674,6 +674,7 @@ extern "C" dx_status dx_get_profile(dx_ctx *c, dx_profile *out)
         out->gate_up_ms += t[0];
         out->down_ms += t[1];
         out->combine_ms += t[2];
+        out->empty_ms += t[3];
         for (auto ev : m) c->timing_pool.push_back(ev);
     }
     c->marks.clear();

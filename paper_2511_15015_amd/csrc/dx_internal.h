@@ -95,7 +95,7 @@ struct dx_ctx {
     // optional per-kernel timing of the forward pass
     bool profiling = false;
     std::vector<hipEvent_t> timing_pool;           // free timing-enabled events
-    std::vector<std::array<hipEvent_t, 4>> marks;  // one tuple per profiled forward call
+    std::vector<std::array<hipEvent_t, 5>> marks;  // one tuple per profiled forward call
 };
 
 #define DX_FAIL(ctx, code, ...)                                   \
@@ -152,8 +152,8 @@ struct dx_fwd_streams {
     hipStream_t aux[2];
     hipEvent_t fork, join[2];
 };
-// marks: null, or 4 events recorded before gate/up, after it, after down, after combine (prefill: around
-// the chain on the caller's stream)
+// marks: null, or 5 events recorded before gate/up, after it, after down, after combine (prefill: around
+// the chain on the caller's stream), and once more right away (an empty bracket)
 hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks);
 // dx_moe_prefill.hip: gate/up then down for the experts above a.m_small tokens.  The 256-row tile
 // kernels (when a.m_big) go to s_big, the 128-row ones to s_tiled (the two may be the same stream).

@@ -793,7 +793,10 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
     } else {
         hipLaunchKernelGGL(k_combine, dim3((a.d / 4 + 255) / 256, a.T), dim3(256), 0, s, a);
     }
-    if (marks) (void)hipEventRecord(marks[3], s);
+    if (marks) {
+        (void)hipEventRecord(marks[3], s);
+        (void)hipEventRecord(marks[4], s); // an empty bracket: the cost of the event pair itself
+    }
     return hipGetLastError();
 }
 
