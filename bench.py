@@ -323,9 +323,17 @@ def main():
         fwd_args = [(h, layer, None, xs[layer].data_ptr(), T, p_ids, p_w, p_off, p_perm, y.data_ptr())
                     for layer in range(L)]
 
+        step_args = [(h, layer, None, lgs[layer].data_ptr(), xs[layer].data_ptr(), T, p_ids, p_w, p_counts, p_off,
+                      p_perm, y.data_ptr()) for layer in range(L)]
+        separate = os.environ.get("DX_BENCH_SEPARATE_CALLS") == "1"
+
         def step_fn(i):
             layer = i % L
-            if lib.dx_route(*route_args[layer]) or lib.dx_moe_forward(*fwd_args[layer]):
+            if separate:
+                rc = lib.dx_route(*route_args[layer]) or lib.dx_moe_forward(*fwd_args[layer])
+            else:   # the same two steps as one call (decode batches route inside the gate/up kernel)
+                rc = lib.dx_route_forward(*step_args[layer])
+            if rc:
                 raise RuntimeError(lib.dx_last_error(h).decode())
 
         for i in range(args.warmup):
@@ -364,7 +372,8 @@ def main():
     decode = args.workload == "C2"
     if decode:
         achieved = alg_per_launch / (gate_up_us * 1e-6) / 1e9
-        roofline = {"bound": "hbm", "kernel": "k_stream<gate/up>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        roofline = {"bound": "hbm", "kernel": "k_stream<gate/up>" if separate else "k_stream_routed (routing prologue + gate/up)",
+                    "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                     "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us}
     else:
@@ -403,7 +412,8 @@ def main():
                                f"Zipf(s={wl.zipf_s}) routing, {wl.n_hi} {'int4' if quant_pair else 'bf16'} + {E - wl.n_hi} "
                                f"{'int2' if quant_pair else 'int4'}-g{wl.group} experts "
                                f"per layer, rotating over {L} layers' weights",
-                   "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"},
+                   "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"
+                           + (" as two calls" if separate else ", as one dx_route_forward call")},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
                       "combine": prof["combine_ms"] * 1e3 / prof["calls"],
                       "empty_event_pair": prof["empty_ms"] * 1e3 / prof["calls"]},

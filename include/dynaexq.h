@@ -132,6 +132,19 @@ dx_status dx_route(dx_ctx *ctx, int layer, const float *logits, int T,
                    int32_t *topk_ids, float *topk_w,
                    int32_t *counts, int32_t *offsets, int32_t *perm);
 
+/* dx_route followed by dx_moe_forward on the same arrays, as one call: same
+ * arguments, same outputs (ids, weights, counts, offsets, perm and y), same
+ * hotness update.  For decode batches (T <= 32, E <= 128, top_k <= 16, shapes
+ * that fit the streaming kernels' fast path) the gate/up kernel routes in its
+ * own prologue (every block repeats the small routing computation of Sec. 3.1
+ * and keeps it in LDS; the first block writes the arrays out), which saves the
+ * routing kernel and its round trip through memory; otherwise the two calls
+ * run one after the other.  table as in dx_moe_forward. */
+dx_status dx_route_forward(dx_ctx *ctx, int layer, const dx_handle *handle_table,
+                           const float *logits /* dev [T,E] */, const void *x_bf16 /* dev [T,d] */, int T,
+                           int32_t *topk_ids, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                           void *y_bf16 /* dev [T,d] */);
+
 /* The router's linear gate in front of dx_route (Sec. 2.1: the router scores
  * every expert for every token; Sec. 3.1 consumes its top-k):
  *   logits[t,e] = sum_c x[t,c] * w_router[e,c] (+ bias[e])

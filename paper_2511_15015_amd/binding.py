@@ -21,7 +21,7 @@ DX_STATE_EMPTY, DX_STATE_RESIDENT_HI, DX_STATE_RESIDENT_LO, DX_STATE_PROMOTING, 
 
 EXPORTS = [
     "dx_create", "dx_destroy", "dx_last_error", "dx_status_str",
-    "dx_route", "dx_router_logits", "dx_moe_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
+    "dx_route", "dx_router_logits", "dx_moe_forward", "dx_route_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
     "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
     "dx_register_host_master", "dx_register_host_packed", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
@@ -94,6 +94,7 @@ def load():
     L.dx_route.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp]
     L.dx_router_logits.argtypes = [vp, vp, vp, vp, i32, vp]
     L.dx_moe_forward.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
+    L.dx_route_forward.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     L.dx_hotness_update.argtypes = [vp, i32, vp]
     L.dx_window_end.argtypes = [vp, vp]
     L.dx_select_resident.argtypes = [vp, i32, u64, vp, C.POINTER(C.c_int32)]
@@ -233,6 +234,11 @@ class Context:
     def dx_moe_forward(self, layer, handle_table, x, T, topk_ids, topk_w, offsets, perm, y):
         self._chk(self.lib.dx_moe_forward(self.h, layer, _ptr(handle_table), _ptr(x), T, _ptr(topk_ids),
                                           _ptr(topk_w), _ptr(offsets), _ptr(perm), _ptr(y)), "dx_moe_forward")
+
+    def dx_route_forward(self, layer, handle_table, logits, x, T, topk_ids, topk_w, counts, offsets, perm, y):
+        self._chk(self.lib.dx_route_forward(self.h, layer, _ptr(handle_table), _ptr(logits), _ptr(x), T,
+                                            _ptr(topk_ids), _ptr(topk_w), _ptr(counts), _ptr(offsets), _ptr(perm),
+                                            _ptr(y)), "dx_route_forward")
 
     def dx_hotness_update(self, layer, counts):
         self._chk(self.lib.dx_hotness_update(self.h, layer, _ptr(counts)), "dx_hotness_update")

@@ -360,30 +360,28 @@ extern "C" dx_status dx_route(dx_ctx *c, int layer, const float *logits, int T, 
     return DX_OK;
 }
 
-extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table, const void *x, int T,
-                                    const int32_t *ids, const float *w, const int32_t *offsets,
-                                    const int32_t *perm, void *y)
+namespace {
+
+// validation and kernel arguments shared by dx_moe_forward and dx_route_forward (T > 0)
+dx_status forward_args(dx_ctx *c, const char *who, int layer, const dx_handle *table, const void *x, int T,
+                       const int32_t *ids, const float *w, const int32_t *offsets, const int32_t *perm, void *y,
+                       dx_fwd_args &a)
 {
-    if (!c) return DX_ERR_INVALID;
-    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: layer %d out of range", layer);
-    if (T < 0 || T > c->cfg.max_tokens)
-        DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: T=%d outside [0,%d]", T, c->cfg.max_tokens);
-    if (T == 0) return DX_OK;
-    if (!x || !y || !ids || !w || !offsets || !perm) DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: null pointer");
+    if (!x || !y || !ids || !w || !offsets || !perm) DX_FAIL(c, DX_ERR_INVALID, "%s: null pointer", who);
     const dx_config &g = c->cfg;
     if (!table) {
         // the context's own table: every expert of the layer must have a published version
         for (int e = 0; e < g.E; ++e)
             if (c->entries[entry_index(c, layer, e)].state == DX_STATE_EMPTY)
-                DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: expert (%d,%d) has no published version", layer, e);
+                DX_FAIL(c, DX_ERR_INVALID, "%s: expert (%d,%d) has no published version", who, layer, e);
         table = c->d_table + (size_t)layer * g.E;
     }
-    dx_fwd_args a{};
+    a = dx_fwd_args{};
     a.table = table;
     a.shared = nullptr;
     if (g.shared_f) {
         if (c->entries[entry_index(c, layer, g.E)].state == DX_STATE_EMPTY)
-            DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: shared expert of layer %d not installed", layer);
+            DX_FAIL(c, DX_ERR_INVALID, "%s: shared expert of layer %d not installed", who, layer);
         a.shared = c->d_table + entry_index(c, layer, g.E);
     }
     a.x = static_cast<const dx_bf16 *>(x);
@@ -402,12 +400,12 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
     a.group = g.group;
     a.shared_f = g.shared_f;
     a.fmax = c->fmax;
-    const dx_fwd_streams side{{c->aux[0], c->aux[1]}, c->fork, {c->join[0], c->join[1]}};
-    if (!c->profiling) {
-        DX_HIP(c, dxk_moe_forward(a, c->n_cu, c->compute, &side, nullptr));
-        return DX_OK;
-    }
-    std::array<hipEvent_t, 5> m;
+    return DX_OK;
+}
+
+// five timing events for a profiled call (from the pool, or new)
+dx_status take_marks(dx_ctx *c, std::array<hipEvent_t, 5> &m)
+{
     for (int i = 0; i < 5; ++i) {
         if (!c->timing_pool.empty()) {
             m[i] = c->timing_pool.back();
@@ -420,10 +418,73 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
             }
         }
     }
+    return DX_OK;
+}
+
+} // namespace
+
+extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table, const void *x, int T,
+                                    const int32_t *ids, const float *w, const int32_t *offsets,
+                                    const int32_t *perm, void *y)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: layer %d out of range", layer);
+    if (T < 0 || T > c->cfg.max_tokens)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_moe_forward: T=%d outside [0,%d]", T, c->cfg.max_tokens);
+    if (T == 0) return DX_OK;
+    dx_fwd_args a;
+    dx_status st = forward_args(c, "dx_moe_forward", layer, table, x, T, ids, w, offsets, perm, y, a);
+    if (st != DX_OK) return st;
+    const dx_fwd_streams side{{c->aux[0], c->aux[1]}, c->fork, {c->join[0], c->join[1]}};
+    if (!c->profiling) {
+        DX_HIP(c, dxk_moe_forward(a, c->n_cu, c->compute, &side, nullptr));
+        return DX_OK;
+    }
+    std::array<hipEvent_t, 5> m;
+    if ((st = take_marks(c, m)) != DX_OK) return st;
     hipError_t e = dxk_moe_forward(a, c->n_cu, c->compute, &side, m.data());
     c->marks.push_back(m);
     if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_moe_forward: %s", hipGetErrorString(e));
     return DX_OK;
+}
+
+extern "C" dx_status dx_route_forward(dx_ctx *c, int layer, const dx_handle *table, const float *logits, const void *x,
+                                      int T, int32_t *ids, float *w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                                      void *y)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!valid_layer(c, layer)) DX_FAIL(c, DX_ERR_INVALID, "dx_route_forward: layer %d out of range", layer);
+    if (T < 0 || T > c->cfg.max_tokens)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_route_forward: T=%d outside [0,%d]", T, c->cfg.max_tokens);
+    if (!counts || !offsets || (T > 0 && (!logits || !ids || !w || !perm)))
+        DX_FAIL(c, DX_ERR_INVALID, "dx_route_forward: null pointer");
+    bool routed = false;
+    if (T > 0) {
+        dx_fwd_args a;
+        dx_status st = forward_args(c, "dx_route_forward", layer, table, x, T, ids, w, offsets, perm, y, a);
+        if (st != DX_OK) return st;
+        dx_route_io r{};
+        r.logits = logits;
+        r.ids = ids;
+        r.w = w;
+        r.counts = counts;
+        r.offsets = offsets;
+        r.perm = perm;
+        r.hotness = c->cfg.route_updates_hotness ? c->d_counters + (size_t)layer * c->cfg.E : nullptr;
+        std::array<hipEvent_t, 5> m;
+        if (c->profiling && (st = take_marks(c, m)) != DX_OK) return st;
+        hipError_t e = dxk_route_forward(a, r, c->n_cu, c->compute, c->profiling ? m.data() : nullptr, &routed);
+        if (c->profiling) {
+            if (routed) c->marks.push_back(m);
+            else for (auto ev : m) c->timing_pool.push_back(ev);
+        }
+        if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_route_forward: %s", hipGetErrorString(e));
+    }
+    if (routed) return DX_OK;
+    // shapes the self-routing kernel does not take: the two separate calls
+    dx_status st = dx_route(c, layer, logits, T, ids, w, counts, offsets, perm);
+    if (st != DX_OK) return st;
+    return dx_moe_forward(c, layer, table, x, T, ids, w, offsets, perm, y);
 }
 
 extern "C" dx_status dx_router_logits(dx_ctx *c, const void *x, const void *w_router, const float *bias, int T,

@@ -146,6 +146,19 @@ struct dx_fwd_args {
     int o_bf16;  // O rows are bf16 (prefill: halves the traffic between the down kernels and the combine), else fp32
     int m_big;   // non-zero: the leading multiple of 256 rows of a bf16 expert takes the 256 x 256 tile kernel
 };
+// Decode batches that the gate/up kernel routes itself (dx_route_forward): what its first block reads and
+// writes on top of dx_fwd_args (whose ids, w, offsets and perm point at the same arrays for the kernels
+// that follow)
+constexpr int DX_ROUTED_MAX_TOKENS = 32, DX_ROUTED_MAX_EXPERTS = 128, DX_ROUTED_MAX_TOPK = 16;
+struct dx_route_io {
+    const float *logits; // [T, E]
+    int32_t *ids;        // [T, k]
+    float *w;            // [T, k]
+    int32_t *counts;     // [E]
+    int32_t *offsets;    // [E + 1]
+    int32_t *perm;       // [T * k]
+    unsigned long long *hotness; // the layer's window counters, or null
+};
 // Side streams for the prefill pass: its kernel chains (streamed small experts; 128-row tiles; 256-row
 // tiles) touch disjoint rows of H and O and run concurrently between `fork` and the joins.
 struct dx_fwd_streams {
@@ -155,6 +168,11 @@ struct dx_fwd_streams {
 // marks: null, or 5 events recorded before gate/up, after it, after down, after combine (prefill: around
 // the chain on the caller's stream), and once more right away (an empty bracket)
 hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks);
+// Routing and forward pass in one call.  Returns true in *routed when the gate/up kernel did the routing
+// (small decode batches whose shapes fit); otherwise nothing was launched and the caller runs dxk_route
+// and dxk_moe_forward.
+hipError_t dxk_route_forward(const dx_fwd_args &a, const dx_route_io &r, int n_cu, hipStream_t s, hipEvent_t *marks,
+                             bool *routed);
 // dx_moe_prefill.hip: gate/up then down for the experts above a.m_small tokens.  The 256-row tile
 // kernels (when a.m_big) go to s_big, the 128-row ones to s_tiled (the two may be the same stream).
 hipError_t dxk_moe_forward_tiled(const dx_fwd_args &a, hipStream_t s_big, hipStream_t s_tiled,

@@ -38,6 +38,9 @@
 // Batches of up to 128 tokens run here alone (segments above 32 tokens in
 // blocks of 32); larger ones hand the big segments to the tile kernels.
 #include "dx_internal.h"
+#include "dx_route_core.h"
+
+#include <cmath>
 
 namespace {
 
@@ -55,6 +58,7 @@ typedef const DX_GLOBAL dx_bf16 *gbf16; // bf16 rows (scales, tokens)
 typedef const DX_GLOBAL u32x4 *gvec16;
 typedef const DX_GLOBAL u32x2 *gvec8;
 typedef const DX_GLOBAL uint32_t *gvec4;
+typedef const __attribute__((address_space(3))) int *lds_ints; // an int array in LDS
 
 union frag8 {
     u32x4 u;
@@ -313,6 +317,7 @@ struct expert_ctx {
     int seg0, m;     // segment in the H/O scratch, tokens
     bool shared;
     int fmt;         // dx_fmt of the published version
+    lds_ints perm_lds; // the permutation in LDS when the kernel routed itself, else null (a.perm is used)
 };
 
 // Add up the partial sums of the strip pairs sb .. sb+live_groups-1 in a fixed order and finish them:
@@ -472,7 +477,11 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
             if constexpr (DOWN) {
                 arow[mt] = (gbf16)a.h + (size_t)(ex.seg0 + slot) * a.fmax;
             } else {
-                const int tok = ex.shared ? slot : a.perm[ex.seg0 + slot] / a.k;
+                int tok = slot;
+                if (!ex.shared) {
+                    const int p = ex.perm_lds ? ex.perm_lds[ex.seg0 + slot] : a.perm[ex.seg0 + slot];
+                    tok = p / a.k;
+                }
                 arow[mt] = (gbf16)a.x + (size_t)tok * ex.K;
             }
         }
@@ -502,22 +511,23 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     }
 }
 
-template <int LK, int CPW, bool DOWN, bool FAST>
-__global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
+// LDS of the partition: per expert its tokens, its segment start and the prefix of the cost units
+struct partition_lds {
+    uint32_t cum[kMaxExperts + 1];
+    int seg_start[kMaxExperts], seg_tokens[kMaxExperts];
+    uint32_t wave_tot[kWaves];
+    int wave_cnt[kWaves];
+    int e_first;
+};
+
+// The partition: cost units of every expert, exclusive prefix, this block's unit range [ub0, ub1) and the
+// first expert in it.  Experts above m_small tokens belong to the tiled kernels: they count as empty
+// here.  All threads; ends with a barrier.
+template <bool DOWN>
+__device__ __forceinline__ void build_partition(const dx_fwd_args &a, partition_lds &pl, uint32_t &ub0, uint32_t &ub1)
 {
-    __shared__ f32x4 red[2][kWaves][4][64]; // 64 KB: partial sums, double buffered
-    __shared__ uint32_t cum[kMaxExperts + 1];
-    __shared__ int seg_start[kMaxExperts], seg_tokens[kMaxExperts];
-    __shared__ uint32_t wave_tot[kWaves];
-    __shared__ int e_first_s;
-#ifdef DX_TRACE
-    const unsigned long long trace_t0 = wall_clock64();
-#endif
     const int nE = a.E + (a.shared ? 1 : 0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-    // ---- the partition: cost units of every expert, exclusive prefix, this block's range ----
-    // experts above m_small tokens belong to the tiled kernels: they count as empty here
     auto tokens_of = [&](int e) {
         const int m = e == a.E ? a.T : a.offsets[e + 1] - a.offsets[e];
         return m <= a.m_small ? m : 0;
@@ -531,8 +541,8 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
         const int e = tid * R + i;
         if (i < R && e < nE) {
             const int m = tokens_of(e);
-            seg_tokens[e] = m;
-            seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
+            pl.seg_tokens[e] = m;
+            pl.seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
             if (m > 0)
                 mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * units_of<DOWN>(fmt_of(e), m) + kRunUnits;
             local += mine[i];
@@ -544,13 +554,13 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
         const uint32_t o = __shfl_up(inc, off, 64);
         if (lane >= off) inc += o;
     }
-    if (lane == 63) wave_tot[wave] = inc;
-    if (tid == 0) e_first_s = nE;
+    if (lane == 63) pl.wave_tot[wave] = inc;
+    if (tid == 0) pl.e_first = nE;
     __syncthreads();
     uint32_t base = 0, U = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-        const uint32_t t = wave_tot[w];
+        const uint32_t t = pl.wave_tot[w];
         if (w < wave) base += t;
         U += t;
     }
@@ -559,81 +569,231 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
     for (int i = 0; i < 3; ++i) {
         const int e = tid * R + i;
         if (i < R && e < nE) {
-            cum[e] = run;
+            pl.cum[e] = run;
             run += mine[i];
         }
     }
-    if (tid == 0) cum[nE] = U;
-    const uint32_t ub0 = (uint32_t)(((unsigned long long)U * blockIdx.x) / gridDim.x);
-    const uint32_t ub1 = (uint32_t)(((unsigned long long)U * (blockIdx.x + 1)) / gridDim.x);
+    if (tid == 0) pl.cum[nE] = U;
+    ub0 = (uint32_t)(((unsigned long long)U * blockIdx.x) / gridDim.x);
+    ub1 = (uint32_t)(((unsigned long long)U * (blockIdx.x + 1)) / gridDim.x);
     __syncthreads();
     // the expert whose unit range contains ub0 (experts without work have empty ranges)
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
         const int e = tid * R + i;
-        if (i < R && e < nE && cum[e] <= ub0 && ub0 < cum[e + 1]) e_first_s = e;
+        if (i < R && e < nE && pl.cum[e] <= ub0 && ub0 < pl.cum[e + 1]) pl.e_first = e;
     }
     __syncthreads();
+}
 
+// This block's share: the strip pairs whose first unit lies in [ub0, ub1), run by run.
+template <int LK, int CPW, bool DOWN, bool FAST>
+__device__ __forceinline__ void run_share(const dx_fwd_args &a, const partition_lds &pl, uint32_t ub0, uint32_t ub1,
+                                          lds_ints perm_lds, f32x4 (*red)[kWaves][4][64])
+{
+    const int nE = a.E + (a.shared ? 1 : 0);
+    int pb = 0;
+    if (ub0 >= ub1) return;
+    for (int e = pl.e_first; e < nE && pl.cum[e] < ub1; ++e) {
+        const uint32_t ue = pl.cum[e + 1] - pl.cum[e];
+        if (ue == 0) continue;
+        expert_ctx ex;
+        ex.shared = e == a.E;
+        ex.m = pl.seg_tokens[e];
+        ex.seg0 = pl.seg_start[e];
+        ex.perm_lds = perm_lds;
+        const dx_handle hd = ex.shared ? *a.shared : a.table[e];
+        ex.fmt = (int)hd.fmt;
+        const int fe = ex.shared ? a.shared_f : a.f;
+        ex.K = DOWN ? fe : a.d;
+        ex.G = ex.K / a.group;
+        ex.row_bytes = ex.fmt == DX_FMT_BF16 ? (size_t)ex.K * 2 : (ex.fmt == DX_FMT_INT4G ? (size_t)ex.K / 2 : (size_t)ex.K / 4);
+        ex.w0 = (gbytes)(DOWN ? hd.w_down : hd.w_gate);
+        ex.w1 = (gbytes)(DOWN ? hd.w_down : hd.w_up);
+        ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
+        ex.s1 = (gbf16)(DOWN ? hd.s_down : hd.s_up);
+        const int spe = DOWN ? a.d / 32 : fe / 16;
+        const uint32_t wgt = units_of<DOWN>((uint32_t)ex.fmt, ex.m);
+        const uint32_t lo = (ub0 > pl.cum[e] ? ub0 : pl.cum[e]) - pl.cum[e];
+        const uint32_t hi = (ub1 < pl.cum[e + 1] ? ub1 : pl.cum[e + 1]) - pl.cum[e];
+        // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi); pair i starts
+        // kRunUnits + i * wgt units into the expert's range
+        const uint32_t lo_p = lo > kRunUnits ? lo - kRunUnits : 0, hi_p = hi > kRunUnits ? hi - kRunUnits : 0;
+        int i = (int)((lo_p + wgt - 1) / wgt);
+        const int i1 = (int)((hi_p + wgt - 1) / wgt);
+        while (i < i1) {
+            const int mb = i / spe;
+            const int iend = i1 < (mb + 1) * spe ? i1 : (mb + 1) * spe;
+            const int s_lo = i - mb * spe, s_hi = iend - mb * spe;
+            const bool two = ex.m - mb * 32 > 16;
+            if (ex.fmt == DX_FMT_INT4G) {
+                if (two) run_strips<LK, CPW, DOWN, 1, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                else run_strips<LK, CPW, DOWN, 1, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+            } else if (ex.fmt == DX_FMT_INT2G) {
+                // (16 codes per word: the library refuses int2 handles when the group is 32, i.e. LK = 8)
+                if constexpr (LK >= 16) {
+                    if (two) run_strips<LK, CPW, DOWN, 2, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                    else run_strips<LK, CPW, DOWN, 2, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                }
+            } else {
+                if (two) run_strips<LK, CPW, DOWN, 0, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+                else run_strips<LK, CPW, DOWN, 0, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
+            }
+            i = iend;
+        }
+    }
+}
+
+template <int LK, int CPW, bool DOWN, bool FAST>
+__global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
+{
+    __shared__ f32x4 red[2][kWaves][4][64]; // 64 KB: partial sums, double buffered
+    __shared__ partition_lds pl;
+#ifdef DX_TRACE
+    const unsigned long long trace_t0 = wall_clock64();
+#endif
+    uint32_t ub0, ub1;
+    build_partition<DOWN>(a, pl, ub0, ub1);
 #ifdef DX_TRACE
     const unsigned long long trace_t1 = wall_clock64();
 #endif
-    int pb = 0;
-    if (ub0 < ub1) {
-        for (int e = e_first_s; e < nE && cum[e] < ub1; ++e) {
-            const uint32_t ue = cum[e + 1] - cum[e];
-            if (ue == 0) continue;
-            expert_ctx ex;
-            ex.shared = e == a.E;
-            ex.m = seg_tokens[e];
-            ex.seg0 = seg_start[e];
-            const dx_handle hd = ex.shared ? *a.shared : a.table[e];
-            ex.fmt = (int)hd.fmt;
-            const int fe = ex.shared ? a.shared_f : a.f;
-            ex.K = DOWN ? fe : a.d;
-            ex.G = ex.K / a.group;
-            ex.row_bytes = ex.fmt == DX_FMT_BF16 ? (size_t)ex.K * 2 : (ex.fmt == DX_FMT_INT4G ? (size_t)ex.K / 2 : (size_t)ex.K / 4);
-            ex.w0 = (gbytes)(DOWN ? hd.w_down : hd.w_gate);
-            ex.w1 = (gbytes)(DOWN ? hd.w_down : hd.w_up);
-            ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
-            ex.s1 = (gbf16)(DOWN ? hd.s_down : hd.s_up);
-            const int spe = strips_of(e);
-            const uint32_t wgt = units_of<DOWN>((uint32_t)ex.fmt, ex.m);
-            const uint32_t lo = (ub0 > cum[e] ? ub0 : cum[e]) - cum[e];
-            const uint32_t hi = (ub1 < cum[e + 1] ? ub1 : cum[e + 1]) - cum[e];
-            // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi); pair i starts
-            // kRunUnits + i * wgt units into the expert's range
-            const uint32_t lo_p = lo > kRunUnits ? lo - kRunUnits : 0, hi_p = hi > kRunUnits ? hi - kRunUnits : 0;
-            int i = (int)((lo_p + wgt - 1) / wgt);
-            const int i1 = (int)((hi_p + wgt - 1) / wgt);
-            while (i < i1) {
-                const int mb = i / spe;
-                const int iend = i1 < (mb + 1) * spe ? i1 : (mb + 1) * spe;
-                const int s_lo = i - mb * spe, s_hi = iend - mb * spe;
-                const bool two = ex.m - mb * 32 > 16;
-                if (ex.fmt == DX_FMT_INT4G) {
-                    if (two) run_strips<LK, CPW, DOWN, 1, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                    else run_strips<LK, CPW, DOWN, 1, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                } else if (ex.fmt == DX_FMT_INT2G) {
-                    // (16 codes per word: the library refuses int2 handles when the group is 32, i.e. LK = 8)
-                    if constexpr (LK >= 16) {
-                        if (two) run_strips<LK, CPW, DOWN, 2, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                        else run_strips<LK, CPW, DOWN, 2, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                    }
-                } else {
-                    if (two) run_strips<LK, CPW, DOWN, 0, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                    else run_strips<LK, CPW, DOWN, 0, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
-                }
-                i = iend;
-            }
-        }
-    }
+    run_share<LK, CPW, DOWN, FAST>(a, pl, ub0, ub1, nullptr, red);
 #ifdef DX_TRACE
     if (threadIdx.x == 0 && blockIdx.x < 8192) {
         g_trace[DOWN ? 1 : 0][blockIdx.x][0] = trace_t0;
         g_trace[DOWN ? 1 : 0][blockIdx.x][1] = wall_clock64();
         g_trace[DOWN ? 1 : 0][blockIdx.x][2] = ub1 - ub0;
         g_trace[DOWN ? 1 : 0][blockIdx.x][3] = trace_t1;
+    }
+#endif
+}
+
+// Decode batches of at most kRoutedTokens tokens and kRoutedExperts experts: the gate/up kernel routes
+// by itself.  Every block repeats the small routing computation (top-k and weights per token, counts,
+// offsets and the stable permutation, as dx_route.hip does them) in its prologue and keeps the result in
+// LDS, so the forward pass does not wait for a routing kernel and its round trip through memory; block 0
+// also writes the routing arrays out for the down and combine kernels and for the caller, and adds the
+// counts to the layer's hotness counters.
+constexpr int kRoutedTokens = DX_ROUTED_MAX_TOKENS, kRoutedExperts = DX_ROUTED_MAX_EXPERTS, kRoutedTopK = DX_ROUTED_MAX_TOPK;
+
+template <int LK, int CPW>
+__global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_route_io r)
+{
+    __shared__ f32x4 red[2][kWaves][4][64];
+    __shared__ partition_lds pl;
+    __shared__ unsigned long long lds_mask[kRoutedExperts];
+    __shared__ int lds_perm[kRoutedTokens * kRoutedTopK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool writer = blockIdx.x == 0;
+    const int nE = a.E + (a.shared ? 1 : 0);
+    static_assert(kRoutedTokens == 4 * kWaves && kRoutedExperts == 128 && kRoutedTopK == 16,
+                  "one token per 16-lane row, eight logits per lane, one selected id per lane of the row");
+#ifdef DX_TRACE
+    const unsigned long long trace_t0 = wall_clock64();
+    unsigned long long trace_t1 = 0, trace_t2 = 0, trace_t3 = 0;
+#endif
+
+    if (tid < kRoutedExperts) lds_mask[tid] = 0ull;
+    unsigned long long hot_before = 0ull;
+    if (writer && r.hotness && tid < a.E) hot_before = r.hotness[tid];
+    uint32_t fmt = DX_FMT_BF16; // of expert `tid`
+    if (tid < a.E) fmt = a.table[tid].fmt;
+    // ---- top-k and weights: token 4 * wavefront + row (rows past T repeat the last token)
+    const int c = lane & 15, t = 4 * wave + (lane >> 4);
+    int my_id;
+    float my_w;
+    {
+        const float *row = r.logits + (size_t)(t < a.T ? t : a.T - 1) * a.E;
+        float v[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) v[s] = 8 * c + s < a.E ? row[8 * c + s] : -INFINITY;
+        __syncthreads(); // the masks are clear
+#ifdef DX_TRACE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        trace_t1 = wall_clock64();
+#endif
+        dx_route_core::topk_rows16(v, a.k, lane, my_id, my_w);
+#ifdef DX_TRACE
+        trace_t2 = wall_clock64();
+#endif
+    }
+    const bool have = t < a.T && c < a.k; // this lane holds pair (t, c)
+    if (have) {
+        atomicOr(&lds_mask[my_id], 1ull << t);
+        if (writer) {
+            r.ids[(size_t)t * a.k + c] = my_id;
+            r.w[(size_t)t * a.k + c] = my_w;
+        }
+    }
+    __syncthreads();
+    // ---- counts, offsets (exclusive scan) and the cost units of the partition, one expert per thread
+    const int e = tid;
+    int cnt = 0, m = 0, mine = 0;
+    if (e < a.E) cnt = m = __popcll(lds_mask[e]);
+    else if (e == a.E && a.shared) m = a.T;
+    if (m > 0)
+        mine = ((m + 31) / 32) * ((e == a.E ? a.shared_f : a.f) / 16) * (int)units_of<false>(fmt, m) + (int)kRunUnits;
+    const int inc = dx_route_core::wave_scan_inclusive(mine), cinc = dx_route_core::wave_scan_inclusive(cnt);
+    if (lane == 63) {
+        pl.wave_tot[wave] = (uint32_t)inc;
+        pl.wave_cnt[wave] = cinc;
+    }
+    if (tid == 0) pl.e_first = nE;
+    __syncthreads();
+    uint32_t base = 0, U = 0;
+    int cbase = 0, ctot = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t tu = pl.wave_tot[w];
+        const int tc = pl.wave_cnt[w];
+        if (w < wave) {
+            base += tu;
+            cbase += tc;
+        }
+        U += tu;
+        ctot += tc;
+    }
+    const int off_e = cbase + cinc - cnt;
+    const uint32_t cum_e = base + (uint32_t)(inc - mine);
+    if (e < nE) {
+        pl.cum[e] = cum_e;
+        pl.seg_tokens[e] = m;
+        pl.seg_start[e] = e == a.E ? a.T * a.k : off_e;
+    }
+    if (tid == 0) pl.cum[nE] = U;
+    if (writer) {
+        if (e < a.E) {
+            r.counts[e] = cnt;
+            r.offsets[e] = off_e;
+            if (r.hotness) r.hotness[e] = hot_before + (unsigned long long)cnt;
+        }
+        if (e == 0) r.offsets[a.E] = ctot;
+    }
+    // this block's unit range (in double: exact for these sizes, and every block evaluates the same
+    // expression for a shared boundary)
+    const double share = (double)U / (double)gridDim.x;
+    const uint32_t ub0 = (uint32_t)(share * (double)blockIdx.x);
+    const uint32_t ub1 = blockIdx.x + 1 == gridDim.x ? U : (uint32_t)(share * (double)(blockIdx.x + 1));
+    if (e < nE && mine && cum_e <= ub0 && ub0 < cum_e + (uint32_t)mine) pl.e_first = e;
+    __syncthreads();
+    // ---- the permutation: the rank of pair (t, c) inside its segment = tokens below t that chose the expert
+    if (have) {
+        const unsigned long long below = lds_mask[my_id] & ((1ull << t) - 1ull);
+        const int at = pl.seg_start[my_id] + __popcll(below);
+        lds_perm[at] = t * a.k + c;
+        if (writer) r.perm[at] = t * a.k + c;
+    }
+    __syncthreads();
+#ifdef DX_TRACE
+    trace_t3 = wall_clock64();
+#endif
+    run_share<LK, CPW, false, true>(a, pl, ub0, ub1, (lds_ints)lds_perm, red);
+#ifdef DX_TRACE
+    if (threadIdx.x == 0 && blockIdx.x < 8192) {
+        g_trace[0][blockIdx.x][0] = trace_t0;
+        g_trace[0][blockIdx.x][1] = wall_clock64();
+        g_trace[0][blockIdx.x][2] = trace_t1 - trace_t0 + ((trace_t2 - trace_t1) << 20) + ((trace_t3 - trace_t2) << 40);
+        g_trace[0][blockIdx.x][3] = trace_t3;
     }
 #endif
 }
@@ -732,8 +892,11 @@ void launch_stream(const dx_fwd_args &a, split_choice c, dim3 grid, hipStream_t 
 // pass (measured on the 30B-shaped layer: 140 us against 171 us at T = 128, equal at T = 256).
 constexpr int kStreamOnlyTokens = 128;
 
+// r: null, or the routing inputs and outputs of a call that asks the gate/up kernel to route; *routed
+// then tells whether it did (if not, nothing has been launched).
 template <int LK>
-hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks)
+hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks,
+                      const dx_route_io *r, bool *routed)
 {
     constexpr int CHUNK = 4 * LK;
     dx_fwd_args a = a_in;
@@ -750,10 +913,19 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
     a.o_bf16 = mixed; // d % 128 == 0 there, so rows split into 8-column pieces
     const split_choice gu = pick_split(a.d / CHUNK, a.d / CHUNK);
     const split_choice dn = pick_split(a.f / CHUNK, (a.shared ? a.shared_f : a.f) / CHUNK);
+    if (r) {
+        *routed = !mixed && gu.fast && a.T >= 1 && a.T <= kRoutedTokens && a.E <= kRoutedExperts && a.k <= kRoutedTopK;
+        if (!*routed) return hipSuccess;
+    }
     if (!mixed) {
         const dim3 grid(n_cu);
         if (marks) (void)hipEventRecord(marks[0], s);
-        launch_stream<LK, false>(a, gu, grid, s);
+        if (r) {
+            if (gu.cpw == 2) hipLaunchKernelGGL((k_stream_routed<LK, 2>), grid, dim3(kThreads), 0, s, a, *r);
+            else hipLaunchKernelGGL((k_stream_routed<LK, 1>), grid, dim3(kThreads), 0, s, a, *r);
+        } else {
+            launch_stream<LK, false>(a, gu, grid, s);
+        }
         if (marks) (void)hipEventRecord(marks[1], s);
         launch_stream<LK, true>(a, dn, grid, s);
         if (marks) (void)hipEventRecord(marks[2], s);
@@ -813,7 +985,17 @@ hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const 
 {
     if (a.T == 0) return hipSuccess;
     // K-chunk = min(group, 128) so that a chunk never crosses a quantization group
-    if (a.group >= 128) return launch_all<32>(a, n_cu, s, side, marks);
-    if (a.group == 64) return launch_all<16>(a, n_cu, s, side, marks);
-    return launch_all<8>(a, n_cu, s, side, marks);
+    if (a.group >= 128) return launch_all<32>(a, n_cu, s, side, marks, nullptr, nullptr);
+    if (a.group == 64) return launch_all<16>(a, n_cu, s, side, marks, nullptr, nullptr);
+    return launch_all<8>(a, n_cu, s, side, marks, nullptr, nullptr);
+}
+
+hipError_t dxk_route_forward(const dx_fwd_args &a, const dx_route_io &r, int n_cu, hipStream_t s, hipEvent_t *marks,
+                             bool *routed)
+{
+    *routed = false;
+    if (a.T == 0) return hipSuccess;
+    if (a.group >= 128) return launch_all<32>(a, n_cu, s, nullptr, marks, &r, routed);
+    if (a.group == 64) return launch_all<16>(a, n_cu, s, nullptr, marks, &r, routed);
+    return launch_all<8>(a, n_cu, s, nullptr, marks, &r, routed);
 }

@@ -11,6 +11,7 @@
 // builds, per expert, a 64-bit mask of the tokens that selected it; ranks are
 // population counts of mask prefixes.  No atomics decide any position.
 #include "dx_internal.h"
+#include "dx_route_core.h"
 
 #include <cfloat>
 
@@ -44,38 +45,6 @@ __device__ int block_exclusive_scan(int v, int *lds_wave_tot /*[kWaves]*/, int *
     return base + inc - v;
 }
 
-// Wave-wide max / sum in six DPP steps (no LDS round trips).  Lane 63 ends up with the reduction over
-// all 64 lanes and is read back as a scalar.
-template <int CTRL, int ROW_MASK, bool BOUND>
-__device__ __forceinline__ float dpp_move(float old, float x)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL, ROW_MASK, 0xF, BOUND));
-}
-
-__device__ __forceinline__ float wave_max(float x)
-{
-    x = fmaxf(x, dpp_move<0xB1, 0xF, false>(x, x));  // quad_perm [1,0,3,2]
-    x = fmaxf(x, dpp_move<0x4E, 0xF, false>(x, x));  // quad_perm [2,3,0,1]
-    x = fmaxf(x, dpp_move<0x141, 0xF, false>(x, x)); // row_half_mirror
-    x = fmaxf(x, dpp_move<0x140, 0xF, false>(x, x)); // row_mirror: every 16-lane row is uniform now
-    x = fmaxf(x, dpp_move<0x142, 0xA, false>(x, x)); // row_bcast:15 into rows 1 and 3
-    x = fmaxf(x, dpp_move<0x143, 0xC, false>(x, x)); // row_bcast:31 into rows 2 and 3
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
-}
-
-__device__ __forceinline__ float wave_sum(float x)
-{
-    // inclusive scan inside each row by shifts (lanes shifted in from outside the row contribute 0) ...
-    x += dpp_move<0x111, 0xF, true>(0.f, x); // row_shr:1
-    x += dpp_move<0x112, 0xF, true>(0.f, x); // row_shr:2
-    x += dpp_move<0x114, 0xF, true>(0.f, x); // row_shr:4
-    x += dpp_move<0x118, 0xF, true>(0.f, x); // row_shr:8 -> lane 15 of every row holds the row's sum
-    // ... then the row sums travel to lane 63
-    x += dpp_move<0x142, 0xA, false>(0.f, x); // row_bcast:15 into rows 1 and 3
-    x += dpp_move<0x143, 0xC, false>(0.f, x); // row_bcast:31 into rows 2 and 3
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
-}
-
 // One chunk of 64 tokens per block.  NV = logits held per lane (E <= 64*NV).
 template <int NV>
 __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
@@ -99,42 +68,19 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
         const int t = chunk * kChunk + tt;
         if (t >= T) break; // wave-uniform
         const float *row = logits + (size_t)t * E;
-        float v[NV];
+        float v[1][NV];
 #pragma unroll
         for (int s = 0; s < NV; ++s) {
             const int e = lane + 64 * s;
-            v[s] = e < E ? row[e] : -INFINITY;
+            v[0][s] = e < E ? row[e] : -INFINITY;
         }
-        int my_id = 0;
-        float my_logit = -INFINITY;
-        for (int j = 0; j < k; ++j) {
-            float bv = v[0];
-#pragma unroll
-            for (int s = 1; s < NV; ++s) bv = fmaxf(bv, v[s]);
-            const float top = wave_max(bv);
-            // the lowest expert index holding `top`: element e = lane + 64*s, so scan s upward and take
-            // the lowest lane of the first non-empty ballot (taken entries are -inf and never match)
-            int idx = 0;
-            bool found = false;
-#pragma unroll
-            for (int s = 0; s < NV; ++s) {
-                const unsigned long long bal = __ballot(v[s] == top);
-                if (!found && bal) {
-                    idx = 64 * s + __builtin_ctzll(bal);
-                    found = true;
-                }
-            }
-#pragma unroll
-            for (int s = 0; s < NV; ++s)
-                if (idx == lane + 64 * s) v[s] = -INFINITY;
-            if (lane == j) { my_id = idx; my_logit = top; }
-        }
-        const float top0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_logit), 0));
-        const float ex = lane < k ? expf(my_logit - top0) : 0.f;
-        const float sum = wave_sum(ex);
+        int id1[1];
+        float wt1[1];
+        dx_route_core::topk_rows<NV, 1>(v, k, lane, id1, wt1);
+        const int my_id = id1[0];
         if (lane < k) {
             ids[(size_t)t * k + lane] = my_id;
-            w[(size_t)t * k + lane] = ex / sum;
+            w[(size_t)t * k + lane] = wt1[0];
             lds_ids[tt * k + lane] = my_id;
             atomicOr(&lds_mask[my_id], 1ull << tt);
         }

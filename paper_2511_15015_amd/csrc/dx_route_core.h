@@ -1,0 +1,151 @@
+// Device code of the router's top-k, shared by the route kernel and by the decode kernel that routes in
+// its own prologue: both must pick the same ids and compute the same weights, bit for bit.
+//
+// Paper: Sec. 2.1 / 3.1 (the router scores the experts per token and the top-k of them run).
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace dx_route_core {
+
+// Wave-wide max / sum in six DPP steps (no LDS round trips).  Lane 63 ends up with the reduction over
+// all 64 lanes and is read back as a scalar.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ float dpp_move(float old, float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL, ROW_MASK, 0xF, BOUND));
+}
+
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = fmaxf(x, dpp_move<0xB1, 0xF, false>(x, x));  // quad_perm [1,0,3,2]
+    x = fmaxf(x, dpp_move<0x4E, 0xF, false>(x, x));  // quad_perm [2,3,0,1]
+    x = fmaxf(x, dpp_move<0x141, 0xF, false>(x, x)); // row_half_mirror
+    x = fmaxf(x, dpp_move<0x140, 0xF, false>(x, x)); // row_mirror: every 16-lane row is uniform now
+    x = fmaxf(x, dpp_move<0x142, 0xA, false>(x, x)); // row_bcast:15 into rows 1 and 3
+    x = fmaxf(x, dpp_move<0x143, 0xC, false>(x, x)); // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+    // inclusive scan inside each row by shifts (lanes shifted in from outside the row contribute 0) ...
+    x += dpp_move<0x111, 0xF, true>(0.f, x); // row_shr:1
+    x += dpp_move<0x112, 0xF, true>(0.f, x); // row_shr:2
+    x += dpp_move<0x114, 0xF, true>(0.f, x); // row_shr:4
+    x += dpp_move<0x118, 0xF, true>(0.f, x); // row_shr:8 -> lane 15 of every row holds the row's sum
+    // ... then the row sums travel to lane 63
+    x += dpp_move<0x142, 0xA, false>(0.f, x); // row_bcast:15 into rows 1 and 3
+    x += dpp_move<0x143, 0xC, false>(0.f, x); // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+// Top-k ids and routing weights of NT token rows by one wavefront.  v[i][s] is the logit of expert
+// lane + 64*s of row i (-inf past the last expert); it is consumed.  On return lane j < k holds the
+// j-th id of row i (descending logit, ties to the lower index) in id[i] and its weight, the softmax over
+// the k selected logits, in wt[i].  The NT rows advance together, one selection per round, so that their
+// dependency chains overlap.
+template <int NV, int NT>
+__device__ __forceinline__ void topk_rows(float (&v)[NT][NV], int k, int lane, int (&id)[NT], float (&wt)[NT])
+{
+    float lg[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        id[i] = 0;
+        lg[i] = -INFINITY;
+    }
+    for (int j = 0; j < k; ++j) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            float bv = v[i][0];
+#pragma unroll
+            for (int s = 1; s < NV; ++s) bv = fmaxf(bv, v[i][s]);
+            const float top = wave_max(bv);
+            // the lowest expert index holding `top`: element e = lane + 64*s, so scan s upward and take
+            // the lowest lane of the first non-empty ballot (taken entries are -inf and never match)
+            int idx = 0;
+            bool found = false;
+#pragma unroll
+            for (int s = 0; s < NV; ++s) {
+                const unsigned long long bal = __ballot(v[i][s] == top);
+                if (!found && bal) {
+                    idx = 64 * s + __builtin_ctzll(bal);
+                    found = true;
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < NV; ++s)
+                if (idx == lane + 64 * s) v[i][s] = -INFINITY;
+            if (lane == j) {
+                id[i] = idx;
+                lg[i] = top;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const float top0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lg[i]), 0));
+        const float ex = lane < k ? expf(lg[i] - top0) : 0.f;
+        const float sum = wave_sum(ex);
+        wt[i] = ex / sum;
+    }
+}
+
+// Inclusive prefix sum over the 64 lanes in six DPP steps (the scan inside wave_sum, for integers).
+__device__ __forceinline__ int wave_scan_inclusive(int x)
+{
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true); // row_shr:1 (zero from outside the row)
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true); // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true); // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true); // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false); // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false); // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+// Four token rows per wavefront, one per 16-lane row, so that one instruction stream serves all four:
+// lane c of a row owns the experts 8c .. 8c+7 of its token (E <= 128), v[s] is the logit of expert 8c+s
+// (-inf past the last expert) and is consumed.  Same results as topk_rows: on return lane c < k of a row
+// holds the c-th id of its token and its weight (k <= 16).  The weights add up in the order of wave_sum
+// (a 16-lane row scan), so they are the same bits.
+__device__ __forceinline__ void topk_rows16(float (&v)[8], int k, int lane, int &id, float &wt)
+{
+    const int c = lane & 15;
+    id = 0;
+    float lg = -INFINITY;
+    for (int j = 0; j < k; ++j) {
+        float top = v[0];
+#pragma unroll
+        for (int s = 1; s < 8; ++s) top = fmaxf(top, v[s]);
+        top = fmaxf(top, dpp_move<0xB1, 0xF, false>(top, top));  // quad_perm [1,0,3,2]
+        top = fmaxf(top, dpp_move<0x4E, 0xF, false>(top, top));  // quad_perm [2,3,0,1]
+        top = fmaxf(top, dpp_move<0x141, 0xF, false>(top, top)); // row_half_mirror
+        top = fmaxf(top, dpp_move<0x140, 0xF, false>(top, top)); // row_mirror: uniform over the row
+        // the lowest expert index that holds it: lowest own candidate, then the minimum over the row
+        int cand = 0x7fffffff;
+#pragma unroll
+        for (int s = 7; s >= 0; --s)
+            if (v[s] == top) cand = 8 * c + s;
+        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0xB1, 0xF, 0xF, false));
+        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0x4E, 0xF, 0xF, false));
+        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0x141, 0xF, 0xF, false));
+        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0x140, 0xF, 0xF, false));
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            if (cand == 8 * c + s) v[s] = -INFINITY;
+        if (c == j) {
+            id = cand;
+            lg = top;
+        }
+    }
+    const float top0 = __shfl(lg, lane & 48, 64);
+    const float ex = c < k ? expf(lg - top0) : 0.f;
+    float x = ex;
+    x += dpp_move<0x111, 0xF, true>(0.f, x); // row_shr:1
+    x += dpp_move<0x112, 0xF, true>(0.f, x); // row_shr:2
+    x += dpp_move<0x114, 0xF, true>(0.f, x); // row_shr:4
+    x += dpp_move<0x118, 0xF, true>(0.f, x); // row_shr:8 -> lane 15 of the row holds its sum
+    const float sum = __shfl(x, lane | 15, 64);
+    wt = ex / sum;
+}
+
+} // namespace dx_route_core

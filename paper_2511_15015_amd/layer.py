@@ -126,6 +126,10 @@ class RoutingBuffers:
         T = self.T if T is None else T
         ctx.dx_route(layer, logits, T, self.ids, self.w, self.counts, self.offsets, self.perm)
 
+    def route_forward(self, ctx: B.Context, layer: int, logits, x, y, table=None, T=None):
+        T = self.T if T is None else T
+        ctx.dx_route_forward(layer, table, logits, x, T, self.ids, self.w, self.counts, self.offsets, self.perm, y)
+
     def forward(self, ctx: B.Context, layer: int, x, y, table=None, T=None):
         T = self.T if T is None else T
         ctx.dx_moe_forward(layer, table, x, T, self.ids, self.w, self.offsets, self.perm, y)

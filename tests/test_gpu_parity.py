@@ -666,3 +666,115 @@ def test_forward_with_a_caller_owned_handle_table(B, LY, dxo, T):
     assert np.array_equal(ctx.dx_get_formats()[0], [0 if e in (0, 2) else 1 for e in range(wl.E)])   # own table untouched
     del lw2
     ctx.close()
+
+
+# --------------------------------------------- routing inside the forward call
+def _route_forward_case(B, LY, dxo, wl, resident, seed, shared=None, logits=None, hotness=False):
+    """dx_route_forward against the oracle (every routing array bit-exact, y within the bar) and against
+    dx_route + dx_moe_forward on the same inputs (the same bits)."""
+    x, lg = W.layer_inputs(wl, seed=seed)
+    if logits is not None:
+        lg = logits
+    T = wl.T
+    ly = Layer(B, LY, dxo, wl, resident, seed=seed, shared=shared)
+    ctx, rb = ly.ctx, ly.rb
+    xd, ld = LY.bits_to_device(x), torch.from_numpy(lg).cuda()
+    y_sep = torch.empty((T, wl.d), dtype=torch.bfloat16, device="cuda")
+    y_one = torch.full_like(y_sep, float("nan"))
+    rb.route(ctx, 0, ld, T)
+    rb.forward(ctx, 0, xd, y_sep, None, T)
+    sync()
+    for t in (rb.ids, rb.counts, rb.offsets, rb.perm):
+        t.fill_(-1)
+    rb.w.fill_(float("nan"))
+    rb.route_forward(ctx, 0, ld, xd, y_one, None, T)
+    sync()
+    ids, w, counts, offsets, perm = dxo.route(lg, wl.k)
+    assert np.array_equal(rb.ids.cpu().numpy()[:T], ids)
+    assert np.array_equal(rb.counts.cpu().numpy(), counts)
+    assert np.array_equal(rb.offsets.cpu().numpy(), offsets)
+    assert np.array_equal(rb.perm.cpu().numpy()[:T * wl.k], perm)
+    wg = rb.w.cpu().numpy()[:T].astype(np.float64)
+    assert np.max(np.abs(wg - w) / np.maximum(w, 1e-30)) < W_TOL or np.max(np.abs(wg - w)) < 1e-7
+    assert torch.equal(y_one, y_sep)
+    y_ref = dxo.moe_forward(ly.versions, wl.d, wl.f, wl.group, x, ids, w, shared=ly.shared,
+                            shared_f=wl.shared_f if ly.shared else 0)
+    err = rel_l2(LY.device_to_bits(y_one), y_ref)
+    print("  rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    ctx.close()
+
+
+@pytest.mark.parametrize("T,E,k,d,f,group,shared_f,resident", [
+    (16, 8, 2, 256, 128, 64, 0, [1, 6]),                 # the small configuration
+    (1, 8, 2, 256, 128, 128, 0, [0, 3]), (7, 8, 8, 256, 128, 128, 0, []), (17, 4, 2, 256, 256, 128, 0, [1]),
+    (32, 128, 8, 256, 128, 128, 0, list(range(0, 128, 3))), (32, 16, 4, 256, 128, 128, 256, [0, 5, 9]),
+    (31, 100, 16, 512, 384, 128, 0, list(range(50))), (32, 1, 1, 256, 128, 32, 0, [0]),
+    # shapes the self-routing kernel does not take: the call runs the two kernels one after the other
+    (33, 8, 2, 256, 128, 64, 0, [1]), (8, 200, 4, 256, 128, 64, 0, [7]), (150, 4, 2, 256, 128, 64, 0, [0]),
+])
+def test_route_forward_matches_oracle_and_separate_calls(B, LY, dxo, T, E, k, d, f, group, shared_f, resident):
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k, d=d, f=f, group=group, shared_f=shared_f)
+    print(f"route_forward T={T} E={E} k={k} d={d} f={f} g={group} shared_f={shared_f}", flush=True)
+    shared = W.shared_master(wl, 23, 0) if shared_f else None
+    _route_forward_case(B, LY, dxo, wl, resident, 23, shared=shared)
+
+
+def test_route_forward_with_tied_logits(B, LY, dxo):
+    """Logits on a coarse grid (many exact ties, both signs of zero): the ids must follow the tie rule."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=32, E=128, k=8, d=256, f=128, group=128)
+    g = np.random.default_rng(77)
+    logits = np.round(g.standard_normal((wl.T, wl.E)) * 2).astype(np.float32) / 2
+    logits[logits == 0] *= np.where(g.random(np.count_nonzero(logits == 0)) < 0.5, -1.0, 1.0).astype(np.float32)
+    _route_forward_case(B, LY, dxo, wl, [0, 1, 2, 64, 127], 29, logits=logits)
+
+
+def test_route_forward_c2_full_size_and_hotness(B, LY, dxo):
+    """The 30B-shaped decode layer through dx_route_forward, with the hotness update inside the call."""
+    wl = WORKLOADS["C2"]
+    masters = W.layer_masters(wl, 0, 0)
+    wg, wu, wd = masters
+    resident = list(range(0, wl.E, 4))
+    ctx = B.Context(L=2, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T, route_updates_hotness=True)
+    dev = [LY.bits_to_device(m) for m in masters]
+    lws = [LY.LayerWeights(ctx, l, *dev, resident, wl.group) for l in range(2)]
+    versions = [dxo.ExpertVersion.bf16(wg[e], wu[e], wd[e]) if e in set(resident)
+                else dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(wl.E)]
+    rb = LY.RoutingBuffers(wl.T, wl.E, wl.k)
+    c = np.zeros((2, wl.E), np.int64)
+    y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+    for step in range(3):
+        for layer in range(2):
+            x, lg = W.layer_inputs(wl, seed=0, layer=layer, step=step)
+            print(f"route_forward C2 step {step} layer {layer}", flush=True)
+            rb.route_forward(ctx, layer, torch.from_numpy(lg).cuda(), LY.bits_to_device(x), y)
+            sync()
+            ids, w, counts, offsets, perm = dxo.route(lg, wl.k)
+            dxo.hotness_update(c[layer], counts)
+            assert np.array_equal(rb.ids.cpu().numpy(), ids) and np.array_equal(rb.perm.cpu().numpy(), perm)
+            assert np.array_equal(rb.offsets.cpu().numpy(), offsets)
+            if step == 2:
+                y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w)
+                err = rel_l2(LY.device_to_bits(y), y_ref)
+                print("  rel-L2", err, flush=True)
+                assert err <= REL_L2_TOL
+    assert np.array_equal(ctx.dx_get_counters(), c)
+    del lws
+    ctx.close()
+
+
+def test_route_forward_rejects_bad_arguments(B, LY):
+    ctx = B.Context(L=1, E=8, d=64, f=64, top_k=2, group=32, max_tokens=4)
+    rb = LY.RoutingBuffers(4, 8, 2)
+    buf = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.DxError):
+        ctx.dx_route_forward(1, None, buf, buf, 4, rb.ids, rb.w, rb.counts, rb.offsets, rb.perm, buf)   # layer
+    with pytest.raises(B.DxError):
+        ctx.dx_route_forward(0, None, buf, buf, 5, rb.ids, rb.w, rb.counts, rb.offsets, rb.perm, buf)   # T > max
+    with pytest.raises(B.DxError):
+        ctx.dx_route_forward(0, None, None, buf, 4, rb.ids, rb.w, rb.counts, rb.offsets, rb.perm, buf)  # null logits
+    with pytest.raises(B.DxError):
+        ctx.dx_route_forward(0, None, buf, buf, 4, rb.ids, rb.w, rb.counts, rb.offsets, rb.perm, buf)   # no versions published
+    ctx.close()
