@@ -118,9 +118,8 @@ def run_c5(args):
                 for s_ in range(window):
                     b = step % n_batches
                     for layer in range(L):
-                        if lib.dx_route(h, layer, lgs[ep][layer][b].data_ptr(), T, p_ids, p_w, p_counts, p_off, p_perm) or \
-                           lib.dx_moe_forward(h, layer, None, xs[layer][b].data_ptr(), T, p_ids, p_w, p_off, p_perm,
-                                              y.data_ptr()):
+                        if lib.dx_route_forward(h, layer, None, lgs[ep][layer][b].data_ptr(), xs[layer][b].data_ptr(), T,
+                                                p_ids, p_w, p_counts, p_off, p_perm, y.data_ptr()):
                             raise RuntimeError(lib.dx_last_error(h).decode())
                     step += 1
                     ev[step].record(stream)
@@ -216,8 +215,8 @@ def run_sweep(args):
 
             def step_fn(i):
                 layer = i % L
-                if lib.dx_route(h, layer, lgs[layer].data_ptr(), T, p_ids, p_w, p_counts, p_off, p_perm) or \
-                   lib.dx_moe_forward(h, layer, None, xs[layer].data_ptr(), T, p_ids, p_w, p_off, p_perm, y.data_ptr()):
+                if lib.dx_route_forward(h, layer, None, lgs[layer].data_ptr(), xs[layer].data_ptr(), T,
+                                        p_ids, p_w, p_counts, p_off, p_perm, y.data_ptr()):
                     raise RuntimeError(lib.dx_last_error(h).decode())
 
             steps = 240 if T <= 256 else 48
@@ -240,7 +239,7 @@ def run_sweep(args):
         "config": {"workload": f"30B-A3B-shaped MoE layer (d={d}, f={f}, E={E}, top-{k}, Zipf(s={base.zipf_s}) routing, "
                                f"{base.n_hi} bf16 + {E - base.n_hi} int4-g{base.group} experts), T from 1 to {t_max}, "
                                f"rotating over {L} layers' weights; value and ms_per_step are the T=32 row",
-                   "step": "dx_route + dx_moe_forward of one layer"},
+                   "step": "dx_route_forward (route + forward) of one layer"},
         "sweep": rows}))
 
 

@@ -548,12 +548,7 @@ __device__ __forceinline__ void build_partition(const dx_fwd_args &a, partition_
             local += mine[i];
         }
     }
-    uint32_t inc = local;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(inc, off, 64);
-        if (lane >= off) inc += o;
-    }
+    const uint32_t inc = dx_route_core::wave_scan_inclusive(local);
     if (lane == 63) pl.wave_tot[wave] = inc;
     if (tid == 0) pl.e_first = nE;
     __syncthreads();
@@ -574,8 +569,11 @@ __device__ __forceinline__ void build_partition(const dx_fwd_args &a, partition_
         }
     }
     if (tid == 0) pl.cum[nE] = U;
-    ub0 = (uint32_t)(((unsigned long long)U * blockIdx.x) / gridDim.x);
-    ub1 = (uint32_t)(((unsigned long long)U * (blockIdx.x + 1)) / gridDim.x);
+    // this block's unit range (in double: exact for these sizes, no 64-bit integer division, and every
+    // block evaluates the same expression for a boundary it shares)
+    const double share = (double)U / (double)gridDim.x;
+    ub0 = (uint32_t)(share * (double)blockIdx.x);
+    ub1 = blockIdx.x + 1 == gridDim.x ? U : (uint32_t)(share * (double)(blockIdx.x + 1));
     __syncthreads();
     // the expert whose unit range contains ub0 (experts without work have empty ranges)
 #pragma unroll

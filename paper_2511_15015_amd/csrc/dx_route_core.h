@@ -5,6 +5,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 namespace dx_route_core {
 
 // Wave-wide max / sum in six DPP steps (no LDS round trips).  Lane 63 ends up with the reduction over
@@ -99,6 +101,22 @@ __device__ __forceinline__ int wave_scan_inclusive(int x)
     x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true); // row_shr:8
     x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false); // row_bcast:15 into rows 1 and 3
     x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false); // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_scan_inclusive(uint32_t x) // the same, modulo 2^32
+{
+    auto shifted = [](uint32_t v, auto ctrl, auto row_mask, auto bound) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, decltype(ctrl)::value, decltype(row_mask)::value, 0xF,
+                                                     decltype(bound)::value);
+    };
+    using std::integral_constant;
+    x += shifted(x, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{}, integral_constant<bool, true>{});
+    x += shifted(x, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{}, integral_constant<bool, true>{});
+    x += shifted(x, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{}, integral_constant<bool, true>{});
+    x += shifted(x, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{}, integral_constant<bool, true>{});
+    x += shifted(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{}, integral_constant<bool, false>{});
+    x += shifted(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{}, integral_constant<bool, false>{});
     return x;
 }
 
