@@ -797,20 +797,34 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
 }
 
 // ---- combine: y[t] = sum_j w[t,j] * O[t*k+j] (+ O[T*k+t] of the shared expert) ----------
+// The rows are fetched eight at a time before they are added (in the order of j), so that a thread has
+// its loads in flight together instead of one round trip per row.
 __global__ __launch_bounds__(256) void k_combine(dx_fwd_args a)
 {
     const int t = blockIdx.y;
     const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c >= a.d) return;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < a.k; ++j) {
-        const float wj = a.w[(size_t)t * a.k + j];
-        const float4 o = *reinterpret_cast<const float4 *>(a.o + ((size_t)t * a.k + j) * a.d + c);
-        acc.x += wj * o.x; acc.y += wj * o.y; acc.z += wj * o.z; acc.w += wj * o.w;
+    float4 sh = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (a.shared) sh = *reinterpret_cast<const float4 *>(a.o + ((size_t)a.T * a.k + t) * a.d + c);
+    for (int j0 = 0; j0 < a.k; j0 += 8) {
+        float4 o[8];
+        float wj[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = j0 + u < a.k ? j0 + u : a.k - 1; // past the end: a duplicate that is not added
+            wj[u] = a.w[(size_t)t * a.k + j];
+            o[u] = *reinterpret_cast<const float4 *>(a.o + ((size_t)t * a.k + j) * a.d + c);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (j0 + u < a.k) {
+                acc.x += wj[u] * o[u].x; acc.y += wj[u] * o[u].y; acc.z += wj[u] * o[u].z; acc.w += wj[u] * o[u].w;
+            }
+        }
     }
     if (a.shared) {
-        const float4 o = *reinterpret_cast<const float4 *>(a.o + ((size_t)a.T * a.k + t) * a.d + c);
-        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+        acc.x += sh.x; acc.y += sh.y; acc.z += sh.z; acc.w += sh.w;
     }
     uint2 out;
     out.x = float_to_bf16_rne(acc.x) | (float_to_bf16_rne(acc.y) << 16);
@@ -826,8 +840,7 @@ __global__ __launch_bounds__(256) void k_combine_bf16(dx_fwd_args a)
     if (c >= a.d) return;
     const dx_bf16 *ob = reinterpret_cast<const dx_bf16 *>(a.o);
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    auto add_row = [&](size_t row, float wj) {
-        const uint4 o = *reinterpret_cast<const uint4 *>(ob + row * a.d + c);
+    auto add_row = [&](const uint4 &o, float wj) {
         const uint32_t p[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -835,8 +848,22 @@ __global__ __launch_bounds__(256) void k_combine_bf16(dx_fwd_args a)
             acc[2 * i + 1] += wj * __uint_as_float(p[i] & 0xFFFF0000u);
         }
     };
-    for (int j = 0; j < a.k; ++j) add_row((size_t)t * a.k + j, a.w[(size_t)t * a.k + j]);
-    if (a.shared) add_row((size_t)a.T * a.k + t, 1.f);
+    uint4 sh = make_uint4(0u, 0u, 0u, 0u);
+    if (a.shared) sh = *reinterpret_cast<const uint4 *>(ob + ((size_t)a.T * a.k + t) * a.d + c);
+    for (int j0 = 0; j0 < a.k; j0 += 8) { // eight rows in flight, added in the order of j
+        uint4 o[8];
+        float wj[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = j0 + u < a.k ? j0 + u : a.k - 1;
+            wj[u] = a.w[(size_t)t * a.k + j];
+            o[u] = *reinterpret_cast<const uint4 *>(ob + ((size_t)t * a.k + j) * a.d + c);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (j0 + u < a.k) add_row(o[u], wj[u]);
+    }
+    if (a.shared) add_row(sh, 1.f);
     uint4 out;
     out.x = float_to_bf16_rne(acc[0]) | (float_to_bf16_rne(acc[1]) << 16);
     out.y = float_to_bf16_rne(acc[2]) | (float_to_bf16_rne(acc[3]) << 16);

@@ -128,33 +128,41 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive(uint32_t x) // the same,
 __device__ __forceinline__ void topk_rows16(float (&v)[8], int k, int lane, int &id, float &wt)
 {
     const int c = lane & 15;
-    id = 0;
-    float lg = -INFINITY;
-    for (int j = 0; j < k; ++j) {
-        float top = v[0];
+    // Order-preserving integer keys (x + 0 turns -0 into +0, so equal logits have equal keys): integer
+    // max / compare, no NaN handling in the way.  A taken entry gets the lowest key, below -inf's.
+    int key[8];
 #pragma unroll
-        for (int s = 1; s < 8; ++s) top = fmaxf(top, v[s]);
-        top = fmaxf(top, dpp_move<0xB1, 0xF, false>(top, top));  // quad_perm [1,0,3,2]
-        top = fmaxf(top, dpp_move<0x4E, 0xF, false>(top, top));  // quad_perm [2,3,0,1]
-        top = fmaxf(top, dpp_move<0x141, 0xF, false>(top, top)); // row_half_mirror
-        top = fmaxf(top, dpp_move<0x140, 0xF, false>(top, top)); // row_mirror: uniform over the row
+    for (int s = 0; s < 8; ++s) {
+        const int b = __float_as_int(v[s] + 0.f);
+        key[s] = b ^ ((b >> 31) & 0x7fffffff);
+    }
+    constexpr int kTaken = (int)0x80000000;
+    id = 0;
+    int lgk = kTaken;
+    for (int j = 0; j < k; ++j) {
+        int top = max(max(max(key[0], key[1]), max(key[2], key[3])), max(max(key[4], key[5]), max(key[6], key[7])));
+        top = max(top, __builtin_amdgcn_mov_dpp(top, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+        top = max(top, __builtin_amdgcn_mov_dpp(top, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+        top = max(top, __builtin_amdgcn_mov_dpp(top, 0x141, 0xF, 0xF, false)); // row_half_mirror
+        top = max(top, __builtin_amdgcn_mov_dpp(top, 0x140, 0xF, 0xF, false)); // row_mirror: uniform over the row
         // the lowest expert index that holds it: lowest own candidate, then the minimum over the row
         int cand = 0x7fffffff;
 #pragma unroll
         for (int s = 7; s >= 0; --s)
-            if (v[s] == top) cand = 8 * c + s;
-        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0xB1, 0xF, 0xF, false));
-        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0x4E, 0xF, 0xF, false));
-        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0x141, 0xF, 0xF, false));
-        cand = min(cand, __builtin_amdgcn_update_dpp(cand, cand, 0x140, 0xF, 0xF, false));
+            if (key[s] == top) cand = 8 * c + s;
+        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0xB1, 0xF, 0xF, false));
+        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x4E, 0xF, 0xF, false));
+        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x141, 0xF, 0xF, false));
+        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x140, 0xF, 0xF, false));
 #pragma unroll
         for (int s = 0; s < 8; ++s)
-            if (cand == 8 * c + s) v[s] = -INFINITY;
+            if (cand == 8 * c + s) key[s] = kTaken;
         if (c == j) {
             id = cand;
-            lg = top;
+            lgk = top;
         }
     }
+    const float lg = __int_as_float(lgk ^ ((lgk >> 31) & 0x7fffffff)); // back to the logit
     const float top0 = __shfl(lg, lane & 48, 64);
     const float ex = c < k ? expf(lg - top0) : 0.f;
     float x = ex;

@@ -483,11 +483,11 @@ def test_forward_c3_prefill_sampled_tokens(B, LY, dxo, T):
     ctx.close()
 
 
-@pytest.mark.parametrize("T", [32, 300])
-def test_route_and_forward_replay_from_a_captured_graph(B, LY, dxo, T):
-    """dx_route + dx_moe_forward recorded into a HIP graph (the decode pass, and the prefill pass with
-    its fork/join over the side streams), replayed several times with eager work and synchronisations
-    in between: every replay reproduces the eager result bit for bit."""
+@pytest.mark.parametrize("T,one_call", [(32, False), (300, False), (32, True)])
+def test_route_and_forward_replay_from_a_captured_graph(B, LY, dxo, T, one_call):
+    """dx_route + dx_moe_forward (or the two as one dx_route_forward call) recorded into a HIP graph (the
+    decode pass, and the prefill pass with its fork/join over the side streams), replayed several times
+    with eager work and synchronisations in between: every replay reproduces the eager result bit for bit."""
     import dataclasses
     wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=4 if T > 64 else 8)
     x, logits = W.layer_inputs(wl, seed=9)
@@ -506,8 +506,11 @@ def test_route_and_forward_replay_from_a_captured_graph(B, LY, dxo, T):
         assert rel_l2(LY.device_to_bits(eager), y_ref) <= REL_L2_TOL
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=stream):
-            rb.route(ctx, 0, ld, T)
-            rb.forward(ctx, 0, xd, y, None, T)
+            if one_call:
+                rb.route_forward(ctx, 0, ld, xd, y, None, T)
+            else:
+                rb.route(ctx, 0, ld, T)
+                rb.forward(ctx, 0, xd, y, None, T)
         for rep in range(4):
             y.zero_()                                  # eager work between the replays
             rb.perm.zero_()
