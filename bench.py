@@ -33,8 +33,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C5"],
+    ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C4", "C5"],
                     help="C2: decode T=32 (the headline metric); C3: the same layer in prefill, T=4096; "
+                         "C4: decode T=32 on the 512-expert, top-10 layer shape with a shared expert; "
                          "C5: a decode stack whose hot set drifts, with live promotions and demotions")
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets to rotate over")
     ap.add_argument("--window", type=int, default=None, help="routing-only warm-up steps per layer for hotness")
@@ -252,6 +253,7 @@ def main():
         return run_sweep(args)
     defaults = {"C2": dict(steps=960, warmup=96, layers=48, window=64),
                 "C3": dict(steps=48, warmup=8, layers=4, window=2),
+                "C4": dict(steps=480, warmup=48, layers=16, window=16),
                 "C5": dict(steps=384, warmup=0, layers=8, window=32)}[args.workload]
     for key, val in defaults.items():
         if getattr(args, key) is None:
@@ -281,11 +283,12 @@ def main():
     b_hi = B.dx_expert_bytes(d, f, wl.group, hi_fmt)
     b_lo = B.dx_expert_bytes(d, f, wl.group, hi_fmt + 1)
     layer_budget = wl.n_hi * b_hi + (E - wl.n_hi) * b_lo       # 535560192 B for the bf16 / int4 pair
+    b_sh = B.dx_expert_bytes(d, wl.shared_f, wl.group, B.DX_FMT_BF16) if wl.shared_f else 0
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         ctx = B.Context(L=L, E=E, d=d, f=f, top_k=k, group=wl.group, max_tokens=T,
-                        window_steps=args.window, budget_bytes=L * layer_budget,
+                        window_steps=args.window, budget_bytes=L * (layer_budget + b_sh), shared_f=wl.shared_f,
                         route_updates_hotness=True, stream=stream.cuda_stream, hi_fmt=hi_fmt)
         rb = LY.RoutingBuffers(T, E, k)
         # inputs of every layer: the measured batch plus the warm-up window's router traces
@@ -304,8 +307,14 @@ def main():
         resident = [ctx.dx_select_resident(layer, layer_budget) for layer in range(L)]
         assert all(len(r) == wl.n_hi for r in resident), [len(r) for r in resident]
         # weights: draw each layer's masters on the device, keep bf16 for the resident set, int4 for the rest
-        layers = []
+        layers, shared = [], []
         for layer in range(L):
+            if wl.shared_f:   # the always-resident bf16 shared expert of the layer
+                g = torch.Generator(device="cuda")
+                g.manual_seed(1000 + layer)
+                shared.append([(0.02 * torch.randn(s, generator=g, device="cuda")).to(torch.bfloat16)
+                               for s in ((wl.shared_f, d), (wl.shared_f, d), (d, wl.shared_f))])
+                ctx.dx_swap_handle(layer, E, B.make_handle(B.DX_FMT_BF16, *shared[layer]))
             wg, wu, wd = W.device_masters(wl, seed, layer)
             if quant_pair:
                 layers.append(LY.QuantPairLayerWeights(ctx, layer, wg, wu, wd, resident[layer], wl.group))
@@ -355,7 +364,8 @@ def main():
                 act = counts > 0
                 hi = layers[i % L].is_hi
                 # decode: activated experts' gate+up bytes in their stored format + the token rows
-                alg_bytes += float((act & hi).sum() * (2 * b_hi // 3) + (act & ~hi).sum() * (2 * b_lo // 3) + T * d * 2)
+                alg_bytes += float((act & hi).sum() * (2 * b_hi // 3) + (act & ~hi).sum() * (2 * b_lo // 3) + T * d * 2
+                                   + 2 * b_sh // 3)
                 # prefill: the 256-row tile kernel multiplies the leading multiple of 256 rows of every bf16
                 # segment: 2 * rows * d * 2f each
                 # (no bf16 experts in the int4 / int2 pair: there the 128-row tile kernel takes every segment above 32)
@@ -368,10 +378,12 @@ def main():
         flops_per_launch = alg_flops / n_alg
         gate_up_us = prof["gate_up_ms"] * 1e3 / prof["calls"]
 
-    decode = args.workload == "C2"
+    decode = args.workload in ("C2", "C4")
+    shape_name = {"C2": "30B-A3B", "C3": "30B-A3B", "C4": "80B-A3B"}[args.workload]
     if decode:
         achieved = alg_per_launch / (gate_up_us * 1e-6) / 1e9
-        roofline = {"bound": "hbm", "kernel": "k_stream<gate/up>" if separate else "k_stream_routed (routing prologue + gate/up)",
+        routed = not separate and T <= 32 and E <= 128 and k <= 16    # what dx_route_forward does with these shapes
+        roofline = {"bound": "hbm", "kernel": "k_stream_routed (routing prologue + gate/up)" if routed else "k_stream<gate/up>",
                     "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                     "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us}
@@ -387,7 +399,7 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "k_stream_gate_up_C2_decode_pmc.txt" if decode
                          else "k_big_gate_up_C3_prefill_pmc.txt")
-    if os.path.exists(tpath) and not quant_pair:
+    if os.path.exists(tpath) and not quant_pair and args.workload != "C4":
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
@@ -407,12 +419,15 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{wl.name}: 30B-A3B-shaped MoE layer, {'decode' if decode else 'prefill'} T={T}, d={d}, f={f}, E={E}, top-{k}, "
+        "config": {"workload": f"{wl.name}: {shape_name}-shaped MoE layer, {'decode' if decode else 'prefill'} T={T}, d={d}, f={f}, E={E}, top-{k}, "
+                               + (f"one bf16 shared expert (f={wl.shared_f}), " if wl.shared_f else "") +
                                f"Zipf(s={wl.zipf_s}) routing, {wl.n_hi} {'int4' if quant_pair else 'bf16'} + {E - wl.n_hi} "
                                f"{'int2' if quant_pair else 'int4'}-g{wl.group} experts "
                                f"per layer, rotating over {L} layers' weights",
                    "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"
-                           + (" as two calls" if separate else ", as one dx_route_forward call")},
+                           + (" as two calls" if separate else ", as one dx_route_forward call")
+                           + ("" if separate or (T <= 32 and E <= 128 and k <= 16) else
+                              " (these shapes run the routing kernel and the forward kernels one after the other)")},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
                       "combine": prof["combine_ms"] * 1e3 / prof["calls"],
                       "empty_event_pair": prof["empty_ms"] * 1e3 / prof["calls"]},
@@ -425,6 +440,7 @@ def main():
         from oracle import dxo
         wg, wu, wd = (LY.device_to_bits(m) for m in W.device_masters(wl, seed, 0))
         res0 = set(int(e) for e in resident[0])
+        sh0 = dxo.ExpertVersion.bf16(*(LY.device_to_bits(t) for t in shared[0])) if wl.shared_f else None
         if quant_pair:
             versions = [dxo.ExpertVersion.int4_from_master(wg[e], wu[e], wd[e], wl.group) if e in res0
                         else dxo.ExpertVersion.int2_from_master(wg[e], wu[e], wd[e], wl.group) for e in range(E)]
@@ -438,7 +454,7 @@ def main():
             while calls < len(batches) and time.perf_counter() - t0 < 10.0:
                 xb, lgb = batches[calls]
                 ids, w, counts, offsets, perm = dxo.route(lgb, k)
-                y_ref = dxo.moe_forward(versions, d, f, wl.group, xb, ids, w)
+                y_ref = dxo.moe_forward(versions, d, f, wl.group, xb, ids, w, shared=sh0, shared_f=wl.shared_f)
                 if calls == 0:
                     y_ref0, ids0 = y_ref, ids
                 calls += 1
@@ -452,7 +468,8 @@ def main():
             tokens0 = np.arange(0, T, 2, dtype=np.int32)                 # every second token of the batch
             t0 = time.perf_counter()
             ids0, w, counts, offsets, perm = dxo.route(lgb, k)
-            y_ref0 = dxo.moe_forward(versions, d, f, wl.group, xb, ids0, w, tokens=tokens0)
+            y_ref0 = dxo.moe_forward(versions, d, f, wl.group, xb, ids0, w, tokens=tokens0, shared=sh0,
+                                     shared_f=wl.shared_f)
             dt = time.perf_counter() - t0
             out["cpu_baseline"] = {"value": len(tokens0) / dt, "unit": "tokens/s", "cores": dxo.threads(), "kind": "oracle",
                                    "sample": f"routing of all {T} tokens + the layer output of {len(tokens0)} evenly "
