@@ -45,7 +45,7 @@ __device__ int block_exclusive_scan(int v, int *lds_wave_tot /*[kWaves]*/, int *
     return base + inc - v;
 }
 
-// One chunk of 64 tokens per block.  NV = logits held per lane (E <= 64*NV).
+// One chunk of 64 tokens per block.  NV = consecutive logits held per lane (E <= 64*NV).
 template <int NV>
 __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
     const float *__restrict__ logits, int T, int E, int k, int32_t *__restrict__ ids, float *__restrict__ w,
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
         float v[1][NV];
 #pragma unroll
         for (int s = 0; s < NV; ++s) {
-            const int e = lane + 64 * s;
+            const int e = NV * lane + s;
             v[0][s] = e < E ? row[e] : -INFINITY;
         }
         int id1[1];

@@ -42,10 +42,12 @@ __device__ __forceinline__ float wave_sum(float x)
 }
 
 // Top-k ids and routing weights of NT token rows by one wavefront.  v[i][s] is the logit of expert
-// lane + 64*s of row i (-inf past the last expert); it is consumed.  On return lane j < k holds the
+// NV*lane + s of row i (-inf past the last expert); it is consumed.  On return lane j < k holds the
 // j-th id of row i (descending logit, ties to the lower index) in id[i] and its weight, the softmax over
-// the k selected logits, in wt[i].  The NT rows advance together, one selection per round, so that their
-// dependency chains overlap.
+// the k selected logits, in wt[i].
+// One selection: every lane finds its own largest entry (the lowest slot among equals), the wave maximum
+// of those is the winner's logit, the lowest lane that holds it is the winner (experts ascend with the
+// lane and the slot, so this is the lowest index), and that lane retires the entry.
 template <int NV, int NT>
 __device__ __forceinline__ void topk_rows(float (&v)[NT][NV], int k, int lane, int (&id)[NT], float (&wt)[NT])
 {
@@ -58,27 +60,23 @@ __device__ __forceinline__ void topk_rows(float (&v)[NT][NV], int k, int lane, i
     for (int j = 0; j < k; ++j) {
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            float bv = v[i][0];
+            float best = v[i][0];
+            int slot = 0;
 #pragma unroll
-            for (int s = 1; s < NV; ++s) bv = fmaxf(bv, v[i][s]);
-            const float top = wave_max(bv);
-            // the lowest expert index holding `top`: element e = lane + 64*s, so scan s upward and take
-            // the lowest lane of the first non-empty ballot (taken entries are -inf and never match)
-            int idx = 0;
-            bool found = false;
-#pragma unroll
-            for (int s = 0; s < NV; ++s) {
-                const unsigned long long bal = __ballot(v[i][s] == top);
-                if (!found && bal) {
-                    idx = 64 * s + __builtin_ctzll(bal);
-                    found = true;
+            for (int s = 1; s < NV; ++s)
+                if (v[i][s] > best) {
+                    best = v[i][s];
+                    slot = s;
                 }
-            }
+            const float top = wave_max(best);
+            const unsigned long long holders = __ballot(best == top); // never empty: top is some lane's best
+            const int win = __builtin_ctzll(holders);
+            const int wslot = __builtin_amdgcn_readlane(slot, win);
 #pragma unroll
             for (int s = 0; s < NV; ++s)
-                if (idx == lane + 64 * s) v[i][s] = -INFINITY;
+                if (lane == win && s == wslot) v[i][s] = -INFINITY;
             if (lane == j) {
-                id[i] = idx;
+                id[i] = NV * win + wslot;
                 lg[i] = top;
             }
         }
