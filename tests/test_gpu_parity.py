@@ -399,7 +399,9 @@ def test_route_can_update_hotness_itself(B, LY, dxo):
                                             (129, 2, 2, [0]), (400, 4, 1, []),
                                             # bf16 segments of 256 rows and more: 256 x 256 tiles plus a remainder
                                             (700, 4, 2, [0, 2]), (1100, 2, 2, [0, 1]), (512, 2, 2, [1]),
-                                            (256, 1, 1, [0])])
+                                            (256, 1, 1, [0]),
+                                            # one bf16 expert with 200, 385 = 256 + 129, 384 = 256 + 128 rows; two with 641
+                                            (200, 1, 1, [0]), (385, 1, 1, [0]), (384, 1, 1, [0]), (641, 2, 2, [0, 1])])
 def test_forward_prefill_tiles_small_shapes(B, LY, dxo, T, E, k, resident):
     """Up to 128 tokens per call the streaming kernels walk each segment in blocks of 32 tokens; above,
     segments of more than 32 tokens take the tiled MFMA kernels (bf16 and int4), the others the
