@@ -266,9 +266,11 @@ dx_status dx_get_stats(dx_ctx *ctx, dx_stats *out);
 
 /* Per-kernel timing of dx_moe_forward with HIP events on the compute stream
  * (measurement aid, off by default).  While enabled, every forward call
- * records events around its kernels; dx_get_profile synchronises the compute
- * stream, adds the elapsed times of all calls since the last read and clears
- * them. */
+ * (dx_moe_forward, dx_route_forward) times its kernels: decode batches attach
+ * events to each kernel's own dispatch (start and stop stamps of the launch),
+ * larger batches record events around the concurrent kernel chains.
+ * dx_get_profile synchronises the compute stream, adds the elapsed times of all
+ * calls since the last read and clears them. */
 typedef struct {
     uint64_t calls;     /* forward calls accumulated */
     double gate_up_ms;  /* summed duration of the gate/up + SwiGLU kernel */

@@ -326,7 +326,7 @@ extern "C" void dx_destroy(dx_ctx *c)
     for (auto ev : c->event_pool) (void)hipEventDestroy(ev);
     for (auto ev : c->timing_pool) (void)hipEventDestroy(ev);
     for (auto &m : c->marks)
-        for (auto ev : m) (void)hipEventDestroy(ev);
+        for (auto ev : m.ev) (void)hipEventDestroy(ev);
     for (dx_block_pool *p : {&c->pool_hi, &c->pool_lo}) {
         for (auto ev : p->reuse_after)
             if (ev) (void)hipEventDestroy(ev);
@@ -403,17 +403,18 @@ dx_status forward_args(dx_ctx *c, const char *who, int layer, const dx_handle *t
     return DX_OK;
 }
 
-// five timing events for a profiled call (from the pool, or new)
-dx_status take_marks(dx_ctx *c, std::array<hipEvent_t, 5> &m)
+// the timing events of a profiled call (from the pool, or new)
+dx_status take_marks(dx_ctx *c, dx_marks &m)
 {
-    for (int i = 0; i < 5; ++i) {
+    m.per_kernel = false;
+    for (int i = 0; i < 8; ++i) {
         if (!c->timing_pool.empty()) {
-            m[i] = c->timing_pool.back();
+            m.ev[i] = c->timing_pool.back();
             c->timing_pool.pop_back();
         } else {
-            hipError_t e = hipEventCreate(&m[i]);
+            hipError_t e = hipEventCreate(&m.ev[i]);
             if (e != hipSuccess) {
-                for (int j = 0; j < i; ++j) c->timing_pool.push_back(m[j]);
+                for (int j = 0; j < i; ++j) c->timing_pool.push_back(m.ev[j]);
                 DX_FAIL(c, DX_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
             }
         }
@@ -440,9 +441,9 @@ extern "C" dx_status dx_moe_forward(dx_ctx *c, int layer, const dx_handle *table
         DX_HIP(c, dxk_moe_forward(a, c->n_cu, c->compute, &side, nullptr));
         return DX_OK;
     }
-    std::array<hipEvent_t, 5> m;
+    dx_marks m;
     if ((st = take_marks(c, m)) != DX_OK) return st;
-    hipError_t e = dxk_moe_forward(a, c->n_cu, c->compute, &side, m.data());
+    hipError_t e = dxk_moe_forward(a, c->n_cu, c->compute, &side, &m);
     c->marks.push_back(m);
     if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_moe_forward: %s", hipGetErrorString(e));
     return DX_OK;
@@ -471,12 +472,12 @@ extern "C" dx_status dx_route_forward(dx_ctx *c, int layer, const dx_handle *tab
         r.offsets = offsets;
         r.perm = perm;
         r.hotness = c->cfg.route_updates_hotness ? c->d_counters + (size_t)layer * c->cfg.E : nullptr;
-        std::array<hipEvent_t, 5> m;
+        dx_marks m;
         if (c->profiling && (st = take_marks(c, m)) != DX_OK) return st;
-        hipError_t e = dxk_route_forward(a, r, c->n_cu, c->compute, c->profiling ? m.data() : nullptr, &routed);
+        hipError_t e = dxk_route_forward(a, r, c->n_cu, c->compute, c->profiling ? &m : nullptr, &routed);
         if (c->profiling) {
             if (routed) c->marks.push_back(m);
-            else for (auto ev : m) c->timing_pool.push_back(ev);
+            else for (auto ev : m.ev) c->timing_pool.push_back(ev);
         }
         if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_route_forward: %s", hipGetErrorString(e));
     }
@@ -726,9 +727,12 @@ extern "C" dx_status dx_get_profile(dx_ctx *c, dx_profile *out)
     *out = dx_profile{};
     DX_HIP(c, hipStreamSynchronize(c->compute));
     for (auto &m : c->marks) {
+        // (start, stop) of gate/up, down, combine and of the empty pair
+        const int from[4] = {0, m.per_kernel ? 5 : 1, m.per_kernel ? 6 : 2, 7};
+        const int to[4] = {1, 2, 3, 4};
         float t[4] = {0.f, 0.f, 0.f, 0.f};
         for (int i = 0; i < 4; ++i) {
-            hipError_t e = hipEventElapsedTime(&t[i], m[i], m[i + 1]);
+            hipError_t e = hipEventElapsedTime(&t[i], m.ev[from[i]], m.ev[to[i]]);
             if (e != hipSuccess) t[i] = 0.f; // a call that recorded nothing (T == 0)
         }
         out->calls++;
@@ -736,7 +740,7 @@ extern "C" dx_status dx_get_profile(dx_ctx *c, dx_profile *out)
         out->down_ms += t[1];
         out->combine_ms += t[2];
         out->empty_ms += t[3];
-        for (auto ev : m) c->timing_pool.push_back(ev);
+        for (auto ev : m.ev) c->timing_pool.push_back(ev);
     }
     c->marks.clear();
     return DX_OK;

@@ -46,6 +46,16 @@ struct dx_transition {
     hipEvent_t done;
 };
 
+// Timing events of one profiled forward call.  ev[0..3]: before gate/up, after it, after down, after
+// combine; ev[7], ev[4]: two records back to back (what an event pair itself adds).  Decode batches set
+// per_kernel: there ev[0]/ev[1], ev[5]/ev[2] and ev[6]/ev[3] are the start and stop stamps of the three
+// kernels' own dispatches (attached to the launches), not records between them.  Prefill: records around
+// the chain on the caller's stream.
+struct dx_marks {
+    hipEvent_t ev[8];
+    bool per_kernel;
+};
+
 struct dx_ctx {
     dx_config cfg{};
     int device = 0;
@@ -95,7 +105,7 @@ struct dx_ctx {
     // optional per-kernel timing of the forward pass
     bool profiling = false;
     std::vector<hipEvent_t> timing_pool;           // free timing-enabled events
-    std::vector<std::array<hipEvent_t, 5>> marks;  // one tuple per profiled forward call
+    std::vector<dx_marks> marks;                   // one per profiled forward call
 };
 
 #define DX_FAIL(ctx, code, ...)                                   \
@@ -165,13 +175,11 @@ struct dx_fwd_streams {
     hipStream_t aux[2];
     hipEvent_t fork, join[2];
 };
-// marks: null, or 5 events recorded before gate/up, after it, after down, after combine (prefill: around
-// the chain on the caller's stream), and once more right away (an empty bracket)
-hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks);
+hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, dx_marks *marks);
 // Routing and forward pass in one call.  Returns true in *routed when the gate/up kernel did the routing
 // (small decode batches whose shapes fit); otherwise nothing was launched and the caller runs dxk_route
 // and dxk_moe_forward.
-hipError_t dxk_route_forward(const dx_fwd_args &a, const dx_route_io &r, int n_cu, hipStream_t s, hipEvent_t *marks,
+hipError_t dxk_route_forward(const dx_fwd_args &a, const dx_route_io &r, int n_cu, hipStream_t s, dx_marks *marks,
                              bool *routed);
 // dx_moe_prefill.hip: gate/up then down for the experts above a.m_small tokens.  The 256-row tile
 // kernels (when a.m_big) go to s_big, the 128-row ones to s_tiled (the two may be the same stream).

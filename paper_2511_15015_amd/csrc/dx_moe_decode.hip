@@ -40,6 +40,8 @@
 #include "dx_internal.h"
 #include "dx_route_core.h"
 
+#include <hip/hip_ext.h>
+
 #include <cmath>
 
 namespace {
@@ -901,15 +903,25 @@ split_choice pick_split(int nc_a, int nc_b)
     return {2, false};
 }
 
+// A launch, optionally with events that take the start and stop time stamps of the kernel's own dispatch
+// (HIP's extended launch): the duration they give is the kernel's, with no event packets inside it.
+template <typename... Args>
+void launch(void (*kernel)(Args...), dim3 grid, dim3 block, hipStream_t s, hipEvent_t start, hipEvent_t stop, Args... args)
+{
+    if (start || stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, start, stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+}
+
 template <int LK, bool DOWN>
-void launch_stream(const dx_fwd_args &a, split_choice c, dim3 grid, hipStream_t s)
+void launch_stream(const dx_fwd_args &a, split_choice c, dim3 grid, hipStream_t s, hipEvent_t start = nullptr,
+                   hipEvent_t stop = nullptr)
 {
     const dim3 block(kThreads);
     if (c.fast) {
-        if (c.cpw == 2) hipLaunchKernelGGL((k_stream<LK, 2, DOWN, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_stream<LK, 1, DOWN, true>), grid, block, 0, s, a);
+        if (c.cpw == 2) launch(k_stream<LK, 2, DOWN, true>, grid, block, s, start, stop, a);
+        else launch(k_stream<LK, 1, DOWN, true>, grid, block, s, start, stop, a);
     } else {
-        hipLaunchKernelGGL((k_stream<LK, 2, DOWN, false>), grid, block, 0, s, a);
+        launch(k_stream<LK, 2, DOWN, false>, grid, block, s, start, stop, a);
     }
 }
 
@@ -920,7 +932,7 @@ constexpr int kStreamOnlyTokens = 128;
 // r: null, or the routing inputs and outputs of a call that asks the gate/up kernel to route; *routed
 // then tells whether it did (if not, nothing has been launched).
 template <int LK>
-hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks,
+hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx_fwd_streams *side, dx_marks *mk,
                       const dx_route_io *r, bool *routed)
 {
     constexpr int CHUNK = 4 * LK;
@@ -942,18 +954,24 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
         *routed = !mixed && gu.fast && a.T >= 1 && a.T <= kRoutedTokens && a.E <= kRoutedExperts && a.k <= kRoutedTopK;
         if (!*routed) return hipSuccess;
     }
+    hipEvent_t *marks = mk ? mk->ev : nullptr;
+    hipEvent_t combine_start = nullptr, combine_stop = nullptr;
+    if (mk) mk->per_kernel = !mixed;
     if (!mixed) {
+        // profiled: every kernel's own start and stop stamps
         const dim3 grid(n_cu);
-        if (marks) (void)hipEventRecord(marks[0], s);
+        hipEvent_t ev[8] = {};
+        if (marks)
+            for (int i = 0; i < 8; ++i) ev[i] = marks[i];
         if (r) {
-            if (gu.cpw == 2) hipLaunchKernelGGL((k_stream_routed<LK, 2>), grid, dim3(kThreads), 0, s, a, *r);
-            else hipLaunchKernelGGL((k_stream_routed<LK, 1>), grid, dim3(kThreads), 0, s, a, *r);
+            if (gu.cpw == 2) launch(k_stream_routed<LK, 2>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
+            else launch(k_stream_routed<LK, 1>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
         } else {
-            launch_stream<LK, false>(a, gu, grid, s);
+            launch_stream<LK, false>(a, gu, grid, s, ev[0], ev[1]);
         }
-        if (marks) (void)hipEventRecord(marks[1], s);
-        launch_stream<LK, true>(a, dn, grid, s);
-        if (marks) (void)hipEventRecord(marks[2], s);
+        launch_stream<LK, true>(a, dn, grid, s, ev[5], ev[2]);
+        combine_start = ev[6];
+        combine_stop = ev[3];
     } else if (!side) {
         const dim3 grid(n_cu);
         launch_stream<LK, false>(a, gu, grid, s);
@@ -986,13 +1004,14 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
         }
     }
     if (a.o_bf16) {
-        hipLaunchKernelGGL(k_combine_bf16, dim3((a.d / 8 + 255) / 256, a.T), dim3(256), 0, s, a);
+        launch(k_combine_bf16, dim3((a.d / 8 + 255) / 256, a.T), dim3(256), s, combine_start, combine_stop, a);
     } else {
-        hipLaunchKernelGGL(k_combine, dim3((a.d / 4 + 255) / 256, a.T), dim3(256), 0, s, a);
+        launch(k_combine, dim3((a.d / 4 + 255) / 256, a.T), dim3(256), s, combine_start, combine_stop, a);
     }
     if (marks) {
-        (void)hipEventRecord(marks[3], s);
-        (void)hipEventRecord(marks[4], s); // an empty bracket: the cost of the event pair itself
+        if (!combine_stop) (void)hipEventRecord(marks[3], s);
+        (void)hipEventRecord(marks[7], s); // two records back to back: the cost of an event pair itself
+        (void)hipEventRecord(marks[4], s);
     }
     return hipGetLastError();
 }
@@ -1006,7 +1025,7 @@ extern "C" int dx_debug_read_trace(void *dst, size_t bytes)
 }
 #endif
 
-hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, hipEvent_t *marks)
+hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const dx_fwd_streams *side, dx_marks *marks)
 {
     if (a.T == 0) return hipSuccess;
     // K-chunk = min(group, 128) so that a chunk never crosses a quantization group
@@ -1015,7 +1034,7 @@ hipError_t dxk_moe_forward(const dx_fwd_args &a, int n_cu, hipStream_t s, const 
     return launch_all<8>(a, n_cu, s, side, marks, nullptr, nullptr);
 }
 
-hipError_t dxk_route_forward(const dx_fwd_args &a, const dx_route_io &r, int n_cu, hipStream_t s, hipEvent_t *marks,
+hipError_t dxk_route_forward(const dx_fwd_args &a, const dx_route_io &r, int n_cu, hipStream_t s, dx_marks *marks,
                              bool *routed)
 {
     *routed = false;
