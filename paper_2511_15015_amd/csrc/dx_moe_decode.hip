@@ -83,12 +83,20 @@ __device__ __forceinline__ uint32_t float_to_bf16_rne(float f)
 // bias is removed through  sum_k a_k (136 + q_k) - 136 sum_k a_k.
 constexpr float kNibbleBias = 136.f;
 
+// The flip, the mask and the OR are one v_bitop3_b32 per register (x is the shifted word): with two
+// constant words p and q the result bit is 0, 1, the bit of x or its complement for (p, q) = (0, 0),
+// (0, 1), (1, 0), (1, 1) -- truth table 0x6A over (x, p, q).
+__device__ __forceinline__ uint32_t keep_flip_set(uint32_t x, uint32_t p, uint32_t q)
+{
+    return __builtin_amdgcn_bitop3_b32(x, p, q, 0x6A);
+}
+
 __device__ __forceinline__ bf16x8 nibbles_to_biased_bf16(uint32_t word)
 {
-    const uint32_t u = word ^ 0x88888888u;
+    constexpr uint32_t p = 0x000F000Fu, q = (0x88888888u & p) | 0x43004300u; // ((x ^ 0x8888...) & p) | 0x4300...
     frag8 out;
-    out.u = u32x4{(u & 0x000F000Fu) | 0x43004300u, ((u >> 4) & 0x000F000Fu) | 0x43004300u,
-                  ((u >> 8) & 0x000F000Fu) | 0x43004300u, ((u >> 12) & 0x000F000Fu) | 0x43004300u};
+    out.u = u32x4{keep_flip_set(word, p, q), keep_flip_set(word >> 4, p, q), keep_flip_set(word >> 8, p, q),
+                  keep_flip_set(word >> 12, p, q)};
     return out.v;
 }
 
@@ -101,10 +109,10 @@ constexpr float kCrumbBias = 130.f;
 template <int HALF>
 __device__ __forceinline__ bf16x8 crumbs_to_biased_bf16(uint32_t word)
 {
-    const uint32_t u = (word ^ 0xAAAAAAAAu) >> (8 * HALF);
+    constexpr uint32_t p = 0x00030003u, q = (0xAAAAAAAAu & p) | 0x43004300u;
     frag8 out;
-    out.u = u32x4{(u & 0x00030003u) | 0x43004300u, ((u >> 2) & 0x00030003u) | 0x43004300u,
-                  ((u >> 4) & 0x00030003u) | 0x43004300u, ((u >> 6) & 0x00030003u) | 0x43004300u};
+    out.u = u32x4{keep_flip_set(word >> (8 * HALF), p, q), keep_flip_set(word >> (8 * HALF + 2), p, q),
+                  keep_flip_set(word >> (8 * HALF + 4), p, q), keep_flip_set(word >> (8 * HALF + 6), p, q)};
     return out.v;
 }
 
@@ -171,12 +179,10 @@ struct wstage {
     static constexpr int NQ = FMT == 1 ? JN : (FMT == 2 ? (JN + 1) / 2 : 1);
     u32x4 w[CPW][FMT ? 1 : JN]; // bf16: JN 16-byte pieces per chunk
     uint32_t wq[CPW][NQ];       // int4: JN words of 8 nibbles; int2: JN/2 words of 16 codes
-    uint32_t sc[CPW];           // int4, int2: bf16 bits of the chunk's group scale
 };
 
 template <int LK, int CPW, int FMT>
-__device__ __forceinline__ void issue_weights(wstage<LK, CPW, FMT> &st, gbytes row, gbf16 srow, int c0, int nc, int q,
-                                              int group)
+__device__ __forceinline__ void issue_weights(wstage<LK, CPW, FMT> &st, gbytes row, int c0, int nc, int q)
 {
     constexpr int CHUNK = 4 * LK, JN = LK / 8;
 #pragma unroll
@@ -193,7 +199,6 @@ __device__ __forceinline__ void issue_weights(wstage<LK, CPW, FMT> &st, gbytes r
                 } else { // 8 codes = 2 bytes (handles of this format are refused for group 32; kept in bounds)
                     st.wq[i][0] = *reinterpret_cast<const DX_GLOBAL uint16_t *>(p);
                 }
-                st.sc[i] = srow[(c * CHUNK) / group];
             } else if constexpr (FMT == 1) {
                 gbytes p = row + ((c * CHUNK + q * LK) >> 1);
                 if constexpr (LK == 32) {
@@ -205,7 +210,6 @@ __device__ __forceinline__ void issue_weights(wstage<LK, CPW, FMT> &st, gbytes r
                 } else {
                     st.wq[i][0] = *reinterpret_cast<gvec4>(p);
                 }
-                st.sc[i] = srow[(c * CHUNK) / group];
             } else {
 #pragma unroll
                 for (int j = 0; j < JN; ++j)
@@ -267,7 +271,7 @@ __device__ __forceinline__ void prepare_quant_tokens(u32x4 (&x)[CPW][MT][LK / 8]
 
 template <int LK, int CPW, int FMT, int MT>
 __device__ __forceinline__ void multiply(const wstage<LK, CPW, FMT> &st, const u32x4 (&x)[CPW][MT][LK / 8],
-                                         const f32x4 (&bias)[CPW][MT], int c0, int nc, f32x4 (&acc)[MT])
+                                         const f32x4 (&bias)[CPW][MT], uint32_t scales, int c0, int nc, f32x4 (&acc)[MT])
 {
     constexpr int JN = LK / 8;
 #pragma unroll
@@ -289,7 +293,8 @@ __device__ __forceinline__ void multiply(const wstage<LK, CPW, FMT> &st, const u
                         part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, wv, part[mt], 0, 0, 0);
                     }
                 }
-                const float scale = bf16_bits_to_float(st.sc[i]);
+                // (the bf16 scales of the wavefront's chunks, two to a word: chunk 0 in the low half)
+                const float scale = __uint_as_float(i == 0 ? scales << 16 : scales & 0xFFFF0000u);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) acc[mt] += (part[mt] - bias[i][mt]) * scale;
             } else {
@@ -428,14 +433,51 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     constexpr int NST = FMT ? 6 : 2;
     const int nhalf = 2 * nsteps;
     wstage<LK, CPW, FMT> st[NST];
+    const gbytes weight_rows0 = ex.w0, weight_rows1 = ex.w1;
     auto issue_step = [&](int t, wstage<LK, CPW, FMT> &dst) {
         const int b = t & 1, sr = t >> 1;
         int s = s_lo + (sr / rounds) * SPP + g;
         s = s < s_hi ? s : s_hi - 1; // ragged tail: fetch a duplicate rather than branch
         const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
-        const gbytes p = (b ? ex.w1 : ex.w0) + (size_t)n * ex.row_bytes;
-        const gbf16 sp = FMT ? (b ? ex.s1 : ex.s0) + (size_t)n * ex.G : nullptr;
-        issue_weights<LK, CPW, FMT>(dst, p, sp, ((sr % rounds) * WPS + kw) * CPW, ncp, q, a.group);
+        const gbytes p = (b ? weight_rows1 : weight_rows0) + (size_t)n * ex.row_bytes;
+        issue_weights<LK, CPW, FMT>(dst, p, ((sr % rounds) * WPS + kw) * CPW, ncp, q);
+    };
+    // Quantized formats: the group scales of the steps [t0, t0 + NST), one per chunk (a chunk never crosses a
+    // group).  They travel apart from the weight stages, a whole loop iteration ahead and issued before that
+    // iteration's weight loads: the registers they land in are carried around the loop, which costs a copy
+    // at the end of every iteration, and the completion counter is in order -- a copy of a load issued
+    // last would wait for every load in flight, a copy of the oldest ones waits for nothing.
+    static_assert(CPW <= 2, "two chunk scales to a word");
+    uint32_t sc_cur[NST], sc_next[NST];
+    const gbf16 scale_rows0 = ex.s0, scale_rows1 = ex.s1;
+    auto issue_scales = [&](int t0 /* even */, uint32_t (&dst)[NST]) __attribute__((always_inline)) {
+        if constexpr (FMT != 0) {
+#pragma unroll
+            for (int u = 0; u < NST; ++u) {
+                const int b = u & 1, sr = (t0 >> 1) + (u >> 1); // step t0 + u
+                int s = s_lo + (sr / rounds) * SPP + g;
+                s = s < s_hi ? s : s_hi - 1;
+                const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
+                const gbf16 sp = (b ? scale_rows1 : scale_rows0) + (size_t)n * ex.G;
+                const int c0 = ((sr % rounds) * WPS + kw) * CPW;
+                if (CPW == 2 && a.group == CHUNK && c0 + 1 < ncp) {
+                    // the two chunks' scales are neighbours (c0 is even, a scale row starts 4-byte aligned)
+                    dst[u] = *reinterpret_cast<gvec4>(sp + c0);
+                } else {
+                    uint32_t v = 0;
+#pragma unroll
+                    for (int i = 0; i < CPW; ++i)
+                        if (c0 + i < ncp) v |= (uint32_t)sp[((c0 + i) * CHUNK) / a.group] << (16 * i);
+                    dst[u] = v;
+                }
+            }
+        }
+    };
+    auto rotate_scales = [&]() {
+        if constexpr (FMT != 0) {
+#pragma unroll
+            for (int u = 0; u < NST; ++u) sc_cur[u] = sc_next[u];
+        }
     };
 
     f32x4 acc[2][MT];
@@ -444,12 +486,13 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[b][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto do_step = [&](int t, const wstage<LK, CPW, FMT> &cur, int b /* = t & 1, compile-time at every call */) {
+    auto do_step = [&](int t, const wstage<LK, CPW, FMT> &cur, uint32_t sc,
+                       int b /* = t & 1, compile-time at every call */) {
         const int sr = t >> 1;
         const int batch = sr / rounds, rnd = sr % rounds;
         const int c0 = (rnd * WPS + kw) * CPW;
         if (rounds > 1 && b == 0) fetch_tokens(c0);
-        multiply<LK, CPW, FMT, MT>(cur, x, bias, c0, ncp, acc[b]);
+        multiply<LK, CPW, FMT, MT>(cur, x, bias, sc, c0, ncp, acc[b]);
         if (b == 0 || rnd != rounds - 1) return;
         // the strip pairs of this batch are complete: park the partial sums (a clamped duplicate is dropped)
         const bool live = s_lo + batch * SPP + g < s_hi;
@@ -468,6 +511,7 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
 #pragma unroll
     for (int i = 0; i < NST - 1; ++i)
         if (i < nhalf) issue_step(i, st[i]);
+    issue_scales(0, sc_cur);
 
     // token rows of this run (A operand): row r of tile mt
     {
@@ -495,21 +539,26 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     // steady state: NST strips per iteration, every prefetch unconditional (NST is even, so stage i always
     // holds a strip with b = i & 1)
     for (; t + 2 * NST - 2 < nhalf; t += NST) {
+        issue_scales(t + NST, sc_next);
 #pragma unroll
         for (int i = 0; i < NST; ++i) {
             issue_step(t + i + NST - 1, st[(i + NST - 1) % NST]);
-            do_step(t + i, st[i], i & 1);
+            do_step(t + i, st[i], sc_cur[i], i & 1);
         }
+        rotate_scales();
     }
-    // drain: the same, with the prefetch guarded
+    // drain: the same, with the prefetch guarded (an unconditional prefetch of duplicates past the end of
+    // the run was measured: the next run then starts behind those loads, 72.6 -> 79.1 us per C2 step)
     for (; t < nhalf; t += NST) {
+        if (t + NST < nhalf) issue_scales(t + NST, sc_next);
 #pragma unroll
         for (int i = 0; i < NST; ++i) {
             if (t + i < nhalf) {
                 if (t + i + NST - 1 < nhalf) issue_step(t + i + NST - 1, st[(i + NST - 1) % NST]);
-                do_step(t + i, st[i], i & 1);
+                do_step(t + i, st[i], sc_cur[i], i & 1);
             }
         }
+        rotate_scales();
     }
 }
 
