@@ -162,6 +162,8 @@ __device__ __forceinline__ uint32_t units_of(uint32_t fmt, int m)
 #ifdef DX_TRACE
 // Debug build only: per-block start/end time stamps (100 MHz wall clock).
 __device__ unsigned long long g_trace[2][8192][4];
+__device__ unsigned long long g_steps[2][4][256];
+__device__ unsigned int g_nsteps[2][4];
 #endif
 
 // element offset inside a chunk of MFMA step j for lane quarter q
@@ -428,9 +430,11 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
 
     // A step is one 16-row strip: step t = (batch * rounds + round) * 2 + b, b = 0 the first strip of the
     // pair (gate rows / lower 16 down rows), b = 1 the second (up rows / upper 16 down rows).  NST
-    // register stages: the strip of step t + NST - 1 is fetched while step t is multiplied.  An int4 strip
-    // is a quarter of the bytes, so it gets a deeper pipeline for the same registers.
-    constexpr int NST = FMT ? 6 : 2;
+    // register stages: the strip of step t + NST - 1 is fetched while step t is multiplied.  A quantized
+    // strip is a quarter of the bytes or less, so it gets a deeper pipeline (four stages; with six or eight
+    // the runs of a decode batch, a dozen steps each, spend most of their steps outside the steady loop,
+    // which measured slower).
+    constexpr int NST = FMT ? 4 : 2;
     const int nhalf = 2 * nsteps;
     wstage<LK, CPW, FMT> st[NST];
     const gbytes weight_rows0 = ex.w0, weight_rows1 = ex.w1;
@@ -492,6 +496,12 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
         const int batch = sr / rounds, rnd = sr % rounds;
         const int c0 = (rnd * WPS + kw) * CPW;
         if (rounds > 1 && b == 0) fetch_tokens(c0);
+#ifdef DX_TRACE
+        if (threadIdx.x == 0 && (blockIdx.x & 63) == 37) {
+            const unsigned int n = g_nsteps[DOWN][blockIdx.x >> 6]++;
+            if (n < 256) g_steps[DOWN][blockIdx.x >> 6][n] = wall_clock64() | ((unsigned long long)FMT << 60) | ((unsigned long long)(t == 0) << 59);
+        }
+#endif
         multiply<LK, CPW, FMT, MT>(cur, x, bias, sc, c0, ncp, acc[b]);
         if (b == 0 || rnd != rounds - 1) return;
         // the strip pairs of this batch are complete: park the partial sums (a clamped duplicate is dropped)
@@ -1071,6 +1081,14 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
 extern "C" int dx_debug_read_trace(void *dst, size_t bytes)
 {
     return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+extern "C" int dx_debug_read_steps(void *dst, void *counts)
+{
+    unsigned int zero[2][4] = {};
+    int rc = (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_steps), sizeof(unsigned long long) * 2 * 4 * 256, 0, hipMemcpyDeviceToHost);
+    rc |= (int)hipMemcpyFromSymbol(counts, HIP_SYMBOL(g_nsteps), sizeof zero, 0, hipMemcpyDeviceToHost);
+    rc |= (int)hipMemcpyToSymbol(HIP_SYMBOL(g_nsteps), zero, sizeof zero, 0, hipMemcpyHostToDevice);
+    return rc;
 }
 #endif
 
