@@ -145,9 +145,10 @@ constexpr int kHiUnits = 16;
 template <bool DOWN>
 constexpr int kLoUnits = DOWN ? 10 : 8;
 // A block that starts on a new expert pays for the handle, the token rows and a cold pipeline (about
-// 3 us, one and a half bf16 pairs): every expert's range begins with this many units that carry no
-// strips, so the block that holds an expert boundary gets correspondingly fewer strips.
-constexpr uint32_t kRunUnits = 24;
+// 3 us: one and a half bf16 gate/up pairs, two down pairs): every expert's range begins with this many
+// units that carry no strips, so the block that holds an expert boundary gets correspondingly fewer strips.
+template <bool DOWN>
+constexpr uint32_t kRunUnits = DOWN ? 32 : 24;
 // int2 pairs (an eighth of the bytes, the same per-step work) are taken a little below the int4 ones.
 // Experts with more than 16 tokens multiply two token tiles per strip and finish twice the outputs:
 // blocks on such experts were measured 9 % (gate/up) and 19 % (down) slower; 3 and 5 extra units per
@@ -605,7 +606,7 @@ __device__ __forceinline__ void build_partition(const dx_fwd_args &a, partition_
             pl.seg_tokens[e] = m;
             pl.seg_start[e] = e == a.E ? a.T * a.k : a.offsets[e];
             if (m > 0)
-                mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * units_of<DOWN>(fmt_of(e), m) + kRunUnits;
+                mine[i] = (uint32_t)((m + 31) / 32) * strips_of(e) * units_of<DOWN>(fmt_of(e), m) + kRunUnits<DOWN>;
             local += mine[i];
         }
     }
@@ -677,7 +678,8 @@ __device__ __forceinline__ void run_share(const dx_fwd_args &a, const partition_
         const uint32_t hi = (ub1 < pl.cum[e + 1] ? ub1 : pl.cum[e + 1]) - pl.cum[e];
         // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi); pair i starts
         // kRunUnits + i * wgt units into the expert's range
-        const uint32_t lo_p = lo > kRunUnits ? lo - kRunUnits : 0, hi_p = hi > kRunUnits ? hi - kRunUnits : 0;
+        constexpr uint32_t kRun = kRunUnits<DOWN>;
+        const uint32_t lo_p = lo > kRun ? lo - kRun : 0, hi_p = hi > kRun ? hi - kRun : 0;
         int i = (int)((lo_p + wgt - 1) / wgt);
         const int i1 = (int)((hi_p + wgt - 1) / wgt);
         while (i < i1) {
@@ -791,7 +793,7 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
     if (e < a.E) cnt = m = __popcll(lds_mask[e]);
     else if (e == a.E && a.shared) m = a.T;
     if (m > 0)
-        mine = ((m + 31) / 32) * ((e == a.E ? a.shared_f : a.f) / 16) * (int)units_of<false>(fmt, m) + (int)kRunUnits;
+        mine = ((m + 31) / 32) * ((e == a.E ? a.shared_f : a.f) / 16) * (int)units_of<false>(fmt, m) + (int)kRunUnits<false>;
     const int inc = dx_route_core::wave_scan_inclusive(mine), cinc = dx_route_core::wave_scan_inclusive(cnt);
     if (lane == 63) {
         pl.wave_tot[wave] = (uint32_t)inc;
