@@ -783,3 +783,38 @@ def test_route_forward_rejects_bad_arguments(B, LY):
     with pytest.raises(B.DxError):
         ctx.dx_route_forward(0, None, buf, buf, 4, rb.ids, rb.w, rb.counts, rb.offsets, rb.perm, buf)   # no versions published
     ctx.close()
+
+
+def test_profiling_reports_every_kernel_of_a_forward_call(B, LY, dxo):
+    """dx_set_profiling / dx_get_profile: decode calls (separate and as one call) and a prefill call are
+    counted, every kernel reports a positive, plausible duration, reading clears the record, and the
+    results are the same as without profiling."""
+    import dataclasses
+    for T, one_call in ((32, False), (32, True), (300, False)):
+        wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=8 if T <= 64 else 4)
+        x, logits = W.layer_inputs(wl, seed=31)
+        ly = Layer(B, LY, dxo, wl, [0, 2], seed=31)
+        ctx, rb = ly.ctx, ly.rb
+        xd, ld = LY.bits_to_device(x), torch.from_numpy(logits).cuda()
+        y0 = torch.empty((T, wl.d), dtype=torch.bfloat16, device="cuda")
+        y1 = torch.empty_like(y0)
+        rb.route(ctx, 0, ld, T)
+        rb.forward(ctx, 0, xd, y0, None, T)
+        ctx.dx_set_profiling(True)
+        for _ in range(3):
+            if one_call:
+                rb.route_forward(ctx, 0, ld, xd, y1, None, T)
+            else:
+                rb.route(ctx, 0, ld, T)
+                rb.forward(ctx, 0, xd, y1, None, T)
+        p = ctx.dx_get_profile()
+        print(f"profile T={T} one_call={one_call}: {p}", flush=True)
+        assert p["calls"] == 3
+        for key in ("gate_up_ms", "down_ms", "combine_ms"):
+            assert 0.0 < p[key] < 3 * 50.0, (key, p[key])          # three calls, far below 50 ms each
+        assert p["empty_ms"] >= 0.0
+        assert ctx.dx_get_profile()["calls"] == 0                   # reading clears
+        ctx.dx_set_profiling(False)
+        sync()
+        assert torch.equal(y0, y1)
+        ctx.close()
