@@ -355,11 +355,26 @@ __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_
     for (int idx = threadIdx.x; idx < live_groups * MT * 256; idx += kThreads) {
         const int gg = idx / (MT * 256), rem = idx % (MT * 256);
         const int mt = rem / 256, L = rem & 63, i = (rem >> 6) & 3;
+        // the partial sums are read four wavefronts at a time before they are added (in the order of the
+        // wavefronts): one LDS round trip per four instead of one each; past WPS a duplicate is read and
+        // not added
         float v0 = 0.f, v1 = 0.f;
-        for (int w = 0; w < WPS; ++w) {
-            const float *base = redf + (((gg * WPS + w) * 4) * 64 + L) * 4 + i;
-            v0 += base[(0 * 2 + mt) * 64 * 4];
-            v1 += base[(1 * 2 + mt) * 64 * 4];
+        for (int w0 = 0; w0 < WPS; w0 += 4) {
+            float p0[4], p1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ww = w0 + u < WPS ? w0 + u : WPS - 1;
+                const float *base = redf + (((gg * WPS + ww) * 4) * 64 + L) * 4 + i;
+                p0[u] = base[(0 * 2 + mt) * 64 * 4];
+                p1[u] = base[(1 * 2 + mt) * 64 * 4];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (w0 + u < WPS) {
+                    v0 += p0[u];
+                    v1 += p1[u];
+                }
+            }
         }
         const int n = (sb + gg) * rows_per_strip + (L & 15);
         if constexpr (DOWN) {
