@@ -382,7 +382,7 @@ def main():
     shape_name = {"C2": "30B-A3B", "C3": "30B-A3B", "C4": "80B-A3B"}[args.workload]
     if decode:
         achieved = alg_per_launch / (gate_up_us * 1e-6) / 1e9
-        routed = not separate and T <= 32 and E <= 128 and k <= 16    # what dx_route_forward does with these shapes
+        routed = not separate and T <= 64 and E <= 128 and k <= 16    # what dx_route_forward does with these shapes
         roofline = {"bound": "hbm", "kernel": "k_stream_routed (routing prologue + gate/up)" if routed else "k_stream<gate/up>",
                     "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
@@ -426,7 +426,7 @@ def main():
                                f"per layer, rotating over {L} layers' weights",
                    "step": "dx_route (top-k, permutation, hotness counters) + dx_moe_forward of one layer"
                            + (" as two calls" if separate else ", as one dx_route_forward call")
-                           + ("" if separate or (T <= 32 and E <= 128 and k <= 16) else
+                           + ("" if separate or (T <= 64 and E <= 128 and k <= 16) else
                               " (these shapes run the routing kernel and the forward kernels one after the other)")},
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
                       "combine": prof["combine_ms"] * 1e3 / prof["calls"],

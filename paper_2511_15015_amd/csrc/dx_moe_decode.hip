@@ -762,8 +762,8 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool writer = blockIdx.x == 0;
     const int nE = a.E + (a.shared ? 1 : 0);
-    static_assert(kRoutedTokens == 4 * kWaves && kRoutedExperts == 128 && kRoutedTopK == 16,
-                  "one token per 16-lane row, eight logits per lane, one selected id per lane of the row");
+    static_assert(kRoutedTokens == 2 * 4 * kWaves && kRoutedExperts == 128 && kRoutedTopK == 16,
+                  "two passes of one token per 16-lane row, eight logits per lane, one selected id per lane of the row");
 #ifdef DX_TRACE
     const unsigned long long trace_t0 = wall_clock64();
     unsigned long long trace_t1 = 0, trace_t2 = 0, trace_t3 = 0;
@@ -774,31 +774,45 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
     if (writer && r.hotness && tid < a.E) hot_before = r.hotness[tid];
     uint32_t fmt = DX_FMT_BF16; // of expert `tid`
     if (tid < a.E) fmt = a.table[tid].fmt;
-    // ---- top-k and weights: token 4 * wavefront + row (rows past T repeat the last token)
-    const int c = lane & 15, t = 4 * wave + (lane >> 4);
-    int my_id;
-    float my_w;
+    // ---- top-k and weights: token 32 * pass + 4 * wavefront + row (rows past T repeat the last token); the
+    // second pass runs for batches of more than 32 tokens
+    const int c = lane & 15, t0 = 4 * wave + (lane >> 4);
+    const bool second = a.T > 32; // block-uniform
+    int my_id[2] = {0, 0};
+    float my_w[2] = {0.f, 0.f};
     {
-        const float *row = r.logits + (size_t)(t < a.T ? t : a.T - 1) * a.E;
-        float v[8];
+        float v[2][8];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) v[s] = 8 * c + s < a.E ? row[8 * c + s] : -INFINITY;
+        for (int p = 0; p < 2; ++p) {
+            if (p == 0 || second) {
+                const int t = t0 + 32 * p;
+                const float *row = r.logits + (size_t)(t < a.T ? t : a.T - 1) * a.E;
+#pragma unroll
+                for (int s = 0; s < 8; ++s) v[p][s] = 8 * c + s < a.E ? row[8 * c + s] : -INFINITY;
+            }
+        }
         __syncthreads(); // the masks are clear
 #ifdef DX_TRACE
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         trace_t1 = wall_clock64();
 #endif
-        dx_route_core::topk_rows16(v, a.k, lane, my_id, my_w);
+        dx_route_core::topk_rows16(v[0], a.k, lane, my_id[0], my_w[0]);
+        if (second) dx_route_core::topk_rows16(v[1], a.k, lane, my_id[1], my_w[1]);
 #ifdef DX_TRACE
         trace_t2 = wall_clock64();
 #endif
     }
-    const bool have = t < a.T && c < a.k; // this lane holds pair (t, c)
-    if (have) {
-        atomicOr(&lds_mask[my_id], 1ull << t);
-        if (writer) {
-            r.ids[(size_t)t * a.k + c] = my_id;
-            r.w[(size_t)t * a.k + c] = my_w;
+    bool have[2]; // this lane holds pair (t, c) of the pass
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int t = t0 + 32 * p;
+        have[p] = t < a.T && c < a.k;
+        if (have[p]) {
+            atomicOr(&lds_mask[my_id[p]], 1ull << t);
+            if (writer) {
+                r.ids[(size_t)t * a.k + c] = my_id[p];
+                r.w[(size_t)t * a.k + c] = my_w[p];
+            }
         }
     }
     __syncthreads();
@@ -853,11 +867,15 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
     if (e < nE && mine && cum_e <= ub0 && ub0 < cum_e + (uint32_t)mine) pl.e_first = e;
     __syncthreads();
     // ---- the permutation: the rank of pair (t, c) inside its segment = tokens below t that chose the expert
-    if (have) {
-        const unsigned long long below = lds_mask[my_id] & ((1ull << t) - 1ull);
-        const int at = pl.seg_start[my_id] + __popcll(below);
-        lds_perm[at] = t * a.k + c;
-        if (writer) r.perm[at] = t * a.k + c;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        if (have[p]) {
+            const int t = t0 + 32 * p;
+            const unsigned long long below = lds_mask[my_id[p]] & ((1ull << t) - 1ull);
+            const int at = pl.seg_start[my_id[p]] + __popcll(below);
+            lds_perm[at] = t * a.k + c;
+            if (writer) r.perm[at] = t * a.k + c;
+        }
     }
     __syncthreads();
 #ifdef DX_TRACE

@@ -715,8 +715,11 @@ def _route_forward_case(B, LY, dxo, wl, resident, seed, shared=None, logits=None
     (1, 8, 2, 256, 128, 128, 0, [0, 3]), (7, 8, 8, 256, 128, 128, 0, []), (17, 4, 2, 256, 256, 128, 0, [1]),
     (32, 128, 8, 256, 128, 128, 0, list(range(0, 128, 3))), (32, 16, 4, 256, 128, 128, 256, [0, 5, 9]),
     (31, 100, 16, 512, 384, 128, 0, list(range(50))), (32, 1, 1, 256, 128, 32, 0, [0]),
+    # more than 32 tokens: a second routing pass in the prologue, segments of more than 32 tokens
+    (33, 8, 2, 256, 128, 64, 0, [1]), (64, 128, 8, 256, 128, 128, 0, list(range(0, 128, 5))),
+    (50, 16, 4, 256, 128, 128, 256, [0, 5, 9]), (63, 4, 4, 256, 128, 128, 0, [2]),
     # shapes the self-routing kernel does not take: the call runs the two kernels one after the other
-    (33, 8, 2, 256, 128, 64, 0, [1]), (8, 200, 4, 256, 128, 64, 0, [7]), (150, 4, 2, 256, 128, 64, 0, [0]),
+    (65, 8, 2, 256, 128, 64, 0, [1]), (8, 200, 4, 256, 128, 64, 0, [7]), (150, 4, 2, 256, 128, 64, 0, [0]),
 ])
 def test_route_forward_matches_oracle_and_separate_calls(B, LY, dxo, T, E, k, d, f, group, shared_f, resident):
     import dataclasses
