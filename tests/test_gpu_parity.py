@@ -821,3 +821,50 @@ def test_profiling_reports_every_kernel_of_a_forward_call(B, LY, dxo):
         sync()
         assert torch.equal(y0, y1)
         ctx.close()
+
+
+def test_route_forward_random_shapes_match_separate_calls(B, LY, dxo):
+    """Seeded random decode shapes (tokens, experts, top-k, sizes, group, resident sets, with and without a
+    shared expert): dx_route_forward gives the routing arrays of the oracle, bit for bit, and the same y
+    bits as dx_route + dx_moe_forward.  (The layer output itself is checked against the oracle in the
+    tests above; this one covers many shapes quickly.)"""
+    import dataclasses
+    g = np.random.default_rng(20251115)
+    for case in range(36):
+        group = int(g.choice([32, 64, 128]))
+        d = group * int(g.integers(1, 9)) if group < 128 else 128 * int(g.choice([1, 2, 4, 8]))
+        d = max(d, 64)
+        f = group * int(g.integers(1, 5))
+        if f % 16:
+            f = (f // 16 + 1) * 16
+        E = int(g.choice([1, 2, 5, 8, 16, 37, 64, 100, 128]))
+        k = int(g.integers(1, min(E, 16) + 1))
+        T = int(g.integers(1, 65))
+        shared_f = int(g.choice([0, 0, f]))
+        n_res = int(g.integers(0, E + 1))
+        resident = sorted(g.choice(E, size=n_res, replace=False).tolist())
+        wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k, d=d, f=f, group=group, shared_f=shared_f)
+        print(f"case {case}: T={T} E={E} k={k} d={d} f={f} g={group} shared_f={shared_f} hi={n_res}", flush=True)
+        x, logits = W.layer_inputs(wl, seed=100 + case)
+        shared = W.shared_master(wl, 100 + case, 0) if shared_f else None
+        ly = Layer(B, LY, dxo, wl, resident, seed=100 + case, shared=shared)
+        ctx, rb = ly.ctx, ly.rb
+        xd, ld = LY.bits_to_device(x), torch.from_numpy(logits).cuda()
+        y_sep = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+        y_one = torch.full_like(y_sep, float("nan"))
+        rb.route(ctx, 0, ld, T)
+        rb.forward(ctx, 0, xd, y_sep, None, T)
+        sync()
+        w_sep = rb.w.clone()
+        for t in (rb.ids, rb.counts, rb.offsets, rb.perm):
+            t.fill_(-1)
+        rb.route_forward(ctx, 0, ld, xd, y_one, None, T)
+        sync()
+        ids, w, counts, offsets, perm = dxo.route(logits, k)
+        assert np.array_equal(rb.ids.cpu().numpy()[:T], ids)
+        assert np.array_equal(rb.counts.cpu().numpy(), counts)
+        assert np.array_equal(rb.offsets.cpu().numpy(), offsets)
+        assert np.array_equal(rb.perm.cpu().numpy()[:T * k], perm)
+        assert torch.equal(rb.w[:T], w_sep[:T])
+        assert torch.equal(y_one, y_sep)
+        ctx.close()
