@@ -868,3 +868,36 @@ def test_route_forward_random_shapes_match_separate_calls(B, LY, dxo):
         assert torch.equal(rb.w[:T], w_sep[:T])
         assert torch.equal(y_one, y_sep)
         ctx.close()
+
+
+def test_forward_random_shapes_match_oracle(B, LY, dxo):
+    """Seeded random layers in both regimes (1 to 400 tokens; streaming kernels, 128-row and 256-row tiles,
+    shapes that fit the tiles and shapes that do not): every layer output within the bar of the oracle's,
+    token by token within twice the bar."""
+    import dataclasses
+    g = np.random.default_rng(20251116)
+    for case in range(24):
+        group = int(g.choice([32, 64, 128]))
+        d = int(g.choice([128, 256, 384, 512])) if group <= 64 else int(g.choice([128, 256, 512]))
+        f = int(g.choice([64, 128, 192, 256, 384])) if group <= 64 else int(g.choice([128, 256, 384]))
+        if d % group or f % group:
+            d, f = 2 * group, 2 * group
+        E = int(g.choice([1, 2, 3, 4, 8, 16, 32]))
+        k = int(g.integers(1, min(E, 6) + 1))
+        T = int(g.choice([1, 5, 31, 32, 33, 64, 100, 128, 129, 200, 257, 400]))
+        shared_f = int(g.choice([0, 0, f]))
+        n_res = int(g.integers(0, E + 1))
+        resident = sorted(g.choice(E, size=n_res, replace=False).tolist())
+        wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k, d=d, f=f, group=group, shared_f=shared_f)
+        print(f"case {case}: T={T} E={E} k={k} d={d} f={f} g={group} shared_f={shared_f} hi={resident}", flush=True)
+        x, logits = W.layer_inputs(wl, seed=200 + case)
+        shared = W.shared_master(wl, 200 + case, 0) if shared_f else None
+        ly = Layer(B, LY, dxo, wl, resident, seed=200 + case, shared=shared)
+        y_gpu, y_ref = ly.run(x, logits)
+        err = rel_l2(y_gpu, y_ref)
+        print("  rel-L2", err, flush=True)
+        assert err <= REL_L2_TOL
+        yg = bf16_bits_to_f32(y_gpu).astype(np.float64)
+        tok = np.linalg.norm(yg - y_ref, axis=1) / np.maximum(np.linalg.norm(y_ref, axis=1), 1e-30)
+        assert tok.max() <= 2 * REL_L2_TOL
+        ly.ctx.close()
