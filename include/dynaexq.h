@@ -270,7 +270,9 @@ dx_status dx_get_stats(dx_ctx *ctx, dx_stats *out);
  * events to each kernel's own dispatch (start and stop stamps of the launch),
  * larger batches record events around the concurrent kernel chains.
  * dx_get_profile synchronises the compute stream, adds the elapsed times of all
- * calls since the last read and clears them. */
+ * calls since the last read and clears them.  Keep profiling off while the
+ * compute stream is being captured into a graph (timing events do not belong
+ * in a captured graph). */
 typedef struct {
     uint64_t calls;     /* forward calls accumulated */
     double gate_up_ms;  /* summed duration of the gate/up + SwiGLU kernel */
