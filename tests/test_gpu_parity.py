@@ -901,3 +901,35 @@ def test_forward_random_shapes_match_oracle(B, LY, dxo):
         tok = np.linalg.norm(yg - y_ref, axis=1) / np.maximum(np.linalg.norm(y_ref, axis=1), 1e-30)
         assert tok.max() <= 2 * REL_L2_TOL
         ly.ctx.close()
+
+
+def test_forward_random_shapes_int4_int2_pair(B, LY, dxo):
+    """Seeded random layers of the int4 (high) / int2 (low) pair in both regimes, through dx_route_forward:
+    routing bit-exact, layer output within the bar of the oracle's."""
+    import dataclasses
+    g = np.random.default_rng(20251117)
+    for case in range(16):
+        group = int(g.choice([64, 128]))
+        d = int(g.choice([128, 256, 512]))
+        f = int(g.choice([128, 256, 384]))
+        E = int(g.choice([2, 4, 8, 16, 32]))
+        k = int(g.integers(1, min(E, 6) + 1))
+        T = int(g.choice([1, 7, 32, 33, 64, 100, 200, 300]))
+        n_hi = int(g.integers(0, E + 1))
+        hi_ids = sorted(g.choice(E, size=n_hi, replace=False).tolist())
+        wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k, d=d, f=f, group=group)
+        print(f"case {case}: T={T} E={E} k={k} d={d} f={f} g={group} int4={hi_ids}", flush=True)
+        x, logits = W.layer_inputs(wl, seed=300 + case)
+        ctx, lw, versions = _quant_pair_layer(B, LY, dxo, wl, hi_ids, 300 + case, T)
+        rb = LY.RoutingBuffers(T, E, k)
+        y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+        rb.route_forward(ctx, 0, torch.from_numpy(logits).cuda(), LY.bits_to_device(x), y)
+        sync()
+        ids, w, counts, offsets, perm = dxo.route(logits, k)
+        assert np.array_equal(rb.ids.cpu().numpy(), ids) and np.array_equal(rb.perm.cpu().numpy(), perm)
+        y_ref = dxo.moe_forward(versions, d, f, group, x, ids, w)
+        err = rel_l2(LY.device_to_bits(y), y_ref)
+        print("  rel-L2", err, flush=True)
+        assert err <= REL_L2_TOL
+        del lw
+        ctx.close()
