@@ -35,6 +35,7 @@ def test_struct_sizes_match_the_header(B):
     assert C.sizeof(B.DxHandle) == 64
     assert C.sizeof(B.DxConfig) == 64
     assert C.sizeof(B.DxStats) == 104
+    assert C.sizeof(B.DxProfile) == 40     # calls + four summed durations
 
 
 def test_host_rules_agree_with_oracle(B, dxo):
