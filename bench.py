@@ -49,8 +49,8 @@ def parse():
 
 
 def run_c5(args):
-    """Decode stack under hot-set drift (30B-shaped layers, Zipf permutation re-drawn every two
-    windows): every step runs route + forward of all layers and then one worker step of the transition
+    """Decode stack under hot-set drift (30B-shaped layers, Zipf permutation re-drawn every four
+    windows, so that the transitions of one re-draw are through before the next): every step runs route + forward of all layers and then one worker step of the transition
     queue; at each window end the EMA scores pick the next resident sets.  Reports stack tokens/s over
     all steps, per-step time percentiles against a run of the same length without drift, and the
     migration traffic."""
@@ -64,7 +64,7 @@ def run_c5(args):
     torch.cuda.set_device(0)
     wl = W.WORKLOADS["C5"]
     L, T, E, k, d, f, n = args.layers, wl.T, wl.E, wl.k, wl.d, wl.f, wl.n_hi
-    window, n_windows, redraw, n_batches = args.window, args.steps // args.window, 2, 16
+    window, n_windows, redraw, n_batches = args.window, args.steps // args.window, 4, 16
     b_hi = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_BF16)
     b_lo = B.dx_expert_bytes(d, f, wl.group, B.DX_FMT_INT4G)
     layer_budget, spare = n * b_hi + (E - n) * b_lo, 16
@@ -254,7 +254,7 @@ def main():
     defaults = {"C2": dict(steps=960, warmup=96, layers=48, window=64),
                 "C3": dict(steps=48, warmup=8, layers=4, window=2),
                 "C4": dict(steps=480, warmup=48, layers=16, window=16),
-                "C5": dict(steps=384, warmup=0, layers=8, window=32)}[args.workload]
+                "C5": dict(steps=512, warmup=0, layers=8, window=32)}[args.workload]
     for key, val in defaults.items():
         if getattr(args, key) is None:
             setattr(args, key, val)
