@@ -378,6 +378,17 @@ def main():
         flops_per_launch = alg_flops / n_alg
         gate_up_us = prof["gate_up_ms"] * 1e3 / prof["calls"]
 
+        # third pass: an event after every step, for the spread of the step times (each event adds a
+        # little to the step it closes; the mean above is the wall clock without them)
+        n_spread = min(args.steps, 480)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_spread + 1)]
+        marks[0].record(stream)
+        for i in range(n_spread):
+            step_fn(i)
+            marks[i + 1].record(stream)
+        stream.synchronize()
+        spread = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_spread)]) * 1e3
+
     decode = args.workload in ("C2", "C4")
     shape_name = {"C2": "30B-A3B", "C3": "30B-A3B", "C4": "80B-A3B"}[args.workload]
     if decode:
@@ -431,6 +442,9 @@ def main():
         "kernel_us": {"gate_up": gate_up_us, "down": prof["down_ms"] * 1e3 / prof["calls"],
                       "combine": prof["combine_ms"] * 1e3 / prof["calls"],
                       "empty_event_pair": prof["empty_ms"] * 1e3 / prof["calls"]},
+        "step_us_with_an_event_per_step": {"p50": float(np.percentile(spread, 50)), "p99": float(np.percentile(spread, 99)),
+                                           "mean": float(spread.mean()), "steps": int(n_spread)},
+        "launches_per_step": (3 if routed else 4) if decode else None,
         "roofline": roofline,
     }
 
