@@ -389,6 +389,22 @@ def main():
         stream.synchronize()
         spread = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_spread)]) * 1e3
 
+        # what a plain read-only kernel of the same launch shape reaches on this device: regions of the size
+        # of the gate/up launch's bytes, rotating over 2.25 GiB so that nothing comes from the last-level cache
+        probe_mib = 192
+        probe_buf = torch.ones(12 * probe_mib << 20, dtype=torch.uint8, device="cuda")
+        regions = [probe_buf.data_ptr() + (i * probe_mib << 20) for i in range(12)]
+        for i in range(12):
+            ctx.dx_probe_read(regions[i], probe_mib << 20)
+        pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pe0.record(stream)
+        for i in range(48):
+            ctx.dx_probe_read(regions[i % 12], probe_mib << 20)
+        pe1.record(stream)
+        stream.synchronize()
+        probe_gbs = 48 * (probe_mib << 20) / (pe0.elapsed_time(pe1) * 1e-3) / 1e9
+        del probe_buf
+
     decode = args.workload in ("C2", "C4")
     shape_name = {"C2": "30B-A3B", "C3": "30B-A3B", "C4": "80B-A3B"}[args.workload]
     if decode:
@@ -397,7 +413,9 @@ def main():
         roofline = {"bound": "hbm", "kernel": "k_stream_routed (routing prologue + gate/up)" if routed else "k_stream<gate/up>",
                     "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                    "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us}
+                    "algorithmic_bytes_per_launch": alg_per_launch, "avg_launch_us": gate_up_us,
+                    "read_probe_GBps": probe_gbs, "frac_of_read_probe": achieved / probe_gbs,
+                    "read_probe": "dx_probe_read: 192 MiB per launch, read-only, same launch shape, cold regions"}
     else:
         achieved = flops_per_launch / (gate_up_us * 1e-6) / 1e12
         step_flops = float(T * k) * 2.0 * d * 3 * f      # all routed pairs through gate, up and down

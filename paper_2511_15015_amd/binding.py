@@ -27,7 +27,7 @@ EXPORTS = [
     "dx_register_host_master", "dx_register_host_packed", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
     "dx_quantize_expert", "dx_quantize_expert_int2", "dx_swap_handle",
     "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats",
-    "dx_set_profiling", "dx_get_profile",
+    "dx_set_profiling", "dx_get_profile", "dx_probe_read",
     "dx_pools_create", "dx_expert_install", "dx_promote_async", "dx_demote_async", "dx_migrate_poll",
 ]
 
@@ -119,6 +119,7 @@ def load():
     L.dx_get_stats.argtypes = [vp, C.POINTER(DxStats)]
     L.dx_set_profiling.argtypes = [vp, i32]
     L.dx_get_profile.argtypes = [vp, C.POINTER(DxProfile)]
+    L.dx_probe_read.argtypes = [vp, vp, C.c_uint64]
     L.dx_pools_create.argtypes = [vp, i32, i32]
     L.dx_register_host_master.argtypes = [vp, i32, i32, vp, vp, vp]
     L.dx_register_host_packed.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -320,6 +321,9 @@ class Context:
         self._chk(self.lib.dx_get_profile(self.h, C.byref(p)), "dx_get_profile")
         return {"calls": int(p.calls), "gate_up_ms": p.gate_up_ms, "down_ms": p.down_ms, "combine_ms": p.combine_ms,
                 "empty_ms": p.empty_ms}
+
+    def dx_probe_read(self, buf, nbytes):
+        self._chk(self.lib.dx_probe_read(self.h, _ptr(buf), nbytes), "dx_probe_read")
 
     # pools and transitions
     def dx_pools_create(self, hi_blocks, lo_blocks):

@@ -714,6 +714,15 @@ extern "C" dx_status dx_get_stats(dx_ctx *c, dx_stats *out)
     return DX_OK;
 }
 
+extern "C" dx_status dx_probe_read(dx_ctx *c, const void *buf, uint64_t bytes)
+{
+    if (!c) return DX_ERR_INVALID;
+    if (!buf || ((uintptr_t)buf & 15) || (bytes & ((1u << 20) - 1)) || bytes >> 20 > 0x7fffffffull)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_probe_read: a 16-byte aligned buffer of whole MiB is needed");
+    DX_HIP(c, dxk_probe_read(buf, (size_t)bytes, c->n_cu, c->compute));
+    return DX_OK;
+}
+
 extern "C" dx_status dx_set_profiling(dx_ctx *c, int enable)
 {
     if (!c) return DX_ERR_INVALID;

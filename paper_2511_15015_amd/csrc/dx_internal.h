@@ -134,6 +134,7 @@ hipError_t dxk_router_gemm(const dx_bf16 *x, const dx_bf16 *w_r, const float *bi
 hipError_t dxk_hotness_add(unsigned long long *counters, const int32_t *counts, int E, hipStream_t s);
 hipError_t dxk_fill_u64(unsigned long long *p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t dxk_store_handle(dx_handle *slot, const dx_handle &h, hipStream_t s);
+hipError_t dxk_probe_read(const void *buf, size_t bytes, int n_cu, hipStream_t s); // bytes: whole MiB are read
 
 // dx_quantize.hip
 hipError_t dxk_quantize(const dx_bf16 *w, int rows, int K, int group, uint8_t *q, dx_bf16 *sc, hipStream_t s);

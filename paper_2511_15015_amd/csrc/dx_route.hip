@@ -175,6 +175,28 @@ __global__ void k_fill_u64(unsigned long long *p, size_t n, unsigned long long v
     if (i < n) p[i] = v;
 }
 
+// Measurement aid: a plain streaming read.  Block b reads the 1 MiB units b, b + grid, ...; 16 bytes per
+// thread and load, eight loads in flight per thread.  What it reads is folded into a value that is never
+// equal to the magic number, so the loads cannot be dropped and nothing is written.
+__global__ __launch_bounds__(512) void k_probe_read(const char *__restrict__ p, int n_units, unsigned *sink)
+{
+    constexpr size_t kUnit = 1u << 20;
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
+        const char *base = p + (size_t)u * kUnit + threadIdx.x * 16;
+        for (size_t o = 0; o < kUnit; o += (size_t)8 * 512 * 16) {
+            uint4 v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4 *>(base + o + (size_t)i * 512 * 16);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                acc.x ^= v[i].x; acc.y ^= v[i].y; acc.z ^= v[i].z; acc.w ^= v[i].w;
+            }
+        }
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x5EED1E55u && sink) *sink = 1u;
+}
+
 __global__ void k_store_handle(dx_handle *slot, dx_handle h)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *slot = h;
@@ -278,6 +300,15 @@ hipError_t dxk_fill_u64(unsigned long long *p, size_t n, unsigned long long v, h
 {
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t dxk_probe_read(const void *buf, size_t bytes, int n_cu, hipStream_t s)
+{
+    const int n_units = (int)(bytes >> 20);
+    if (n_units == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_probe_read, dim3(n_cu), dim3(512), 0, s, static_cast<const char *>(buf), n_units,
+                       static_cast<unsigned *>(nullptr));
     return hipGetLastError();
 }
 

@@ -933,3 +933,18 @@ def test_forward_random_shapes_int4_int2_pair(B, LY, dxo):
         assert err <= REL_L2_TOL
         del lw
         ctx.close()
+
+
+def test_probe_read_runs_and_checks_its_arguments(B):
+    ctx = B.Context(L=1, E=8, d=64, f=64, top_k=2, group=32, max_tokens=4)
+    buf = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
+    ctx.dx_probe_read(buf, 8 << 20)
+    ctx.dx_probe_read(buf, 0)                                   # nothing to read
+    sync()
+    with pytest.raises(B.DxError):
+        ctx.dx_probe_read(buf, (8 << 20) - 1)                   # not whole MiB
+    with pytest.raises(B.DxError):
+        ctx.dx_probe_read(None, 1 << 20)
+    with pytest.raises(B.DxError):
+        ctx.dx_probe_read(buf.data_ptr() + 4, 1 << 20)          # misaligned
+    ctx.close()
