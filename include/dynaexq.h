@@ -39,8 +39,8 @@ typedef enum {
     DX_ERR_HIP = 5      /* a HIP runtime call failed */
 } dx_status;
 
-/* numeric format of one stored expert version (Sec. 3.2: "multiple weight
- * versions that implement the same operator in different numeric formats") */
+/* numeric format of one stored expert version (Sec. 3.2: an expert keeps
+ * several stored versions of the same operator, one per numeric format) */
 typedef enum { DX_FMT_BF16 = 0, DX_FMT_INT4G = 1, DX_FMT_INT2G = 2 } dx_fmt;
 
 /* residency state of an expert entry (Sec. 3.2, "Residency states") */
@@ -118,9 +118,8 @@ const char *dx_last_error(const dx_ctx *ctx);
 const char *dx_status_str(dx_status s);
 
 /* ----------------------------------------------------------- the hot path */
-/* Router top-k and token permutation (Sec. 3.1: "each request invokes the
- * router to obtain top-k expert IDs, which are used to index a handle
- * table").  logits: dev fp32 [T,E].  Outputs, all dev:
+/* Router top-k and token permutation (Sec. 3.1: the router's top-k expert
+ * ids of a request are the indices into the handle table).  logits: dev fp32 [T,E].  Outputs, all dev:
  *   topk_ids int32 [T,k]  the k largest logits, largest first, ties to the lower index
  *   topk_w   fp32  [T,k]  softmax over those k logits
  *   counts   int32 [E]    pairs routed to each expert
@@ -154,9 +153,9 @@ dx_status dx_route_forward(dx_ctx *ctx, int layer, const dx_handle *handle_table
 dx_status dx_router_logits(dx_ctx *ctx, const void *x_bf16, const void *w_router, const float *bias,
                            int T, float *logits);
 
-/* Mixed-precision expert execution (Sec. 3.2: "The compute path resolves
- * the handle to obtain the active pointer and the associated quantization
- * parameters, then invokes the corresponding kernel").
+/* Mixed-precision expert execution (Sec. 3.2: every selected expert's handle
+ * is resolved to its active version and that version's quantization
+ * parameters, and the kernel for that format runs).
  *   y[t] = sum_j topk_w[t,j] * W_down( silu(W_gate x[t]) * (W_up x[t]) )  of expert topk_ids[t,j]
  *          (+ the layer's shared expert, weight 1, when shared_f > 0)
  * handle_table: dev, E entries of this layer; NULL = the context's own table

@@ -367,13 +367,18 @@ int dxo_moe_forward(const dxo_expert *experts, int E, int d, int f, int group,
         double *o = (double *)malloc(sizeof(double) * (size_t)d);
         double *y = y_out + (size_t)i * d;
         if (!x || !h || !o || t < 0 || t >= T) {
+#pragma omp atomic write
             status = 1;
         } else {
             for (int c = 0; c < d; ++c) x[c] = bf16_widen(x_bf16[(size_t)t * d + c]);
             for (int c = 0; c < d; ++c) y[c] = 0.0;
             for (int j = 0; j < k; ++j) {
                 int e = ids[(size_t)t * k + j];
-                if (e < 0 || e >= E) { status = 1; continue; }
+                if (e < 0 || e >= E) {
+#pragma omp atomic write
+                    status = 1;
+                    continue;
+                }
                 expert_apply(&experts[e], d, f, group, x, h, o);
                 double wj = w[(size_t)t * k + j];
                 for (int c = 0; c < d; ++c) y[c] += wj * o[c];

@@ -1055,8 +1055,15 @@ extern "C" dx_status dx_migrate_poll(dx_ctx *c, int wait, int *n_published)
             c->event_pool.push_back(after);
             return s;
         }
+        // The handle is swapped from here on, so the bookkeeping below must follow whatever happens.  If
+        // the event cannot be recorded, wait for the compute stream instead: after that no forward pass
+        // reads the old version and its block needs no event to be reused.
         hipError_t e = hipEventRecord(after, c->compute);
-        if (e != hipSuccess) DX_FAIL(c, DX_ERR_HIP, "dx_migrate_poll: hipEventRecord: %s", hipGetErrorString(e));
+        if (e != hipSuccess) {
+            (void)hipStreamSynchronize(c->compute);
+            c->event_pool.push_back(after);
+            after = nullptr;
+        }
         pool_give(old_pool, old_block, after);
         track_release(c, t.promote ? c->b_lo : c->b_hi);
         en.block = en.next_block;
