@@ -144,6 +144,26 @@ dx_status dx_route_forward(dx_ctx *ctx, int layer, const dx_handle *handle_table
                            int32_t *topk_ids, float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
                            void *y_bf16 /* dev [T,d] */);
 
+/* dx_route for callers that cannot allocate device memory or create a context
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same kernels and the same outputs as dx_route, with the
+ * routing scratch (per-chunk token masks and segment bases) in a static
+ * device array of DX_ROUTE_STATIC_MAX_ENTRIES entries (768 KiB per GPU, held
+ * until the process ends) instead of a context's buffers.  The call allocates
+ * nothing, frees nothing and needs no context; it runs on the current device,
+ * on hip_stream (NULL = the null stream), and never touches hotness counters.
+ * Limits: 1 <= E <= 1024, 1 <= top_k <= min(E, 64), T >= 0 and
+ * ceil(T/64) * E <= DX_ROUTE_STATIC_MAX_ENTRIES (T = 8192 at E = 512, 4096 at
+ * E = 1024); anything beyond returns DX_ERR_INVALID with nothing launched, and
+ * dx_route_static_last_error() gives the reason (per thread).  All calls on one
+ * GPU share that GPU's array: calls that may overlap on one GPU (different
+ * streams without ordering between them) race; calls on one stream do not. */
+#define DX_ROUTE_STATIC_MAX_ENTRIES 65536
+dx_status dx_route_static(const float *logits /* dev [T,E] */, int T, int E, int top_k,
+                          int32_t *topk_ids, float *topk_w,
+                          int32_t *counts, int32_t *offsets, int32_t *perm, void *hip_stream);
+const char *dx_route_static_last_error(void);
+
 /* The router's linear gate in front of dx_route (Sec. 2.1: the router scores
  * every expert for every token; Sec. 3.1 consumes its top-k):
  *   logits[t,e] = sum_c x[t,c] * w_router[e,c] (+ bias[e])

@@ -21,7 +21,7 @@ DX_STATE_EMPTY, DX_STATE_RESIDENT_HI, DX_STATE_RESIDENT_LO, DX_STATE_PROMOTING, 
 
 EXPORTS = [
     "dx_create", "dx_destroy", "dx_last_error", "dx_status_str",
-    "dx_route", "dx_router_logits", "dx_moe_forward", "dx_route_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
+    "dx_route", "dx_route_static", "dx_route_static_last_error", "dx_router_logits", "dx_moe_forward", "dx_route_forward", "dx_hotness_update", "dx_window_end", "dx_select_resident",
     "dx_expert_bytes", "dx_budget_capacity", "dx_select_topn", "dx_plan_transitions",
     "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
     "dx_register_host_master", "dx_register_host_packed", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
@@ -92,6 +92,9 @@ def load():
     L.dx_status_str.argtypes = [i32]
     L.dx_status_str.restype = C.c_char_p
     L.dx_route.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp]
+    L.dx_route_static.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    L.dx_route_static_last_error.argtypes = []
+    L.dx_route_static_last_error.restype = C.c_char_p
     L.dx_router_logits.argtypes = [vp, vp, vp, vp, i32, vp]
     L.dx_moe_forward.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
     L.dx_route_forward.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
@@ -187,6 +190,15 @@ def dx_select_rank_slack(scores: np.ndarray, cur: np.ndarray, n: int, slack: int
     if s:
         raise DxError(s, "dx_select_rank_slack", "invalid argument")
     return out
+
+
+def dx_route_static(logits, T, E, top_k, topk_ids, topk_w, counts, offsets, perm, stream=None):
+    """dx_route without a context and without any allocation (static device scratch)."""
+    lib = load()
+    s = lib.dx_route_static(_ptr(logits), T, E, top_k, _ptr(topk_ids), _ptr(topk_w), _ptr(counts), _ptr(offsets),
+                            _ptr(perm), C.c_void_p(stream) if stream else None)
+    if s:
+        raise DxError(s, "dx_route_static", lib.dx_route_static_last_error().decode())
 
 
 class Context:

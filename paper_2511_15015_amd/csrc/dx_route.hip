@@ -14,6 +14,8 @@
 #include "dx_route_core.h"
 
 #include <cfloat>
+#include <cstdarg>
+#include <mutex>
 
 namespace {
 
@@ -316,4 +318,76 @@ hipError_t dxk_store_handle(dx_handle *slot, const dx_handle &h, hipStream_t s)
 {
     hipLaunchKernelGGL(k_store_handle, dim3(1), dim3(64), 0, s, slot, h);
     return hipGetLastError();
+}
+
+// ---- dx_route for callers that cannot allocate ---------------------------------------------------
+// The routing scratch (per-chunk token masks and per-chunk segment bases, the two arrays dx_create
+// otherwise allocates for a context) lives in a file-scope device array.  Every GPU the library runs
+// on holds its own copy at its own address until the process ends; the address is asked for once per
+// device, with that device current, and kept.  In host code the array's name is only a stand-in for
+// the symbol: kernels get the resolved pointer, never the name.
+namespace {
+
+constexpr size_t kStaticEntries = DX_ROUTE_STATIC_MAX_ENTRIES; // (chunks of 64 tokens) x experts
+struct route_scratch {
+    unsigned long long mask[kStaticEntries];
+    int32_t chunk_base[kStaticEntries];
+};
+static __device__ __align__(256) route_scratch scratch; // 768 KiB per GPU
+
+constexpr int kMaxDevices = 64;
+route_scratch *g_scratch_ptr[kMaxDevices]; // per device, null until resolved
+std::mutex g_scratch_lock;
+thread_local char g_static_err[256] = "";
+
+dx_status static_fail(dx_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_static_err, sizeof g_static_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+} // namespace
+
+extern "C" const char *dx_route_static_last_error(void) { return g_static_err; }
+
+extern "C" dx_status dx_route_static(const float *logits, int T, int E, int top_k, int32_t *ids, float *w,
+                                     int32_t *counts, int32_t *offsets, int32_t *perm, void *hip_stream)
+{
+    if (E < 1 || E > 1024) return static_fail(DX_ERR_INVALID, "dx_route_static: E=%d outside [1,1024]", E);
+    if (top_k < 1 || top_k > E || top_k > 64)
+        return static_fail(DX_ERR_INVALID, "dx_route_static: top_k=%d outside [1,min(E,64)]", top_k);
+    if (T < 0) return static_fail(DX_ERR_INVALID, "dx_route_static: T=%d is negative", T);
+    const long long n_chunks = T > 0 ? ((long long)T + kChunk - 1) / kChunk : 1;
+    if (n_chunks * E > (long long)kStaticEntries)
+        return static_fail(DX_ERR_INVALID,
+                           "dx_route_static: ceil(T/64)*E = %lld exceeds the static scratch of %zu entries "
+                           "(T=%d, E=%d); use dx_route on a context for larger batches",
+                           n_chunks * E, kStaticEntries, T, E);
+    if (!counts || !offsets || (T > 0 && (!logits || !ids || !w || !perm)))
+        return static_fail(DX_ERR_INVALID, "dx_route_static: null pointer");
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return static_fail(DX_ERR_HIP, "dx_route_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return static_fail(DX_ERR_INVALID, "dx_route_static: device %d not supported", dev);
+    route_scratch *sp;
+    {
+        std::lock_guard<std::mutex> hold(g_scratch_lock);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p)
+                return static_fail(DX_ERR_HIP, "dx_route_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+            g_scratch_ptr[dev] = static_cast<route_scratch *>(p);
+        }
+        sp = g_scratch_ptr[dev];
+    }
+    // Nothing in the scratch has to start at zero: every chunk's block writes all E masks of its chunk,
+    // and the scan writes every base the placement reads.
+    e = dxk_route(logits, T, E, top_k, ids, w, counts, offsets, perm, sp->mask, sp->chunk_base, nullptr,
+                  static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return static_fail(DX_ERR_HIP, "dx_route_static: launch: %s", hipGetErrorString(e));
+    return DX_OK;
 }

@@ -92,3 +92,11 @@ def test_product_path_never_imports_the_oracle():
                 src = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in src.replace("the CPU oracle", "").replace("CPU oracle", ""), fn
                 assert "dxo" not in src, fn
+
+
+def test_route_static_refuses_sizes_beyond_its_scratch_without_touching_a_gpu(B):
+    """The entry point for callers that cannot allocate checks its limits before any HIP call."""
+    lib = B.load()
+    for T, E, k in [(8192, 1024, 8), (64, 2048, 8), (64, 0, 1), (64, 128, 0), (64, 128, 65), (-1, 128, 8)]:
+        assert lib.dx_route_static(None, T, E, k, None, None, None, None, None, None) == B.DX_ERR_INVALID
+        assert lib.dx_route_static_last_error().decode().startswith("dx_route_static:")
