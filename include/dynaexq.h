@@ -282,6 +282,11 @@ dx_status dx_get_formats(dx_ctx *ctx, uint8_t *fmt_out /* host [L*E], dx_fmt; 25
 dx_status dx_get_states(dx_ctx *ctx, uint8_t *state_out /* host [L*E], dx_state */);
 dx_status dx_get_counters(dx_ctx *ctx, int64_t *counters_out /* host [L*E] */); /* syncs the compute stream */
 dx_status dx_get_stats(dx_ctx *ctx, dx_stats *out);
+/* Where a weight pool of Sec. 3.3 lives: which = 0 pool_hi, 1 pool_lo; *base dev (NULL before
+ * dx_pools_create), blocks of *block_bytes bytes, *n_blocks of them, block i at base + i * block_bytes.
+ * For inspection and tests (e.g. filling free blocks with a poison pattern); the memory stays the
+ * library's. */
+dx_status dx_get_pool(dx_ctx *ctx, int which, void **base, uint64_t *block_bytes, int32_t *n_blocks);
 
 /* Per-kernel timing of dx_moe_forward with HIP events on the compute stream
  * (measurement aid, off by default).  While enabled, every forward call

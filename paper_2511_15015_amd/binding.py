@@ -26,7 +26,7 @@ EXPORTS = [
     "dx_select_hysteresis", "dx_select_rank_slack", "dx_select_resident_stable",
     "dx_register_host_master", "dx_register_host_packed", "dx_transitions_limits", "dx_transitions_enqueue", "dx_transitions_pump",
     "dx_quantize_expert", "dx_quantize_expert_int2", "dx_swap_handle",
-    "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats",
+    "dx_handle_table", "dx_get_handle", "dx_get_formats", "dx_get_states", "dx_get_counters", "dx_get_stats", "dx_get_pool",
     "dx_set_profiling", "dx_get_profile", "dx_probe_read",
     "dx_pools_create", "dx_expert_install", "dx_promote_async", "dx_demote_async", "dx_migrate_poll",
 ]
@@ -120,6 +120,7 @@ def load():
     L.dx_get_states.argtypes = [vp, vp]
     L.dx_get_counters.argtypes = [vp, vp]
     L.dx_get_stats.argtypes = [vp, C.POINTER(DxStats)]
+    L.dx_get_pool.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(u64), C.POINTER(C.c_int32)]
     L.dx_set_profiling.argtypes = [vp, i32]
     L.dx_get_profile.argtypes = [vp, C.POINTER(DxProfile)]
     L.dx_probe_read.argtypes = [vp, vp, C.c_uint64]
@@ -324,6 +325,12 @@ class Context:
         st = DxStats()
         self._chk(self.lib.dx_get_stats(self.h, C.byref(st)), "dx_get_stats")
         return st.asdict()
+
+    def dx_get_pool(self, which: int):
+        """-> (base address, block bytes, blocks) of pool_hi (0) or pool_lo (1)"""
+        base, bb, n = C.c_void_p(), C.c_uint64(0), C.c_int32(0)
+        self._chk(self.lib.dx_get_pool(self.h, which, C.byref(base), C.byref(bb), C.byref(n)), "dx_get_pool")
+        return int(base.value or 0), int(bb.value), int(n.value)
 
     def dx_set_profiling(self, enable: bool):
         self._chk(self.lib.dx_set_profiling(self.h, 1 if enable else 0), "dx_set_profiling")

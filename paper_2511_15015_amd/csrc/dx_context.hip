@@ -714,6 +714,18 @@ extern "C" dx_status dx_get_stats(dx_ctx *c, dx_stats *out)
     return DX_OK;
 }
 
+extern "C" dx_status dx_get_pool(dx_ctx *c, int which, void **base, uint64_t *block_bytes, int32_t *n_blocks)
+{
+    if (!c) return DX_ERR_INVALID;
+    if ((which != 0 && which != 1) || !base || !block_bytes || !n_blocks)
+        DX_FAIL(c, DX_ERR_INVALID, "dx_get_pool: bad argument");
+    const dx_block_pool &p = which == 0 ? c->pool_hi : c->pool_lo;
+    *base = p.base;
+    *block_bytes = p.block_bytes;
+    *n_blocks = p.n_blocks;
+    return DX_OK;
+}
+
 extern "C" dx_status dx_probe_read(dx_ctx *c, const void *buf, uint64_t bytes)
 {
     if (!c) return DX_ERR_INVALID;

@@ -184,6 +184,16 @@ struct wstage {
     uint32_t wq[CPW][NQ];       // int4: JN words of 8 nibbles; int2: JN/2 words of 16 codes
 };
 
+// One place for the cache policy of the weight stream.  Plain loads: with the non-temporal hint a read-only
+// stream of whole 128-byte lines is faster on this chip (7.0 against 6.2 TB/s), but here a load instruction
+// covers 64 bytes of each of 16 rows, the other half of every line follows in the next instruction, and the
+// hinted version of these kernels measured slower (gate/up 46.5 against 44.4 us on the 30B-shaped layer).
+template <typename T>
+__device__ __forceinline__ T stream_load(const DX_GLOBAL T *p)
+{
+    return *p;
+}
+
 template <int LK, int CPW, int FMT>
 __device__ __forceinline__ void issue_weights(wstage<LK, CPW, FMT> &st, gbytes row, int c0, int nc, int q)
 {
@@ -195,28 +205,28 @@ __device__ __forceinline__ void issue_weights(wstage<LK, CPW, FMT> &st, gbytes r
             if constexpr (FMT == 2) {
                 gbytes p = row + ((c * CHUNK + q * LK) >> 2);
                 if constexpr (LK == 32) {
-                    const u32x2 t = *reinterpret_cast<gvec8>(p);
+                    const u32x2 t = stream_load(reinterpret_cast<gvec8>(p));
                     st.wq[i][0] = t.x; st.wq[i][1] = t.y;
                 } else if constexpr (LK == 16) {
-                    st.wq[i][0] = *reinterpret_cast<gvec4>(p);
+                    st.wq[i][0] = stream_load(reinterpret_cast<gvec4>(p));
                 } else { // 8 codes = 2 bytes (handles of this format are refused for group 32; kept in bounds)
                     st.wq[i][0] = *reinterpret_cast<const DX_GLOBAL uint16_t *>(p);
                 }
             } else if constexpr (FMT == 1) {
                 gbytes p = row + ((c * CHUNK + q * LK) >> 1);
                 if constexpr (LK == 32) {
-                    const u32x4 t = *reinterpret_cast<gvec16>(p);
+                    const u32x4 t = stream_load(reinterpret_cast<gvec16>(p));
                     st.wq[i][0] = t.x; st.wq[i][1] = t.y; st.wq[i][2] = t.z; st.wq[i][3] = t.w;
                 } else if constexpr (LK == 16) {
-                    const u32x2 t = *reinterpret_cast<gvec8>(p);
+                    const u32x2 t = stream_load(reinterpret_cast<gvec8>(p));
                     st.wq[i][0] = t.x; st.wq[i][1] = t.y;
                 } else {
-                    st.wq[i][0] = *reinterpret_cast<gvec4>(p);
+                    st.wq[i][0] = stream_load(reinterpret_cast<gvec4>(p));
                 }
             } else {
 #pragma unroll
                 for (int j = 0; j < JN; ++j)
-                    st.w[i][j] = *reinterpret_cast<gvec16>(row + (size_t)(c * CHUNK + k_of<LK, 0>(j, q)) * 2);
+                    st.w[i][j] = stream_load(reinterpret_cast<gvec16>(row + (size_t)(c * CHUNK + k_of<LK, 0>(j, q)) * 2));
             }
         }
     }

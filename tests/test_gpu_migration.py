@@ -401,3 +401,56 @@ def test_int4_int2_pair_through_the_pools_and_the_queue(B, LY, dxo):
     assert st["h2d_bytes"] == b_hi + b_lo and st["quantize_read_bytes"] == 0
     assert st["reserved_bytes"] == budget
     ctx.close()
+
+
+def test_poisoned_destination_blocks_never_reach_a_forward_pass(B, LY, dxo):
+    """Publish-after-complete made visible numerically: every pool_hi block that no published handle
+    points to is filled with a NaN bit pattern, eight promotions of 9.4 MB each are started, and a
+    forward pass is issued at once, without polling.  It must be finite and bit for bit the old
+    mapping's result (a handle published before its copy completed would read poison); after the poll
+    the new mapping answers, finite and within tolerance of the oracle."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C2"], E=16, k=4, T=16, n_hi=0)
+    E, n_pro = wl.E, 8
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, 0), dxo.expert_bytes(wl.d, wl.f, wl.group, 1)
+    ctx = B.Context(L=1, E=E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T,
+                    budget_bytes=n_pro * b_hi + (E - n_pro) * b_lo, transient_bytes=n_pro * b_lo)
+    ctx.dx_pools_create(n_pro, E)
+    masters = W.layer_masters(wl, 21, 0)
+    pinned = [tuple(torch.from_numpy(m[e].view(np.int16)).pin_memory() for m in masters) for e in range(E)]
+    for e in range(E):
+        ctx.dx_expert_install(0, e, B.DX_FMT_INT4G, *pinned[e], src_on_device=False)
+    base, block_bytes, n_blocks = ctx.dx_get_pool(0)
+    assert base and n_blocks == n_pro and block_bytes >= b_hi
+    hip = _hip()
+    hip.hipMemset.argtypes = [C.c_void_p, C.c_int, C.c_size_t]
+    assert hip.hipMemset(C.c_void_p(base), 0xFF, n_blocks * block_bytes) == 0      # bf16 0xFFFF is a NaN
+    assert np.all(read_device(base, 64) == 0xFF)
+    x, lg = W.layer_inputs(wl, 21, 0, 0)
+    xd, ld = LY.bits_to_device(x), torch.from_numpy(lg).cuda()
+    rb = LY.RoutingBuffers(wl.T, E, wl.k)
+    y = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
+
+    def forward():
+        rb.route_forward(ctx, 0, ld, xd, y)
+        torch.cuda.synchronize()
+        return LY.device_to_bits(y).copy()
+
+    before = forward()
+    ids, w, counts, *_ = dxo.route(lg, wl.k)
+    hot = [int(e) for e in np.argsort(-counts, kind="stable")[:n_pro]]              # promote the busiest experts
+    for e in hot:
+        ctx.dx_promote_async(0, e, *pinned[e])
+    during = forward()                                                              # no poll in between
+    assert np.isfinite(bf16_bits_to_f32(during)).all()
+    assert np.array_equal(during, before)
+    assert all(ctx.dx_get_formats()[0, e] == B.DX_FMT_INT4G for e in hot)
+    assert ctx.dx_migrate_poll(wait=True) == n_pro
+    after = forward()
+    assert np.isfinite(bf16_bits_to_f32(after)).all() and not np.array_equal(after, before)
+    versions = [dxo.ExpertVersion.bf16(*(m[e] for m in masters)) if e in hot
+                else dxo.ExpertVersion.int4_from_master(*(m[e] for m in masters), wl.group) for e in range(E)]
+    y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w)
+    ya = bf16_bits_to_f32(after).astype(np.float64)
+    assert np.linalg.norm(ya - y_ref) / np.linalg.norm(y_ref) <= REL_L2_TOL
+    ctx.close()

@@ -7,6 +7,7 @@ import torch
 
 from paper_2511_15015_amd import workloads as W
 from paper_2511_15015_amd.workloads import WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits
+from tests.bounds import assert_elementwise
 
 pytestmark = pytest.mark.gpu
 
@@ -201,6 +202,10 @@ class Layer:
         y_gpu = self.LY.device_to_bits(y)
         if tokens is not None:
             y_gpu = y_gpu[np.asarray(tokens)]
+        # next to the norm the caller checks: every element within the bound the bf16 roundings of H, O and y allow
+        used = assert_elementwise(self.dxo, y_gpu, y_ref, self.versions, self.wl.group, x_bits, ids, w, shared=self.shared,
+                                  tokens=tokens, T_call=T)
+        print(f"  element-wise: largest error = {used:.2f} of its bound", flush=True)
         return y_gpu, y_ref
 
 
@@ -481,6 +486,8 @@ def test_forward_c3_prefill_sampled_tokens(B, LY, dxo, T):
     yg = bf16_bits_to_f32(y_gpu).astype(np.float64)
     tok = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
     assert tok.max() <= 2 * REL_L2_TOL
+    used = assert_elementwise(dxo, y_gpu, y_ref, versions, wl.group, x, ids, w, tokens=tokens, T_call=wl.T)
+    print(f"  element-wise: largest error = {used:.2f} of its bound", flush=True)
     del lw
     ctx.close()
 
@@ -707,6 +714,7 @@ def _route_forward_case(B, LY, dxo, wl, resident, seed, shared=None, logits=None
     err = rel_l2(LY.device_to_bits(y_one), y_ref)
     print("  rel-L2", err, flush=True)
     assert err <= REL_L2_TOL
+    assert_elementwise(dxo, LY.device_to_bits(y_one), y_ref, ly.versions, wl.group, x, ids, w, shared=ly.shared, T_call=T)
     ctx.close()
 
 
@@ -768,6 +776,8 @@ def test_route_forward_c2_full_size_and_hotness(B, LY, dxo):
                 err = rel_l2(LY.device_to_bits(y), y_ref)
                 print("  rel-L2", err, flush=True)
                 assert err <= REL_L2_TOL
+                used = assert_elementwise(dxo, LY.device_to_bits(y), y_ref, versions, wl.group, x, ids, w)
+                print(f"  element-wise: largest error = {used:.2f} of its bound", flush=True)
     assert np.array_equal(ctx.dx_get_counters(), c)
     del lws
     ctx.close()

@@ -364,3 +364,107 @@ def test_c4_layer_with_the_int4_int2_pair_under_a_budget(B, LY, dxo):
     assert err <= REL_L2_TOL
     del lw
     ctx.close()
+
+
+def _oracle_versions(dxo, B, LY, master_bits, formats, counts, group):
+    """Oracle-side versions of the activated experts under a format map (others: any placeholder)."""
+    versions, filler = [None] * len(formats), None
+    for e in np.flatnonzero(counts > 0):
+        e = int(e)
+        m = master_bits(e)
+        versions[e] = (dxo.ExpertVersion.bf16(*m) if formats[e] == B.DX_FMT_BF16
+                       else dxo.ExpertVersion.int4_from_master(*m, group))
+        filler = versions[e]
+    return [v if v is not None else filler for v in versions]
+
+
+def test_c4_stack_48_layers_under_40_gib(B, LY, dxo):
+    """The 80B-shaped stack as the configuration states it: 48 layers in one context, a 40 GiB expert
+    budget for the whole stack, the budget rule and dx_select_resident per layer (12 bf16 experts each),
+    a step = one dx_route_forward per layer.  Selections of every layer against the oracle; the layer
+    output of layers 0, 23 and 47 against the oracle (norm and element-wise), routing bit for bit."""
+    from paper_2511_15015_amd import stack as ST
+    from tests.bounds import assert_elementwise
+    wl = WORKLOADS["C4"]
+    L, window, budget = wl.L, 8, 40 * 2 ** 30
+    checked = [0, 23, 47]
+    stk = ST.StaticStack(wl, L, 0, budget, window, keep_masters_of=checked,
+                         progress=lambda m: print("  C4 stack:", m, flush=True))
+    b_hi, b_lo = dxo.expert_bytes(wl.d, wl.f, wl.group, 0), dxo.expert_bytes(wl.d, wl.f, wl.group, 1)
+    b_sh = dxo.expert_bytes(wl.d, wl.shared_f, wl.group, 0)
+    assert stk.layer_budget == (budget - L * b_sh) // L
+    n = dxo.budget_capacity(stk.layer_budget, wl.E, b_hi, b_lo)
+    assert n == 12
+    # scores and selections of all 48 layers from the same warm-up traces on the oracle side
+    for layer in range(L):
+        c = np.zeros(wl.E, np.int64)
+        wr = W.router_matrix(wl, 0, layer)
+        for step in range(1, window + 1):
+            lg = W.router_logits(wl, W.activations(wl, 0, layer, step), wr, 0, layer)
+            dxo.hotness_update(c, dxo.route(lg, wl.k)[2])
+        S = np.zeros(wl.E, np.uint64)
+        dxo.window_end(S, c, 0)
+        assert np.array_equal(stk.scores[layer], S), layer
+        assert np.array_equal(stk.resident[layer], dxo.select_topn(S, n)), layer
+    held = stk.bytes_held()
+    assert held == L * (n * b_hi + (wl.E - n) * b_lo + b_sh) and held <= budget
+    print(f"  C4 stack: {held / 2**30:.2f} GiB held of {budget / 2**30:.0f} GiB", flush=True)
+    for _ in range(2):                                            # whole-stack steps
+        stk.step()
+    torch.cuda.synchronize()
+    for layer in checked:
+        stk.layer_call(layer)
+        torch.cuda.synchronize()
+        x, lg = stk.x_bits[layer], stk.logits_host[layer]
+        ids, w, counts, offsets, perm = dxo.route(lg, wl.k)
+        assert np.array_equal(stk.rb.ids.cpu().numpy(), ids) and np.array_equal(stk.rb.perm.cpu().numpy(), perm)
+        mh = [LY.device_to_bits(m) for m in stk.masters[layer]]
+        fm = stk.ctx.dx_get_formats()[layer]
+        assert set(np.flatnonzero(fm == B.DX_FMT_BF16)) == set(int(e) for e in stk.resident[layer])
+        versions = _oracle_versions(dxo, B, LY, lambda e: tuple(m[e] for m in mh), fm, counts, wl.group)
+        sh = dxo.ExpertVersion.bf16(*(LY.device_to_bits(t) for t in stk.shared[layer]))
+        y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w, shared=sh, shared_f=wl.shared_f)
+        yb = LY.device_to_bits(stk.y)
+        err = rel_l2(yb, y_ref)
+        used = assert_elementwise(dxo, yb, y_ref, versions, wl.group, x, ids, w, shared=sh)
+        print(f"  C4 stack layer {layer}: rel-L2 {err:.2e}, element-wise {used:.2f} of the bound", flush=True)
+        assert err <= REL_L2_TOL
+    stk.close()
+
+
+def test_c5_schedule_as_stated_on_48_layers(B, LY, dxo):
+    """The drifting stack with the stated schedule (48 layers, 256-step hotness window, the Zipf
+    permutation re-drawn every 256 steps, windowed counts, plain top-n) for three windows -- the stated
+    run is eight; layers 0, 23 and 47 at the first step, around every window boundary and at the last
+    step are replayed by the oracle with the format map the library reported for that call."""
+    from paper_2511_15015_amd import stack as ST
+    from tests.bounds import assert_elementwise
+    wl = WORKLOADS["C5"]
+    L, window, redraw, steps = wl.L, wl.window_steps, wl.redraw_every, 3 * wl.window_steps
+    assert (L, window, redraw) == (48, 256, 256)
+    stk = ST.DriftStack(wl, L, 0, window, n_epochs=steps // redraw, progress=lambda m: print("  C5:", m, flush=True))
+    layers = [0, 23, 47]
+    at = sorted({0, steps - 1} | {w * window + o for w in range(1, steps // window) for o in (-1, 0, 1)})
+    print(f"  C5: running {steps} steps, sampling steps {at}", flush=True)
+    res, kept = stk.run(steps, redraw, samples={(s, l) for s in at for l in layers}, time_steps=False)
+    print("  C5:", {k: v for k, v in res.items() if k != "steps_to_settle_after_redraw"}, flush=True)
+    assert len(kept) == len(at) * len(layers)
+    assert res["promotions"] > 0 and res["demotions"] > 0
+    assert res["peak_reserved_bytes"] <= stk.budget_cap()
+    seen_mixed = 0
+    for smp in kept:
+        layer, b, ep = smp["layer"], smp["batch"], smp["epoch"]
+        x, lg = stk.x_bits[layer][b], stk.logits_host[ep][layer][b]
+        ids, w, counts, offsets, perm = dxo.route(lg, wl.k)
+        assert np.array_equal(smp["ids"].cpu().numpy(), ids) and np.array_equal(smp["perm"].cpu().numpy(), perm)
+        fm = smp["formats"]
+        assert int((fm == B.DX_FMT_BF16).sum()) <= wl.n_hi
+        seen_mixed += int(not np.array_equal(np.flatnonzero(fm == B.DX_FMT_BF16), np.arange(wl.n_hi)))
+        versions = _oracle_versions(dxo, B, LY, lambda e: stk.master_bits(layer, e), fm, counts, wl.group)
+        y_ref = dxo.moe_forward(versions, wl.d, wl.f, wl.group, x, ids, w)
+        yb = LY.device_to_bits(smp["y"])
+        err = rel_l2(yb, y_ref)
+        assert err <= REL_L2_TOL, (smp["step"], layer, err)
+        assert_elementwise(dxo, yb, y_ref, versions, wl.group, x, ids, w)
+    assert seen_mixed > 0                                         # the resident sets did move
+    stk.close()
