@@ -50,8 +50,9 @@ def parse():
     ap.add_argument("--redraw", type=int, default=256, help="C5: steps between re-draws of the Zipf permutation")
     ap.add_argument("--alpha", type=float, default=0.0, help="C5: EMA factor of the hotness score, 0 <= alpha < 1")
     ap.add_argument("--margin", type=float, default=0.0, help="C5: hysteresis margin in counts (0: plain top-n)")
-    ap.add_argument("--issue-per-step", type=int, default=16, help="C5: transitions issued per step at most")
-    ap.add_argument("--max-inflight", type=int, default=32, help="C5: transitions between issue and publication at most")
+    ap.add_argument("--issue-per-step", type=int, default=32, help="C5: transitions issued per step at most")
+    ap.add_argument("--max-inflight", type=int, default=64, help="C5: transitions between issue and publication at most")
+    ap.add_argument("--spare", type=int, default=64, help="C5: spare blocks per pool (the transient room of in-flight transitions)")
     ap.add_argument("--banks", type=int, default=8, help="C5: pinned host master banks, shared by layer mod banks")
     ap.add_argument("--budget-gib", type=float, default=40.0, help="C4: expert-weight budget of the whole stack")
     return ap.parse_args()
@@ -83,7 +84,8 @@ def run_c5(args):
     say = lambda m: print(f"bench C5: {m}", file=sys.stderr, flush=True)
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        stk = ST.DriftStack(wl, L, args.seed, window, alpha_q16=alpha_q16, banks=args.banks, max_inflight=args.max_inflight,
+        stk = ST.DriftStack(wl, L, args.seed, window, alpha_q16=alpha_q16, banks=args.banks, spare=args.spare,
+                            max_inflight=args.max_inflight,
                             n_epochs=n_epochs, stream=stream, progress=say)
         kw = dict(margin_q16=margin_q16, issue_per_step=args.issue_per_step)
         say("warm-up run (no drift): reaches the resident sets of the first permutation")
@@ -106,7 +108,7 @@ def run_c5(args):
         "config": {"workload": f"C5: {L} 30B-A3B-shaped MoE layers per step, decode T={T}, Zipf(s={wl.zipf_s}) permutation "
                                f"re-drawn every {redraw} steps, {window}-step hotness window, EMA alpha {args.alpha:g}, "
                                f"margin {args.margin:g} counts, {n} bf16 experts per layer, at most {args.max_inflight} "
-                               f"transitions in flight and {args.issue_per_step} issued per step; pinned bf16 masters as "
+                               f"transitions in flight, {args.issue_per_step} issued per step, {args.spare} spare blocks per pool; pinned bf16 masters as "
                                f"{stk.banks} banks shared by layer mod {stk.banks}",
                    "step": "route + forward of every layer (one dx_route_forward each), stream synchronize, then one "
                            "dx_transitions_pump; dx_window_end + dx_select_resident + queueing at every window end"},

@@ -133,7 +133,7 @@ dx_status dx_route(dx_ctx *ctx, int layer, const float *logits, int T,
 
 /* dx_route followed by dx_moe_forward on the same arrays, as one call: same
  * arguments, same outputs (ids, weights, counts, offsets, perm and y), same
- * hotness update.  For decode batches (T <= 64, E <= 128, top_k <= 16, shapes
+ * hotness update.  For decode batches (T <= 64, E <= 512, top_k <= 16, shapes
  * that fit the streaming kernels' fast path) the gate/up kernel routes in its
  * own prologue (every block repeats the small routing computation of Sec. 3.1
  * and keeps it in LDS; the first block writes the arrays out), which saves the

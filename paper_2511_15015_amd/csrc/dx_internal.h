@@ -160,7 +160,7 @@ struct dx_fwd_args {
 // Decode batches that the gate/up kernel routes itself (dx_route_forward): what its first block reads and
 // writes on top of dx_fwd_args (whose ids, w, offsets and perm point at the same arrays for the kernels
 // that follow)
-constexpr int DX_ROUTED_MAX_TOKENS = 64, DX_ROUTED_MAX_EXPERTS = 128, DX_ROUTED_MAX_TOPK = 16;
+constexpr int DX_ROUTED_MAX_TOKENS = 64, DX_ROUTED_MAX_EXPERTS = 512, DX_ROUTED_MAX_TOPK = 16;
 struct dx_route_io {
     const float *logits; // [T, E]
     int32_t *ids;        // [T, k]

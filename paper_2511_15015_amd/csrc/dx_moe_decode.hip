@@ -760,30 +760,41 @@ __global__ __launch_bounds__(kThreads) void k_stream(dx_fwd_args a)
 // LDS, so the forward pass does not wait for a routing kernel and its round trip through memory; block 0
 // also writes the routing arrays out for the down and combine kernels and for the caller, and adds the
 // counts to the layer's hotness counters.
+// NV = logits per lane of a token's 16-lane row (E <= 16 * NV): 8 for up to 128 experts, 32 for up to 512.
+// Each thread also owns EPT consecutive experts for the counts, offsets and cost units.
 constexpr int kRoutedTokens = DX_ROUTED_MAX_TOKENS, kRoutedExperts = DX_ROUTED_MAX_EXPERTS, kRoutedTopK = DX_ROUTED_MAX_TOPK;
 
-template <int LK, int CPW>
+template <int LK, int CPW, int NV>
 __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_route_io r)
 {
+    constexpr int kE = 16 * NV;                 // experts this instance takes
+    constexpr int EPT = kE >= kThreads ? 2 : 1; // experts per thread: E + shared <= kThreads * EPT
     __shared__ f32x4 red[2][kWaves][4][64];
     __shared__ partition_lds pl;
-    __shared__ unsigned long long lds_mask[kRoutedExperts];
+    __shared__ unsigned long long lds_mask[kE];
     __shared__ int lds_perm[kRoutedTokens * kRoutedTopK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool writer = blockIdx.x == 0;
     const int nE = a.E + (a.shared ? 1 : 0);
-    static_assert(kRoutedTokens == 2 * 4 * kWaves && kRoutedExperts == 128 && kRoutedTopK == 16,
-                  "two passes of one token per 16-lane row, eight logits per lane, one selected id per lane of the row");
+    static_assert(kRoutedTokens == 2 * 4 * kWaves && kE <= kRoutedExperts && kRoutedTopK == 16,
+                  "two passes of one token per 16-lane row, NV logits per lane, one selected id per lane of the row");
+    static_assert(kE + 1 <= kThreads * EPT, "every expert and the shared one have a thread");
 #ifdef DX_TRACE
     const unsigned long long trace_t0 = wall_clock64();
     unsigned long long trace_t1 = 0, trace_t2 = 0, trace_t3 = 0;
 #endif
 
-    if (tid < kRoutedExperts) lds_mask[tid] = 0ull;
-    unsigned long long hot_before = 0ull;
-    if (writer && r.hotness && tid < a.E) hot_before = r.hotness[tid];
-    uint32_t fmt = DX_FMT_BF16; // of expert `tid`
-    if (tid < a.E) fmt = a.table[tid].fmt;
+    for (int i = tid; i < kE; i += kThreads) lds_mask[i] = 0ull;
+    unsigned long long hot_before[EPT];
+    uint32_t fmt[EPT]; // of the experts tid * EPT + i
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int e = tid * EPT + i;
+        hot_before[i] = 0ull;
+        fmt[i] = DX_FMT_BF16;
+        if (writer && r.hotness && e < a.E) hot_before[i] = r.hotness[e];
+        if (e < a.E) fmt[i] = a.table[e].fmt;
+    }
     // ---- top-k and weights: token 32 * pass + 4 * wavefront + row (rows past T repeat the last token); the
     // second pass runs for batches of more than 32 tokens
     const int c = lane & 15, t0 = 4 * wave + (lane >> 4);
@@ -791,14 +802,12 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
     int my_id[2] = {0, 0};
     float my_w[2] = {0.f, 0.f};
     {
-        float v[2][8];
+        float v[2][NV];
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             if (p == 0 || second) {
                 const int t = t0 + 32 * p;
-                const float *row = r.logits + (size_t)(t < a.T ? t : a.T - 1) * a.E;
-#pragma unroll
-                for (int s = 0; s < 8; ++s) v[p][s] = 8 * c + s < a.E ? row[8 * c + s] : -INFINITY;
+                dx_route_core::load_logits<NV>(r.logits + (size_t)(t < a.T ? t : a.T - 1) * a.E, c, a.E, v[p]);
             }
         }
         __syncthreads(); // the masks are clear
@@ -806,8 +815,8 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         trace_t1 = wall_clock64();
 #endif
-        dx_route_core::topk_rows16(v[0], a.k, lane, my_id[0], my_w[0]);
-        if (second) dx_route_core::topk_rows16(v[1], a.k, lane, my_id[1], my_w[1]);
+        dx_route_core::topk_rows16<NV>(v[0], a.k, lane, my_id[0], my_w[0]);
+        if (second) dx_route_core::topk_rows16<NV>(v[1], a.k, lane, my_id[1], my_w[1]);
 #ifdef DX_TRACE
         trace_t2 = wall_clock64();
 #endif
@@ -826,14 +835,21 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
         }
     }
     __syncthreads();
-    // ---- counts, offsets (exclusive scan) and the cost units of the partition, one expert per thread
-    const int e = tid;
-    int cnt = 0, m = 0, mine = 0;
-    if (e < a.E) cnt = m = __popcll(lds_mask[e]);
-    else if (e == a.E && a.shared) m = a.T;
-    if (m > 0)
-        mine = ((m + 31) / 32) * ((e == a.E ? a.shared_f : a.f) / 16) * (int)units_of<false>(fmt, m) + (int)kRunUnits<false>;
-    const int inc = dx_route_core::wave_scan_inclusive(mine), cinc = dx_route_core::wave_scan_inclusive(cnt);
+    // ---- counts, offsets (exclusive scan) and the cost units of the partition, EPT consecutive experts per thread
+    int cnt[EPT], m[EPT], mine[EPT], cnt_local = 0, mine_local = 0;
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int e = tid * EPT + i;
+        cnt[i] = m[i] = mine[i] = 0;
+        if (e < a.E) cnt[i] = m[i] = __popcll(lds_mask[e]);
+        else if (e == a.E && a.shared) m[i] = a.T;
+        if (m[i] > 0)
+            mine[i] = ((m[i] + 31) / 32) * ((e == a.E ? a.shared_f : a.f) / 16) * (int)units_of<false>(fmt[i], m[i]) +
+                      (int)kRunUnits<false>;
+        cnt_local += cnt[i];
+        mine_local += mine[i];
+    }
+    const int inc = dx_route_core::wave_scan_inclusive(mine_local), cinc = dx_route_core::wave_scan_inclusive(cnt_local);
     if (lane == 63) {
         pl.wave_tot[wave] = (uint32_t)inc;
         pl.wave_cnt[wave] = cinc;
@@ -853,28 +869,36 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
         U += tu;
         ctot += tc;
     }
-    const int off_e = cbase + cinc - cnt;
-    const uint32_t cum_e = base + (uint32_t)(inc - mine);
-    if (e < nE) {
-        pl.cum[e] = cum_e;
-        pl.seg_tokens[e] = m;
-        pl.seg_start[e] = e == a.E ? a.T * a.k : off_e;
-    }
-    if (tid == 0) pl.cum[nE] = U;
-    if (writer) {
-        if (e < a.E) {
-            r.counts[e] = cnt;
-            r.offsets[e] = off_e;
-            if (r.hotness) r.hotness[e] = hot_before + (unsigned long long)cnt;
-        }
-        if (e == 0) r.offsets[a.E] = ctot;
-    }
     // this block's unit range (in double: exact for these sizes, and every block evaluates the same
     // expression for a shared boundary)
     const double share = (double)U / (double)gridDim.x;
     const uint32_t ub0 = (uint32_t)(share * (double)blockIdx.x);
     const uint32_t ub1 = blockIdx.x + 1 == gridDim.x ? U : (uint32_t)(share * (double)(blockIdx.x + 1));
-    if (e < nE && mine && cum_e <= ub0 && ub0 < cum_e + (uint32_t)mine) pl.e_first = e;
+    {
+        int off_e = cbase + cinc - cnt_local;
+        uint32_t cum_e = base + (uint32_t)(inc - mine_local);
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int e = tid * EPT + i;
+            if (e < nE) {
+                pl.cum[e] = cum_e;
+                pl.seg_tokens[e] = m[i];
+                pl.seg_start[e] = e == a.E ? a.T * a.k : off_e;
+                if (mine[i] && cum_e <= ub0 && ub0 < cum_e + (uint32_t)mine[i]) pl.e_first = e;
+            }
+            if (writer && e < a.E) {
+                r.counts[e] = cnt[i];
+                r.offsets[e] = off_e;
+                if (r.hotness) r.hotness[e] = hot_before[i] + (unsigned long long)cnt[i];
+            }
+            off_e += cnt[i];
+            cum_e += (uint32_t)mine[i];
+        }
+    }
+    if (tid == 0) {
+        pl.cum[nE] = U;
+        if (writer) r.offsets[a.E] = ctot;
+    }
     __syncthreads();
     // ---- the permutation: the rank of pair (t, c) inside its segment = tokens below t that chose the expert
 #pragma unroll
@@ -1067,9 +1091,12 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
         hipEvent_t ev[8] = {};
         if (marks)
             for (int i = 0; i < 8; ++i) ev[i] = marks[i];
-        if (r) {
-            if (gu.cpw == 2) launch(k_stream_routed<LK, 2>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
-            else launch(k_stream_routed<LK, 1>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
+        if (r && a.E <= 128) {
+            if (gu.cpw == 2) launch(k_stream_routed<LK, 2, 8>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
+            else launch(k_stream_routed<LK, 1, 8>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
+        } else if (r) {
+            if (gu.cpw == 2) launch(k_stream_routed<LK, 2, 32>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
+            else launch(k_stream_routed<LK, 1, 32>, grid, dim3(kThreads), s, ev[0], ev[1], a, *r);
         } else {
             launch_stream<LK, false>(a, gu, grid, s, ev[0], ev[1]);
         }

@@ -71,10 +71,13 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
         if (t >= T) break; // wave-uniform
         const float *row = logits + (size_t)t * E;
         float v[1][NV];
+        if constexpr (NV >= 4) dx_route_core::load_logits<NV>(row, lane, E, v[0]);
+        else {
 #pragma unroll
-        for (int s = 0; s < NV; ++s) {
-            const int e = NV * lane + s;
-            v[0][s] = e < E ? row[e] : -INFINITY;
+            for (int s = 0; s < NV; ++s) {
+                const int e = NV * lane + s;
+                v[0][s] = e < E ? row[e < E ? e : E - 1] : -INFINITY;
+            }
         }
         int id1[1];
         float wt1[1];

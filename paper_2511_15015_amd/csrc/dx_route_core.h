@@ -119,18 +119,19 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive(uint32_t x) // the same,
 }
 
 // Four token rows per wavefront, one per 16-lane row, so that one instruction stream serves all four:
-// lane c of a row owns the experts 8c .. 8c+7 of its token (E <= 128), v[s] is the logit of expert 8c+s
-// (-inf past the last expert) and is consumed.  Same results as topk_rows: on return lane c < k of a row
-// holds the c-th id of its token and its weight (k <= 16).  The weights add up in the order of wave_sum
-// (a 16-lane row scan), so they are the same bits.
-__device__ __forceinline__ void topk_rows16(float (&v)[8], int k, int lane, int &id, float &wt)
+// lane c of a row owns the experts NV*c .. NV*c+NV-1 of its token (E <= 16*NV), v[s] is the logit of expert
+// NV*c+s (-inf past the last expert) and is consumed.  Same results as topk_rows: on return lane c < k of
+// a row holds the c-th id of its token and its weight (k <= 16).  The weights add up in the order of
+// wave_sum (a 16-lane row scan), so they are the same bits.
+template <int NV>
+__device__ __forceinline__ void topk_rows16(float (&v)[NV], int k, int lane, int &id, float &wt)
 {
     const int c = lane & 15;
     // Order-preserving integer keys (x + 0 turns -0 into +0, so equal logits have equal keys): integer
     // max / compare, no NaN handling in the way.  A taken entry gets the lowest key, below -inf's.
-    int key[8];
+    int key[NV];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < NV; ++s) {
         const int b = __float_as_int(v[s] + 0.f);
         key[s] = b ^ ((b >> 31) & 0x7fffffff);
     }
@@ -138,7 +139,9 @@ __device__ __forceinline__ void topk_rows16(float (&v)[8], int k, int lane, int 
     id = 0;
     int lgk = kTaken;
     for (int j = 0; j < k; ++j) {
-        int top = max(max(max(key[0], key[1]), max(key[2], key[3])), max(max(key[4], key[5]), max(key[6], key[7])));
+        int top = key[0];
+#pragma unroll
+        for (int s = 1; s < NV; ++s) top = max(top, key[s]);
         top = max(top, __builtin_amdgcn_mov_dpp(top, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
         top = max(top, __builtin_amdgcn_mov_dpp(top, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
         top = max(top, __builtin_amdgcn_mov_dpp(top, 0x141, 0xF, 0xF, false)); // row_half_mirror
@@ -146,15 +149,15 @@ __device__ __forceinline__ void topk_rows16(float (&v)[8], int k, int lane, int 
         // the lowest expert index that holds it: lowest own candidate, then the minimum over the row
         int cand = 0x7fffffff;
 #pragma unroll
-        for (int s = 7; s >= 0; --s)
-            if (key[s] == top) cand = 8 * c + s;
+        for (int s = NV - 1; s >= 0; --s)
+            if (key[s] == top) cand = NV * c + s;
         cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0xB1, 0xF, 0xF, false));
         cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x4E, 0xF, 0xF, false));
         cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x141, 0xF, 0xF, false));
         cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x140, 0xF, 0xF, false));
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
-            if (cand == 8 * c + s) key[s] = kTaken;
+        for (int s = 0; s < NV; ++s)
+            if (cand == NV * c + s) key[s] = kTaken;
         if (c == j) {
             id = cand;
             lgk = top;
@@ -170,6 +173,28 @@ __device__ __forceinline__ void topk_rows16(float (&v)[8], int k, int lane, int 
     x += dpp_move<0x118, 0xF, true>(0.f, x); // row_shr:8 -> lane 15 of the row holds its sum
     const float sum = __shfl(x, lane | 15, 64);
     wt = ex / sum;
+}
+
+// The NV consecutive logits row[NV*c .. NV*c+NV-1] of one lane (-inf past the last expert E), every load
+// unconditional: 16-byte loads when the row is a whole number of them and starts on a 16-byte boundary
+// (E % 4 == 0 and an aligned array: then every token's row does), else single loads on clamped indices -- never one round trip per logit.
+template <int NV>
+__device__ __forceinline__ void load_logits(const float *row, int c, int E, float (&v)[NV])
+{
+    float raw[NV];
+    if ((E & 3) == 0 && (reinterpret_cast<uintptr_t>(row) & 15) == 0) {
+#pragma unroll
+        for (int s = 0; s < NV; s += 4) {
+            const int e0 = NV * c + s < E ? NV * c + s : E - 4;
+            const float4 t = *reinterpret_cast<const float4 *>(row + e0);
+            raw[s] = t.x; raw[s + 1] = t.y; raw[s + 2] = t.z; raw[s + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < NV; ++s) raw[s] = row[NV * c + s < E ? NV * c + s : E - 1];
+    }
+#pragma unroll
+    for (int s = 0; s < NV; ++s) v[s] = NV * c + s < E ? raw[s] : -INFINITY;
 }
 
 } // namespace dx_route_core

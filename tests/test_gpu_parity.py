@@ -726,8 +726,19 @@ def _route_forward_case(B, LY, dxo, wl, resident, seed, shared=None, logits=None
     # more than 32 tokens: a second routing pass in the prologue, segments of more than 32 tokens
     (33, 8, 2, 256, 128, 64, 0, [1]), (64, 128, 8, 256, 128, 128, 0, list(range(0, 128, 5))),
     (50, 16, 4, 256, 128, 128, 256, [0, 5, 9]), (63, 4, 4, 256, 128, 128, 0, [2]),
+    # more than 128 experts: 32 logits per lane in the routing prologue, two experts per thread in the scans
+    (8, 200, 4, 256, 128, 64, 0, [7]), (32, 512, 10, 256, 128, 128, 0, list(range(3, 512, 43))),
+    (32, 512, 10, 256, 128, 128, 128, list(range(0, 512, 50))), (64, 300, 16, 256, 128, 128, 0, [0, 299]),
+    (33, 511, 10, 256, 128, 64, 128, list(range(100, 140))), (1, 129, 1, 256, 128, 128, 0, []),
     # shapes the self-routing kernel does not take: the call runs the two kernels one after the other
-    (65, 8, 2, 256, 128, 64, 0, [1]), (8, 200, 4, 256, 128, 64, 0, [7]), (150, 4, 2, 256, 128, 64, 0, [0]),
+    (65, 8, 2, 256, 128, 64, 0, [1]), (8, 600, 4, 256, 128, 64, 0, [7]), (150, 4, 2, 256, 128, 64, 0, [0]),
+    # full-width contractions (8 or 16 K-chunks) at small intermediate sizes, every chunk size, with and
+    # without a shared expert, resident sets from none to all
+    (32, 16, 4, 2048, 128, 128, 0, [0, 5, 9]), (32, 128, 8, 2048, 128, 128, 0, list(range(0, 128, 4))),
+    (17, 12, 3, 2048, 128, 128, 0, []), (5, 8, 2, 2048, 128, 128, 0, list(range(8))), (1, 8, 2, 1024, 128, 128, 0, [2, 3]),
+    (32, 16, 4, 2048, 128, 128, 256, [0, 5, 9]), (16, 6, 6, 1024, 128, 128, 128, [4]), (31, 40, 16, 1024, 128, 64, 0, [1, 2, 3, 30]),
+    (32, 8, 2, 512, 64, 64, 0, [0, 1]), (9, 8, 3, 512, 64, 32, 64, [6]), (32, 4, 2, 256, 32, 32, 0, [3]),
+    (32, 128, 8, 2048, 128, 128, 0, list(range(60, 124))), (3, 128, 8, 2048, 128, 128, 128, [0]),
 ])
 def test_route_forward_matches_oracle_and_separate_calls(B, LY, dxo, T, E, k, d, f, group, shared_f, resident):
     import dataclasses
