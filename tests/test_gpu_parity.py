@@ -66,6 +66,61 @@ def test_quantize_bit_exact(B, LY, dxo, rows, K, group):
     ctx.close()
 
 
+@pytest.mark.parametrize("bits", [4, 2])
+def test_quantize_exact_ties_and_extreme_scales(B, LY, dxo, bits):
+    """Rows built to sit on the quantizer's rounding ties: the group scale is a power of two (absmax = q_max *
+    2^k) and the other values are multiples of half a step, so about half of them are exact ties that must go
+    to the even code; scales with other mantissas mixed in; groups with tiny and huge scales (the kernel's
+    divide shortcut does not cover those) and an all-zero group.  Codes and scales bit for bit."""
+    group, rows, K = 128, 96, 1024
+    g = np.random.default_rng(1234 + bits)
+    q_max = 7 if bits == 4 else 1
+    w = np.zeros((rows, K), np.float32)
+    for r in range(rows):
+        for c0 in range(0, K, group):
+            kind = (r + c0 // group) % 6
+            if kind == 0:                                   # step 2^k: every multiple of step/2 in range
+                step = 2.0 ** int(g.integers(-12, 3))
+                vals = g.integers(-2 * q_max, 2 * q_max + 1, group) * (step / 2)
+            elif kind == 1:                                 # step 1.5 * 2^k: ties at odd multiples of 0.75 * 2^k
+                step = 1.5 * 2.0 ** int(g.integers(-10, 2))
+                vals = g.integers(-2 * q_max, 2 * q_max + 1, group) * (step / 2)
+            elif kind == 2:                                 # tiny scale (below the shortcut's range)
+                step = 2.0 ** -110
+                vals = g.integers(-2 * q_max, 2 * q_max + 1, group) * (step / 2)
+            elif kind == 3:                                 # huge scale
+                step = 2.0 ** 105
+                vals = g.integers(-2 * q_max, 2 * q_max + 1, group) * (step / 2)
+            elif kind == 4:                                 # ordinary weights
+                step = None
+                vals = 0.02 * g.standard_normal(group)
+            else:
+                step = None
+                vals = np.zeros(group)
+            vals = np.asarray(vals, np.float64)
+            if step is not None:
+                vals[0] = q_max * step                      # pins absmax, hence the scale
+            w[r, c0:c0 + group] = vals
+    bits_in = f32_to_bf16_bits(w)
+    quant = dxo.quantize if bits == 4 else dxo.quantize2
+    q_ref, s_ref = quant(bits_in, group)
+    # the rows really are full of ties: the oracle's codes differ from rounding half away from zero
+    wf = bf16_bits_to_f32(bits_in).astype(np.float64)
+    sf = np.repeat(bf16_bits_to_f32(s_ref).astype(np.float64), group, axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        frac = np.where(sf > 0, np.abs(wf / sf) % 1.0, 0.0)
+    assert np.count_nonzero(frac == 0.5) > rows * K // 8
+    ctx = B.Context(L=1, E=4, d=128, f=128, top_k=2, group=group, max_tokens=4)
+    q = torch.empty((rows, K // (8 // bits)), dtype=torch.uint8, device="cuda")
+    s = torch.empty((rows, K // group), dtype=torch.bfloat16, device="cuda")
+    (ctx.dx_quantize_expert if bits == 4 else ctx.dx_quantize_expert_int2)(LY.bits_to_device(bits_in), rows, K, group, q, s)
+    sync()
+    assert np.array_equal(LY.device_to_bits(s), s_ref)
+    bad = np.argwhere(q.cpu().numpy() != q_ref)
+    assert len(bad) == 0, bad[:5]
+    ctx.close()
+
+
 def test_quantize_rejects_bad_arguments(B):
     ctx = B.Context(L=1, E=4, d=128, f=128, top_k=2, group=64, max_tokens=4)
     buf = torch.zeros(4096, dtype=torch.uint8, device="cuda")
