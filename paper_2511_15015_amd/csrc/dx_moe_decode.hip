@@ -12,7 +12,7 @@
 // every compute unit streams for the whole duration of the kernel, so:
 //   - Persistent grid, one block of 8 wavefronts per compute unit.  The work
 //     is the list of (activated expert, 32-token block, pair of 16-row weight
-//     strips), weighed in cost units (kHiUnits, kLoUnits, kRunUnits below);
+//     strips), weighed in cost units (units_of, kRunUnits below);
 //     block b takes the pairs that start in units [b*U/G, (b+1)*U/G).  Every
 //     block derives the same partition from `offsets` and the handles'
 //     formats in its prologue (a block-wide scan): no atomics, no work queue.
@@ -138,26 +138,26 @@ __device__ __forceinline__ u32x4 interleave_halves(u32x4 v)
 constexpr int kWaves = 8;             // wavefronts per block
 constexpr int kThreads = 64 * kWaves; // 512
 constexpr int kMaxExperts = 1024 + 1; // routed + shared
-// Relative cost of a bf16 / int4 strip pair in the partition.  An int4 pair is a quarter of the bytes
-// but carries the same per-step work (barrier, reduction), so it is weighed by measured time, not
-// bytes: 8/16 of a bf16 pair when K is long (gate/up), 10/16 when it is short (down).
-constexpr int kHiUnits = 16;
+// Cost units of the partition, from a fit of the blocks' measured times (per-block time stamps of a debug
+// build, 30B- and 80B-shaped decode layers, a dozen routing draws each) to
+//   time = runs * c_run + sum over the block's strip pairs of c(format, token tiles):
+// a bf16 pair for up to 16 tokens is 32 units; the same pair for two token tiles multiplies and finishes
+// twice as much (1.22x gate/up, 1.29x down); a quantized pair is a quarter of the bytes or less but carries
+// the same per-step work (expansion, barrier, reduction), 0.43x for one tile and 0.7x to 0.75x for two --
+// weighed by time, not bytes.  int2 pairs (an eighth of the bytes, the same per-step work) are taken a
+// little below the int4 ones.
+// A run that starts on a new expert pays for the token rows and a cold pipeline (3 to 4 us: one bf16
+// gate/up pair, almost three down pairs): every expert's range begins with kRunUnits units that carry no
+// strips, so the block that holds an expert boundary gets correspondingly fewer strips.
 template <bool DOWN>
-constexpr int kLoUnits = DOWN ? 10 : 8;
-// A block that starts on a new expert pays for the handle, the token rows and a cold pipeline (about
-// 3 us: one and a half bf16 gate/up pairs, two down pairs): every expert's range begins with this many
-// units that carry no strips, so the block that holds an expert boundary gets correspondingly fewer strips.
-template <bool DOWN>
-constexpr uint32_t kRunUnits = DOWN ? 32 : 24;
-// int2 pairs (an eighth of the bytes, the same per-step work) are taken a little below the int4 ones.
-// Experts with more than 16 tokens multiply two token tiles per strip and finish twice the outputs:
-// blocks on such experts were measured 9 % (gate/up) and 19 % (down) slower; 3 and 5 extra units per
-// pair gave the shortest kernels.
+constexpr uint32_t kRunUnits = DOWN ? 88 : 40;
 template <bool DOWN>
 __device__ __forceinline__ uint32_t units_of(uint32_t fmt, int m)
 {
-    const uint32_t base = fmt == DX_FMT_BF16 ? kHiUnits : (fmt == DX_FMT_INT4G ? kLoUnits<DOWN> : kLoUnits<DOWN> - 2);
-    return base + (m > 16 ? (DOWN ? 5 : 3) : 0);
+    const bool two = m > 16;
+    if (fmt == DX_FMT_BF16) return two ? (DOWN ? 41 : 40) : 32;
+    const uint32_t q = two ? (DOWN ? 24 : 23) : (DOWN ? 13 : 14);
+    return fmt == DX_FMT_INT4G ? q : q - 3;
 }
 
 #ifdef DX_TRACE
@@ -165,6 +165,7 @@ __device__ __forceinline__ uint32_t units_of(uint32_t fmt, int m)
 __device__ unsigned long long g_trace[2][8192][4];
 __device__ unsigned long long g_steps[2][4][256];
 __device__ unsigned int g_nsteps[2][4];
+__device__ unsigned int g_mix[2][8192][8]; // per block: runs, then strip pairs by (format != bf16) * 2 + (second token tile)
 #endif
 
 // element offset inside a chunk of MFMA step j for lane quarter q
@@ -712,6 +713,12 @@ __device__ __forceinline__ void run_share(const dx_fwd_args &a, const partition_
             const int iend = i1 < (mb + 1) * spe ? i1 : (mb + 1) * spe;
             const int s_lo = i - mb * spe, s_hi = iend - mb * spe;
             const bool two = ex.m - mb * 32 > 16;
+#ifdef DX_TRACE
+            if (threadIdx.x == 0 && blockIdx.x < 8192) {
+                g_mix[DOWN][blockIdx.x][0] += 1;
+                g_mix[DOWN][blockIdx.x][1 + (ex.fmt != DX_FMT_BF16) * 2 + two] += s_hi - s_lo;
+            }
+#endif
             if (ex.fmt == DX_FMT_INT4G) {
                 if (two) run_strips<LK, CPW, DOWN, 1, 2, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
                 else run_strips<LK, CPW, DOWN, 1, 1, FAST>(a, ex, mb, s_lo, s_hi, red, pb);
@@ -815,8 +822,17 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         trace_t1 = wall_clock64();
 #endif
-        dx_route_core::topk_rows16<NV>(v[0], a.k, lane, my_id[0], my_w[0]);
-        if (second) dx_route_core::topk_rows16<NV>(v[1], a.k, lane, my_id[1], my_w[1]);
+        if constexpr (NV <= 8) {
+            dx_route_core::topk_rows16<NV>(v[0], a.k, lane, my_id[0], my_w[0]);
+            if (second) dx_route_core::topk_rows16<NV>(v[1], a.k, lane, my_id[1], my_w[1]);
+        } else {
+            // wide layers: a threshold first, then the selections over the few entries at or above it; the keys
+            // pass through this wavefront's eighth of `red`, which holds nothing yet
+            static_assert(sizeof(red) >= sizeof(int) * 64 * NV * kWaves, "NV * 64 words of LDS per wavefront");
+            auto scratch = (__attribute__((address_space(3))) int *)&red[0][0][0][0] + wave * 64 * NV;
+            dx_route_core::topk_rows16_filtered<NV, 6>(v[0], a.k, lane, my_id[0], my_w[0], scratch);
+            if (second) dx_route_core::topk_rows16_filtered<NV, 6>(v[1], a.k, lane, my_id[1], my_w[1], scratch);
+        }
 #ifdef DX_TRACE
         trace_t2 = wall_clock64();
 #endif
@@ -1153,6 +1169,14 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
 extern "C" int dx_debug_read_trace(void *dst, size_t bytes)
 {
     return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+extern "C" int dx_debug_read_mix(void *dst) // reads and clears
+{
+    int rc = (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_mix), sizeof(unsigned int) * 2 * 8192 * 8, 0, hipMemcpyDeviceToHost);
+    void *p = nullptr;
+    rc |= (int)hipGetSymbolAddress(&p, HIP_SYMBOL(g_mix));
+    if (p) rc |= (int)hipMemset(p, 0, sizeof(unsigned int) * 2 * 8192 * 8);
+    return rc;
 }
 extern "C" int dx_debug_read_steps(void *dst, void *counts)
 {

@@ -118,51 +118,71 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive(uint32_t x) // the same,
     return x;
 }
 
-// Four token rows per wavefront, one per 16-lane row, so that one instruction stream serves all four:
-// lane c of a row owns the experts NV*c .. NV*c+NV-1 of its token (E <= 16*NV), v[s] is the logit of expert
-// NV*c+s (-inf past the last expert) and is consumed.  Same results as topk_rows: on return lane c < k of
-// a row holds the c-th id of its token and its weight (k <= 16).  The weights add up in the order of
-// wave_sum (a 16-lane row scan), so they are the same bits.
-template <int NV>
-__device__ __forceinline__ void topk_rows16(float (&v)[NV], int k, int lane, int &id, float &wt)
+// ---- four token rows per wavefront, one per 16-lane row, so that one instruction stream serves all four ----
+
+__device__ __forceinline__ int row_max(int x) // maximum over the 16-lane row, in every lane of it
 {
-    const int c = lane & 15;
-    // Order-preserving integer keys (x + 0 turns -0 into +0, so equal logits have equal keys): integer
-    // max / compare, no NaN handling in the way.  A taken entry gets the lowest key, below -inf's.
-    int key[NV];
-#pragma unroll
-    for (int s = 0; s < NV; ++s) {
-        const int b = __float_as_int(v[s] + 0.f);
-        key[s] = b ^ ((b >> 31) & 0x7fffffff);
-    }
-    constexpr int kTaken = (int)0x80000000;
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x141, 0xF, 0xF, false)); // row_half_mirror
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x140, 0xF, 0xF, false)); // row_mirror
+    return x;
+}
+
+__device__ __forceinline__ int row_min(int x)
+{
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, false));
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, false));
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0x141, 0xF, 0xF, false));
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0x140, 0xF, 0xF, false));
+    return x;
+}
+
+constexpr int kTakenKey = (int)0x80000000; // below every logit's key, -inf's included
+
+// Order-preserving integer key of a logit (x + 0 turns -0 into +0, so equal logits have equal keys): integer
+// max / compare, no NaN handling in the way.
+__device__ __forceinline__ int key_of(float x)
+{
+    const int b = __float_as_int(x + 0.f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+
+// k selections over the row's entries: lane c holds N of them, key[s] with expert index ix[s], the indices
+// ascending in s (unused places: kTakenKey with an index above every expert's).  Each selection takes the
+// largest key of the row and, among equals, the lowest expert index; lane j < k of the row ends up with
+// the j-th selection's index in id and its key in lgk.  key is consumed.
+template <int N>
+__device__ __forceinline__ void select_rows16(int (&key)[N], const int (&ix)[N], int k, int c, int &id, int &lgk)
+{
     id = 0;
-    int lgk = kTaken;
+    lgk = kTakenKey;
     for (int j = 0; j < k; ++j) {
         int top = key[0];
 #pragma unroll
-        for (int s = 1; s < NV; ++s) top = max(top, key[s]);
-        top = max(top, __builtin_amdgcn_mov_dpp(top, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
-        top = max(top, __builtin_amdgcn_mov_dpp(top, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
-        top = max(top, __builtin_amdgcn_mov_dpp(top, 0x141, 0xF, 0xF, false)); // row_half_mirror
-        top = max(top, __builtin_amdgcn_mov_dpp(top, 0x140, 0xF, 0xF, false)); // row_mirror: uniform over the row
+        for (int s = 1; s < N; ++s) top = max(top, key[s]);
+        top = row_max(top);
         // the lowest expert index that holds it: lowest own candidate, then the minimum over the row
         int cand = 0x7fffffff;
 #pragma unroll
-        for (int s = NV - 1; s >= 0; --s)
-            if (key[s] == top) cand = NV * c + s;
-        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0xB1, 0xF, 0xF, false));
-        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x4E, 0xF, 0xF, false));
-        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x141, 0xF, 0xF, false));
-        cand = min(cand, __builtin_amdgcn_mov_dpp(cand, 0x140, 0xF, 0xF, false));
+        for (int s = N - 1; s >= 0; --s)
+            if (key[s] == top) cand = ix[s];
+        cand = row_min(cand);
 #pragma unroll
-        for (int s = 0; s < NV; ++s)
-            if (cand == NV * c + s) key[s] = kTaken;
+        for (int s = 0; s < N; ++s)
+            if (ix[s] == cand) key[s] = kTakenKey;
         if (c == j) {
             id = cand;
             lgk = top;
         }
     }
+}
+
+// The routing weight of the row's lane c < k from the selected keys: the softmax over the k selected logits.
+// The terms add up in the order of wave_sum (a 16-lane row scan), so the weights are the same bits.
+__device__ __forceinline__ float weight_rows16(int lgk, int k, int lane)
+{
+    const int c = lane & 15;
     const float lg = __int_as_float(lgk ^ ((lgk >> 31) & 0x7fffffff)); // back to the logit
     const float top0 = __shfl(lg, lane & 48, 64);
     const float ex = c < k ? expf(lg - top0) : 0.f;
@@ -172,7 +192,77 @@ __device__ __forceinline__ void topk_rows16(float (&v)[NV], int k, int lane, int
     x += dpp_move<0x114, 0xF, true>(0.f, x); // row_shr:4
     x += dpp_move<0x118, 0xF, true>(0.f, x); // row_shr:8 -> lane 15 of the row holds its sum
     const float sum = __shfl(x, lane | 15, 64);
-    wt = ex / sum;
+    return ex / sum;
+}
+
+// Lane c of a row owns the experts NV*c .. NV*c+NV-1 of its token (E <= 16*NV), v[s] is the logit of expert
+// NV*c+s (-inf past the last expert).  Same results as topk_rows: on return lane c < k of a row holds the
+// c-th id of its token and its weight (k <= 16).
+template <int NV>
+__device__ __forceinline__ void topk_rows16(const float (&v)[NV], int k, int lane, int &id, float &wt)
+{
+    const int c = lane & 15;
+    int key[NV], ix[NV];
+#pragma unroll
+    for (int s = 0; s < NV; ++s) {
+        key[s] = key_of(v[s]);
+        ix[s] = NV * c + s;
+    }
+    int lgk;
+    select_rows16<NV>(key, ix, k, c, id, lgk);
+    wt = weight_rows16(lgk, k, lane);
+}
+
+// The same for many logits per lane (wide layers), where k selections over NV entries each are most of a
+// decode kernel's prologue.  A threshold first: the k-th of the row's lane maxima taken one value at a time
+// (all lanes that hold the value retire together, so ties only lower it) has at least k entries at or above
+// it, hence every selected entry is among those -- a dozen or two per row instead of 16*NV.  Each lane keeps
+// up to C of them (its keys go through `scratch`, NV*64 words of LDS of this wavefront alone, to be fetched
+// by a position that differs from lane to lane) and the selections run over C entries.  When some lane of
+// the wavefront has more than C entries at or above the threshold (heavy ties, a token whose favourites are
+// neighbours), the wavefront selects over all NV as above: the results are the same either way.
+template <int NV, int C>
+__device__ __forceinline__ void topk_rows16_filtered(const float (&v)[NV], int k, int lane, int &id, float &wt,
+                                                     __attribute__((address_space(3))) int *scratch)
+{
+    static_assert(NV <= 32, "the entries at or above the threshold are a 32-bit mask");
+    const int c = lane & 15;
+    int key[NV];
+#pragma unroll
+    for (int s = 0; s < NV; ++s) key[s] = key_of(v[s]);
+    int best = key[0];
+#pragma unroll
+    for (int s = 1; s < NV; ++s) best = max(best, key[s]);
+    int tau = kTakenKey;
+    for (int j = 0; j < k; ++j) {
+        tau = row_max(best);
+        if (best == tau) best = kTakenKey;
+    }
+    uint32_t above = 0;
+#pragma unroll
+    for (int s = 0; s < NV; ++s) above |= (key[s] >= tau ? 1u : 0u) << s;
+    int lgk;
+    if (__ballot(__popc(above) > C) != 0ull) { // wavefront-uniform
+        int ix[NV];
+#pragma unroll
+        for (int s = 0; s < NV; ++s) ix[s] = NV * c + s;
+        select_rows16<NV>(key, ix, k, c, id, lgk);
+    } else {
+#pragma unroll
+        for (int s = 0; s < NV; ++s) scratch[s * 64 + lane] = key[s];
+        int ck[C], ci[C];
+#pragma unroll
+        for (int j = 0; j < C; ++j) {
+            const bool have = above != 0u;
+            const int slot = have ? __builtin_ctz(above) : 0;
+            above &= above - 1u;
+            const int got = scratch[slot * 64 + lane];
+            ck[j] = have ? got : kTakenKey;
+            ci[j] = have ? NV * c + slot : 0x7fffffff;
+        }
+        select_rows16<C>(ck, ci, k, c, id, lgk);
+    }
+    wt = weight_rows16(lgk, k, lane);
 }
 
 // The NV consecutive logits row[NV*c .. NV*c+NV-1] of one lane (-inf past the last expert E), every load

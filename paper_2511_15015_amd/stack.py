@@ -189,7 +189,7 @@ class DriftStack:
         kept = []
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)] if time_steps else None
         st0 = ctx.dx_get_stats()
-        settle, since_redraw, armed = [], None, False
+        drain, since_enqueue = [], None  # steps from a window end until its transitions are all published
         hi_pairs = total_pairs = 0
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -198,8 +198,6 @@ class DriftStack:
         for step in range(steps):
             ep = epoch0 + (step // redraw_steps if redraw_steps else 0)
             assert ep < self.n_epochs
-            if redraw_steps and step % redraw_steps == 0 and step > 0:
-                since_redraw, armed = 0, False
             b = step % self.n_batches
             for layer in range(L):
                 if lib.dx_route_forward(h, layer, None, self.lgs[ep][layer][b].data_ptr(), self.xs[layer][b].data_ptr(), T,
@@ -213,12 +211,13 @@ class DriftStack:
                 ev[step + 1].record(stream)
             stream.synchronize()
             issued, published, queued = ctx.dx_transitions_pump(issue_per_step)
-            if since_redraw is not None:
-                since_redraw += 1
-                if armed and queued == 0 and ctx.dx_get_stats()["in_flight"] == 0:
-                    settle.append(since_redraw)
-                    since_redraw = None
-            if (step + 1) % self.window == 0:
+            if since_enqueue is not None:
+                since_enqueue += 1
+                if queued == 0 and ctx.dx_get_stats()["in_flight"] == 0:
+                    drain.append(since_enqueue)
+                    since_enqueue = None
+            if (step + 1) % self.window == 0 and step + 1 < steps:  # no step follows the last one to carry it out
+                wanted = 0
                 ctx.dx_window_end()
                 for layer in range(L):
                     if margin_q16 or rank_slack:
@@ -228,7 +227,9 @@ class DriftStack:
                         target = ctx.dx_select_resident(layer, self.layer_budget)
                     pro, dem = ctx.dx_plan_transitions(layer, target)
                     ctx.dx_transitions_enqueue(layer, pro, dem)
-                armed = True
+                    wanted += len(pro) + len(dem)
+                if wanted and since_enqueue is None:
+                    since_enqueue = 0
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         st1 = ctx.dx_get_stats()
@@ -238,7 +239,7 @@ class DriftStack:
                    h2d_bytes_per_step=(st1["h2d_bytes"] - st0["h2d_bytes"]) / steps,
                    quantize_bytes_per_step=(st1["quantize_read_bytes"] + st1["quantize_write_bytes"]
                                             - st0["quantize_read_bytes"] - st0["quantize_write_bytes"]) / steps,
-                   steps_to_settle_after_redraw=settle, still_unsettled_at_end=since_redraw is not None,
+                   steps_to_drain_after_window_end=drain, still_draining_at_end=since_enqueue is not None,
                    queued_at_end=st1["queued"], in_flight_at_end=st1["in_flight"],
                    peak_in_flight=st1["peak_in_flight"], peak_reserved_bytes=st1["peak_reserved_bytes"],
                    deferred=st1["deferred"] - st0["deferred"])

@@ -813,6 +813,41 @@ def test_route_forward_with_tied_logits(B, LY, dxo):
     _route_forward_case(B, LY, dxo, wl, [0, 1, 2, 64, 127], 29, logits=logits)
 
 
+@pytest.mark.parametrize("case", ["coarse grid", "all equal", "favourites are neighbours", "one lane and ties",
+                                  "few above a sea of equals", "second pass"])
+def test_route_forward_wide_layer_threshold_and_its_fallback(B, LY, dxo, case):
+    """Layers of more than 128 experts select through a threshold and a short list per lane, and fall back to
+    the plain selection when a lane's list overflows: logits built so that both ways run (many exact ties;
+    every favourite of a token among 32 neighbouring experts; a few distinct values above a constant), all
+    of them against the oracle's ids, weights and permutation."""
+    import dataclasses
+    T = 40 if case == "second pass" else 32
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=512, k=10, d=256, f=128, group=128)
+    g = np.random.default_rng(901)
+    if case == "coarse grid":
+        logits = np.round(g.standard_normal((T, wl.E)) * 2).astype(np.float32) / 2
+        logits[logits == 0] *= np.where(g.random(np.count_nonzero(logits == 0)) < 0.5, -1.0, 1.0).astype(np.float32)
+    elif case == "all equal":
+        logits = np.full((T, wl.E), 0.25, np.float32)
+        logits[1::2] = -3.0
+    elif case == "favourites are neighbours":
+        logits = g.standard_normal((T, wl.E)).astype(np.float32)
+        for t in range(T):       # the ten largest inside one lane's 32 experts, a different lane per token
+            lane = t % 16
+            logits[t, 32 * lane + g.permutation(32)[:12]] += 8.0
+    elif case == "one lane and ties":
+        logits = g.standard_normal((T, wl.E)).astype(np.float32)
+        for t in range(T):
+            logits[t, 32 * (t % 16) + np.arange(0, 32, 2)] = 5.0   # sixteen equal favourites in one lane
+    elif case == "few above a sea of equals":
+        logits = np.zeros((T, wl.E), np.float32)
+        for t in range(T):
+            logits[t, g.permutation(wl.E)[:4]] = g.random(4).astype(np.float32) + 1.0   # 4 < k distinct leaders
+    else:
+        logits = (g.standard_normal((T, wl.E)) * 1.5).astype(np.float32)
+    _route_forward_case(B, LY, dxo, wl, list(range(5, 512, 61)), 31, logits=logits)
+
+
 def test_route_forward_c2_full_size_and_hotness(B, LY, dxo):
     """The 30B-shaped decode layer through dx_route_forward, with the hotness update inside the call."""
     wl = WORKLOADS["C2"]

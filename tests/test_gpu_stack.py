@@ -447,7 +447,7 @@ def test_c5_schedule_as_stated_on_48_layers(B, LY, dxo):
     at = sorted({0, steps - 1} | {w * window + o for w in range(1, steps // window) for o in (-1, 0, 1)})
     print(f"  C5: running {steps} steps, sampling steps {at}", flush=True)
     res, kept = stk.run(steps, redraw, samples={(s, l) for s in at for l in layers}, time_steps=False)
-    print("  C5:", {k: v for k, v in res.items() if k != "steps_to_settle_after_redraw"}, flush=True)
+    print("  C5:", {k: v for k, v in res.items() if k != "steps_to_drain_after_window_end"}, flush=True)
     assert len(kept) == len(at) * len(layers)
     assert res["promotions"] > 0 and res["demotions"] > 0
     assert res["peak_reserved_bytes"] <= stk.budget_cap()
