@@ -185,14 +185,91 @@ struct wstage {
     uint32_t wq[CPW][NQ];       // int4: JN words of 8 nibbles; int2: JN/2 words of 16 codes
 };
 
-// One place for the cache policy of the weight stream.  Plain loads: with the non-temporal hint a read-only
-// stream of whole 128-byte lines is faster on this chip (7.0 against 6.2 TB/s), but here a load instruction
-// covers 64 bytes of each of 16 rows, the other half of every line follows in the next instruction, and the
-// hinted version of these kernels measured slower (gate/up 46.5 against 44.4 us on the 30B-shaped layer).
+// The cache policy of the weight stream.  With the non-temporal hint a read-only stream of whole 128-byte
+// lines is faster on this chip (7.0 against 6.2 TB/s), but only when a load instruction covers whole lines.
+// The operand layout of the matrix instruction wants, per instruction, 16 bytes per lane of the lane's own
+// row: 64 bytes of each of 16 rows, the other half of every line in the next instruction -- hinted loads of
+// that shape measured slower than plain ones (gate/up 46.5 against 44.4 us on the 30B-shaped layer).
+// kLines<...> chooses the other shape where the sizes allow it: an instruction covers 128 bytes of each of 8
+// rows (lane (r, q) fetches row r % 8 of the strip's lower or upper half, 16-byte piece q + 4 * (r / 8) of
+// the line), so half of what a lane receives belongs to the lane 8 places away in its 16-lane row; one DPP
+// move per register (row rotation by 8, written to half of the row) puts it there when the stage is used.
+// The K order of the operands does not change.
 template <typename T>
 __device__ __forceinline__ T stream_load(const DX_GLOBAL T *p)
 {
     return *p;
+}
+template <typename T>
+__device__ __forceinline__ T line_load(const DX_GLOBAL T *p)
+{
+    return __builtin_nontemporal_load(p);
+}
+
+// bf16: a chunk of 128 elements is two lines per row; int4: two chunks side by side are one line per row
+template <int LK, int CPW, int FMT, bool FAST>
+constexpr bool kLines = LK == 32 && (FMT == 0 || (FMT == 1 && CPW == 2 && FAST));
+
+// Line-shaped loads of one strip: `row_lo` is the strip's row r % 8, `half_rows` the bytes from there to row
+// 8 + r % 8, `piece` = q + 4 * (r / 8).  Stage register n of chunk i then holds load (line n / 2, half n % 2)
+// (bf16) resp. chunk register i holds the load of half i (int4) until settle_lines sorts them out.
+template <int LK, int CPW, int FMT>
+__device__ __forceinline__ void issue_weight_lines(wstage<LK, CPW, FMT> &st, gbytes row_lo, size_t half_rows, int c0,
+                                                   int nc, int piece)
+{
+    if constexpr (FMT == 0) {
+#pragma unroll
+        for (int i = 0; i < CPW; ++i) {
+            if (c0 + i < nc) { // wavefront-uniform
+#pragma unroll
+                for (int n = 0; n < 4; ++n)
+                    st.w[i][n] = line_load(reinterpret_cast<gvec16>(row_lo + (n & 1) * half_rows + (size_t)(c0 + i) * 256 +
+                                                                   128 * (n >> 1) + 16 * piece));
+            }
+        }
+    } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const u32x4 t = line_load(reinterpret_cast<gvec16>(row_lo + h * half_rows + (size_t)c0 * 64 + 16 * piece));
+            st.wq[h][0] = t.x; st.wq[h][1] = t.y; st.wq[h][2] = t.z; st.wq[h][3] = t.w;
+        }
+    }
+}
+
+// register pair (a, b) = loads (lower half rows, upper half rows) of the same line: afterwards a holds the
+// lane's own row's first piece, b its second (lanes 0..7 of a row keep a and receive b from 8 places up,
+// lanes 8..15 keep b and receive a from 8 places down)
+__device__ __forceinline__ void settle_pair(uint32_t &a, uint32_t &b)
+{
+    const int a0 = (int)a, b0 = (int)b;
+    a = (uint32_t)__builtin_amdgcn_update_dpp(a0, b0, 0x128 /* row_ror:8 */, 0xF, 0xC, false);
+    b = (uint32_t)__builtin_amdgcn_update_dpp(b0, a0, 0x128, 0xF, 0x3, false);
+}
+
+template <int LK, int CPW, int FMT>
+__device__ __forceinline__ wstage<LK, CPW, FMT> settle_lines(const wstage<LK, CPW, FMT> &in, int c0, int nc)
+{
+    wstage<LK, CPW, FMT> st = in;
+    if constexpr (FMT == 0) {
+#pragma unroll
+        for (int i = 0; i < CPW; ++i) {
+            if (c0 + i < nc) {
+#pragma unroll
+                for (int l = 0; l < 2; ++l)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        uint32_t a = st.w[i][2 * l][k], b = st.w[i][2 * l + 1][k];
+                        settle_pair(a, b);
+                        st.w[i][2 * l][k] = a;
+                        st.w[i][2 * l + 1][k] = b;
+                    }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) settle_pair(st.wq[0][k], st.wq[1][k]);
+    }
+    return st;
 }
 
 template <int LK, int CPW, int FMT>
@@ -469,9 +546,15 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
         const int b = t & 1, sr = t >> 1;
         int s = s_lo + (sr / rounds) * SPP + g;
         s = s < s_hi ? s : s_hi - 1; // ragged tail: fetch a duplicate rather than branch
-        const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
-        const gbytes p = (b ? weight_rows1 : weight_rows0) + (size_t)n * ex.row_bytes;
-        issue_weights<LK, CPW, FMT>(dst, p, ((sr % rounds) * WPS + kw) * CPW, ncp, q);
+        if constexpr (kLines<LK, CPW, FMT, FAST>) {
+            const int n = s * rows_per_strip + (r & 7) + (DOWN ? 16 * b : 0);
+            const gbytes p = (b ? weight_rows1 : weight_rows0) + (size_t)n * ex.row_bytes;
+            issue_weight_lines<LK, CPW, FMT>(dst, p, 8 * ex.row_bytes, ((sr % rounds) * WPS + kw) * CPW, ncp, q + 4 * (r >> 3));
+        } else {
+            const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
+            const gbytes p = (b ? weight_rows1 : weight_rows0) + (size_t)n * ex.row_bytes;
+            issue_weights<LK, CPW, FMT>(dst, p, ((sr % rounds) * WPS + kw) * CPW, ncp, q);
+        }
     };
     // Quantized formats: the group scales of the steps [t0, t0 + NST), one per chunk (a chunk never crosses a
     // group).  They travel apart from the weight stages, a whole loop iteration ahead and issued before that
@@ -529,7 +612,8 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
             if (n < 256) g_steps[DOWN][blockIdx.x >> 6][n] = wall_clock64() | ((unsigned long long)FMT << 60) | ((unsigned long long)(t == 0) << 59);
         }
 #endif
-        multiply<LK, CPW, FMT, MT>(cur, x, bias, sc, c0, ncp, acc[b]);
+        if constexpr (kLines<LK, CPW, FMT, FAST>) multiply<LK, CPW, FMT, MT>(settle_lines<LK, CPW, FMT>(cur, c0, ncp), x, bias, sc, c0, ncp, acc[b]);
+        else multiply<LK, CPW, FMT, MT>(cur, x, bias, sc, c0, ncp, acc[b]);
         if (b == 0 || rnd != rounds - 1) return;
         // the strip pairs of this batch are complete: park the partial sums (a clamped duplicate is dropped)
         const bool live = s_lo + batch * SPP + g < s_hi;
