@@ -394,7 +394,7 @@ def main():
         stream.synchronize()
         spread = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_spread)]) * 1e3
 
-        # what a plain read-only kernel of the same launch shape reaches on this device: regions of the size
+        # what a read-only kernel of the same launch shape and load policy reaches on this device: regions of the size
         # of the gate/up launch's bytes, rotating over 2.25 GiB so that nothing comes from the last-level cache
         probe_mib = 192
         probe_buf = torch.ones(12 * probe_mib << 20, dtype=torch.uint8, device="cuda")
@@ -427,7 +427,7 @@ def main():
                                            "shared expert, x, logits, y and the routing arrays, over the wall-clock "
                                            "time of a layer call (all kernels and the gaps between them)"},
                     "read_probe_GBps": probe_gbs, "frac_of_read_probe": achieved / probe_gbs,
-                    "read_probe": "dx_probe_read: 192 MiB per launch, read-only, same launch shape, cold regions"}
+                    "read_probe": "dx_probe_read: 192 MiB per launch, read-only, same launch shape and load policy (whole lines, non-temporal), cold regions"}
     else:
         routed = False
         achieved = flops_per_launch / (gate_up_us * 1e-6) / 1e12

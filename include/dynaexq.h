@@ -306,10 +306,11 @@ typedef struct {
                            between them: what an event pair itself adds to each figure above */
 } dx_profile;
 dx_status dx_set_profiling(dx_ctx *ctx, int enable);
-/* Measurement aid: a plain streaming read of `bytes` bytes of device memory
+/* Measurement aid: a streaming read of `bytes` bytes of device memory
  * (whole MiB, 16-byte aligned) on the compute stream, in the launch shape of the
  * decode kernels (one 512-thread block per compute unit, eight 16-byte loads in
- * flight per thread).  Nothing is written.  Timed by the caller, it gives the
+ * flight per thread, whole lines per load instruction, non-temporal hint: the
+ * fastest read this device was found to do).  Nothing is written.  Timed by the caller, it gives the
  * bandwidth a read-only kernel reaches on this device, next to which the
  * benchmark reports what the expert kernels achieve. */
 dx_status dx_probe_read(dx_ctx *ctx, const void *buf /* dev */, uint64_t bytes);

@@ -142,21 +142,21 @@ constexpr int kMaxExperts = 1024 + 1; // routed + shared
 // build, 30B- and 80B-shaped decode layers, a dozen routing draws each) to
 //   time = runs * c_run + sum over the block's strip pairs of c(format, token tiles):
 // a bf16 pair for up to 16 tokens is 32 units; the same pair for two token tiles multiplies and finishes
-// twice as much (1.22x gate/up, 1.29x down); a quantized pair is a quarter of the bytes or less but carries
-// the same per-step work (expansion, barrier, reduction), 0.43x for one tile and 0.7x to 0.75x for two --
+// twice as much (1.25x gate/up, 1.35x down); a quantized pair is a quarter of the bytes or less but carries
+// the same per-step work (expansion, barrier, reduction), 0.47x for one tile and 0.8x for two --
 // weighed by time, not bytes.  int2 pairs (an eighth of the bytes, the same per-step work) are taken a
 // little below the int4 ones.
 // A run that starts on a new expert pays for the token rows and a cold pipeline (3 to 4 us: one bf16
 // gate/up pair, almost three down pairs): every expert's range begins with kRunUnits units that carry no
 // strips, so the block that holds an expert boundary gets correspondingly fewer strips.
 template <bool DOWN>
-constexpr uint32_t kRunUnits = DOWN ? 88 : 40;
+constexpr uint32_t kRunUnits = DOWN ? 88 : 42;
 template <bool DOWN>
 __device__ __forceinline__ uint32_t units_of(uint32_t fmt, int m)
 {
     const bool two = m > 16;
-    if (fmt == DX_FMT_BF16) return two ? (DOWN ? 41 : 40) : 32;
-    const uint32_t q = two ? (DOWN ? 24 : 23) : (DOWN ? 13 : 14);
+    if (fmt == DX_FMT_BF16) return two ? (DOWN ? 43 : 40) : 32;
+    const uint32_t q = two ? (DOWN ? 26 : 25) : 15;
     return fmt == DX_FMT_INT4G ? q : q - 3;
 }
 
@@ -606,7 +606,7 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
         const int batch = sr / rounds, rnd = sr % rounds;
         const int c0 = (rnd * WPS + kw) * CPW;
         if (rounds > 1 && b == 0) fetch_tokens(c0);
-#ifdef DX_TRACE
+#ifdef DX_TRACE_STEPS
         if (threadIdx.x == 0 && (blockIdx.x & 63) == 37) {
             const unsigned int n = g_nsteps[DOWN][blockIdx.x >> 6]++;
             if (n < 256) g_steps[DOWN][blockIdx.x >> 6][n] = wall_clock64() | ((unsigned long long)FMT << 60) | ((unsigned long long)(t == 0) << 59);

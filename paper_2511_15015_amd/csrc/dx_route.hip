@@ -180,19 +180,22 @@ __global__ void k_fill_u64(unsigned long long *p, size_t n, unsigned long long v
     if (i < n) p[i] = v;
 }
 
-// Measurement aid: a plain streaming read.  Block b reads the 1 MiB units b, b + grid, ...; 16 bytes per
-// thread and load, eight loads in flight per thread.  What it reads is folded into a value that is never
-// equal to the magic number, so the loads cannot be dropped and nothing is written.
+// Measurement aid: a streaming read as fast as this chip does one (whole lines per load instruction,
+// non-temporal hint, as the decode kernels' weight stream).  Block b reads the 1 MiB units b, b + grid, ...;
+// 16 bytes per thread and load, eight loads in flight per thread.  What it reads is folded into a value that
+// is never equal to the magic number, so the loads cannot be dropped and nothing is written.
 __global__ __launch_bounds__(512) void k_probe_read(const char *__restrict__ p, int n_units, unsigned *sink)
 {
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
     constexpr size_t kUnit = 1u << 20;
-    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    u32x4 acc = {0u, 0u, 0u, 0u};
     for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
         const char *base = p + (size_t)u * kUnit + threadIdx.x * 16;
         for (size_t o = 0; o < kUnit; o += (size_t)8 * 512 * 16) {
-            uint4 v[8];
+            u32x4 v[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4 *>(base + o + (size_t)i * 512 * 16);
+            for (int i = 0; i < 8; ++i)
+                v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + o + (size_t)i * 512 * 16));
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 acc.x ^= v[i].x; acc.y ^= v[i].y; acc.z ^= v[i].z; acc.w ^= v[i].w;
