@@ -11,27 +11,31 @@
 // bandwidth-bound.  What decides the achieved bandwidth on this chip is that
 // every compute unit streams for the whole duration of the kernel, so:
 //   - Persistent grid, one block of 8 wavefronts per compute unit.  The work
-//     is the list of (activated expert, 32-token block, pair of 16-row weight
-//     strips), weighed in cost units (units_of, kRunUnits below);
-//     block b takes the pairs that start in units [b*U/G, (b+1)*U/G).  Every
-//     block derives the same partition from `offsets` and the handles'
-//     formats in its prologue (a block-wide scan): no atomics, no work queue.
+//     is the list of (activated expert, 32-token block, strip of 16 weight
+//     rows: 16 rows of W_down, or 8 rows of W_gate with the same 8 of W_up),
+//     weighed in cost units (units_of, kRunUnits below); block b takes the
+//     strips that start in units [b*U/G, (b+1)*U/G).  Every block derives
+//     the same partition from `offsets` and the handles' formats in its
+//     prologue (a block-wide scan): no atomics, no work queue.
 //   - The 8 wavefronts of a block split the K extent of a strip between them
 //     (wavefront kw owns CPW consecutive K-chunks of 4*LK elements), so a
 //     whole strip is in flight at once and the following ones are prefetched
-//     into further register stages while this one is multiplied.  When K is
-//     short, the block works on several strip pairs side by side.  Partial
-//     sums meet in LDS, are added in a fixed order and finished (SwiGLU, or
-//     the store of the down output) by all threads of the block.
+//     into further register stages while this one is multiplied.  Strips go
+//     in pairs (two accumulators, one barrier per pair); when K is short,
+//     the block works on several pairs side by side.  Partial sums meet in
+//     LDS, are added in a fixed order and finished (SwiGLU, or the store of
+//     the down output) by all threads of the block.
 //   - The token rows (A operand of v_mfma_f32_16x16x32_bf16) only depend on
 //     the expert and the K-chunk, so each wavefront keeps its fragments in
 //     registers for all strips of a run: after the first strip, weights are
 //     the only global traffic.
-//   - Lane (r = lane%16, q = lane/16) owns weight row r.  bf16: step j of a
-//     chunk takes elements 32j + 8q .. +7 (four lanes of a row read 64
-//     contiguous bytes per instruction).  int4 / int2: the lane takes the LK
-//     consecutive elements at q*LK (one 16-byte / 8-byte load for LK = 32).
-//     Token fragments use the same K ownership, which makes either order valid.
+//   - Lane (r = lane%16, q = lane/16) owns tile row r.  bf16: step j of a
+//     chunk takes elements 32j + 8q .. +7.  int4 / int2: the lane takes the
+//     LK consecutive elements at q*LK (one 16-byte / 8-byte piece for LK =
+//     32).  Token fragments use the same K ownership, which makes either
+//     order valid.  Where the sizes allow it the loads themselves cover whole
+//     128-byte lines of 8 rows and a DPP move sorts the pieces into this
+//     ownership (see kLines).
 //   - Quantized weights are expanded to exact small bf16 integers; a K-chunk
 //     never crosses a quantization group, so the group's scale multiplies the
 //     chunk's fp32 partial sums once (q*s is never rounded).
@@ -140,17 +144,17 @@ constexpr int kThreads = 64 * kWaves; // 512
 constexpr int kMaxExperts = 1024 + 1; // routed + shared
 // Cost units of the partition, from a fit of the blocks' measured times (per-block time stamps of a debug
 // build, 30B- and 80B-shaped decode layers, a dozen routing draws each) to
-//   time = runs * c_run + sum over the block's strip pairs of c(format, token tiles):
-// a bf16 pair for up to 16 tokens is 32 units; the same pair for two token tiles multiplies and finishes
-// twice as much (1.25x gate/up, 1.35x down); a quantized pair is a quarter of the bytes or less but carries
-// the same per-step work (expansion, barrier, reduction), 0.47x for one tile and 0.8x for two --
-// weighed by time, not bytes.  int2 pairs (an eighth of the bytes, the same per-step work) are taken a
+//   time = runs * c_run + sum over the block's strips of c(format, token tiles):
+// a bf16 strip for up to 16 tokens is 32 units; the same strip for two token tiles multiplies and finishes
+// twice as much (1.25x gate/up, 1.35x down); a quantized strip is a quarter of the bytes or less but
+// carries the same per-step work (expansion, barrier, reduction), 0.47x for one tile and 0.8x for two --
+// weighed by time, not bytes.  int2 strips (an eighth of the bytes, the same per-step work) are taken a
 // little below the int4 ones.
-// A run that starts on a new expert pays for the token rows and a cold pipeline (3 to 4 us: one bf16
-// gate/up pair, almost three down pairs): every expert's range begins with kRunUnits units that carry no
+// A run that starts on a new expert pays for the token rows and a cold pipeline (3 to 5 us: two to three
+// bf16 gate/up strips, five down strips): every expert's range begins with kRunUnits units that carry no
 // strips, so the block that holds an expert boundary gets correspondingly fewer strips.
 template <bool DOWN>
-constexpr uint32_t kRunUnits = DOWN ? 88 : 42;
+constexpr uint32_t kRunUnits = DOWN ? 176 : 84;
 template <bool DOWN>
 __device__ __forceinline__ uint32_t units_of(uint32_t fmt, int m)
 {
@@ -165,7 +169,7 @@ __device__ __forceinline__ uint32_t units_of(uint32_t fmt, int m)
 __device__ unsigned long long g_trace[2][8192][4];
 __device__ unsigned long long g_steps[2][4][256];
 __device__ unsigned int g_nsteps[2][4];
-__device__ unsigned int g_mix[2][8192][8]; // per block: runs, then strip pairs by (format != bf16) * 2 + (second token tile)
+__device__ unsigned int g_mix[2][8192][8]; // per block: runs, then strips by (format != bf16) * 2 + (second token tile)
 #endif
 
 // element offset inside a chunk of MFMA step j for lane quarter q
@@ -210,11 +214,12 @@ __device__ __forceinline__ T line_load(const DX_GLOBAL T *p)
 template <int LK, int CPW, int FMT, bool FAST>
 constexpr bool kLines = LK == 32 && (FMT == 0 || (FMT == 1 && CPW == 2 && FAST));
 
-// Line-shaped loads of one strip: `row_lo` is the strip's row r % 8, `half_rows` the bytes from there to row
-// 8 + r % 8, `piece` = q + 4 * (r / 8).  Stage register n of chunk i then holds load (line n / 2, half n % 2)
-// (bf16) resp. chunk register i holds the load of half i (int4) until settle_lines sorts them out.
+// Line-shaped loads of one strip: `row_lo` is row r % 8 of the strip's lower eight rows, `row_hi` row r % 8
+// of its upper eight (in a gate/up strip another matrix), `piece` = q + 4 * (r / 8).  Stage register n of
+// chunk i then holds load (line n / 2, half n % 2) (bf16) resp. chunk register i holds the load of half i
+// (int4) until settle_lines sorts them out.
 template <int LK, int CPW, int FMT>
-__device__ __forceinline__ void issue_weight_lines(wstage<LK, CPW, FMT> &st, gbytes row_lo, size_t half_rows, int c0,
+__device__ __forceinline__ void issue_weight_lines(wstage<LK, CPW, FMT> &st, gbytes row_lo, gbytes row_hi, int c0,
                                                    int nc, int piece)
 {
     if constexpr (FMT == 0) {
@@ -223,14 +228,14 @@ __device__ __forceinline__ void issue_weight_lines(wstage<LK, CPW, FMT> &st, gby
             if (c0 + i < nc) { // wavefront-uniform
 #pragma unroll
                 for (int n = 0; n < 4; ++n)
-                    st.w[i][n] = line_load(reinterpret_cast<gvec16>(row_lo + (n & 1) * half_rows + (size_t)(c0 + i) * 256 +
+                    st.w[i][n] = line_load(reinterpret_cast<gvec16>(((n & 1) ? row_hi : row_lo) + (size_t)(c0 + i) * 256 +
                                                                    128 * (n >> 1) + 16 * piece));
             }
         }
     } else {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const u32x4 t = line_load(reinterpret_cast<gvec16>(row_lo + h * half_rows + (size_t)c0 * 64 + 16 * piece));
+            const u32x4 t = line_load(reinterpret_cast<gvec16>((h ? row_hi : row_lo) + (size_t)c0 * 64 + 16 * piece));
             st.wq[h][0] = t.x; st.wq[h][1] = t.y; st.wq[h][2] = t.z; st.wq[h][3] = t.w;
         }
     }
@@ -418,9 +423,16 @@ struct expert_ctx {
     lds_ints perm_lds; // the permutation in LDS when the kernel routed itself, else null (a.perm is used)
 };
 
-// Add up the partial sums of the strip pairs sb .. sb+live_groups-1 in a fixed order and finish them:
-// gate/up -> H = silu(gate) * up (bf16); down -> the two 16-row halves of O (fp32).  All threads.
-// Element (group gg, tile mt, accumulator lane L, component i) is token 4*(L/16)+i, column L%16.
+// Strips.  The unit of work is a strip of 16 weight rows against all of K: for the down projection rows
+// 16s .. 16s+15 of W_down (16 columns of O); for gate/up the rows 8s .. 8s+7 of W_gate as tile rows 0..7 and
+// the same rows of W_up as tile rows 8..15 (8 columns of H: silu(gate) * up pairs column c with column
+// c + 8 of the same accumulator).  Strips are worked through in pairs (two accumulators, one barrier and
+// one finish per pair); a run of an odd number of strips ends with half a pair.
+//
+// Add up the partial sums of the pairs that start at strips sb, sb + 2, ... (live_groups of them, side by
+// side across the wavefront groups) in a fixed order and finish the strips below h_hi:
+// gate/up -> H = silu(gate) * up (bf16); down -> O (fp32 or bf16).  All threads.
+// Element (group gg, tile mt, accumulator lane L, component i) is token 4*(L/16)+i, tile column L%16.
 // (slot, row of O) of the output elements a thread finishes: idx = threadIdx.x + n * kThreads has the
 // same idx % (MT * 256) for every n, so both are fixed for a whole run and the row lookup in the
 // permutation happens once, off the critical path of the first finish.
@@ -436,13 +448,16 @@ __device__ __forceinline__ void finish_target(const dx_fwd_args &a, const expert
 
 template <bool DOWN, int MT>
 __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_ctx &ex, int slot, int orow, int sb,
-                                             int live_groups, int WPS, const float *redf)
+                                             int live_groups, int WPS, int h_hi, const float *redf)
 {
-    const int rows_per_strip = DOWN ? 32 : 16;
     if (slot >= ex.m) return;
     for (int idx = threadIdx.x; idx < live_groups * MT * 256; idx += kThreads) {
         const int gg = idx / (MT * 256), rem = idx % (MT * 256);
         const int mt = rem / 256, L = rem & 63, i = (rem >> 6) & 3;
+        // down: the thread adds up column L%16 of both strips of the pair; gate/up: column L%16 of the pair's
+        // 16 columns of H lies in strip (L%16)/8, its gate sum in tile column L%8 and its up sum 8 columns on
+        const int first = DOWN ? 0 : (L >> 3) & 1, second = DOWN ? 1 : first;
+        const int l0 = DOWN ? L : (L & 0x37), l1 = DOWN ? L : l0 + 8;
         // the partial sums are read four wavefronts at a time before they are added (in the order of the
         // wavefronts): one LDS round trip per four instead of one each; past WPS a duplicate is read and
         // not added
@@ -452,9 +467,9 @@ __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int ww = w0 + u < WPS ? w0 + u : WPS - 1;
-                const float *base = redf + (((gg * WPS + ww) * 4) * 64 + L) * 4 + i;
-                p0[u] = base[(0 * 2 + mt) * 64 * 4];
-                p1[u] = base[(1 * 2 + mt) * 64 * 4];
+                const float *base = redf + ((gg * WPS + ww) * 4) * 64 * 4 + i;
+                p0[u] = base[((first * 2 + mt) * 64 + l0) * 4];
+                p1[u] = base[((second * 2 + mt) * 64 + l1) * 4];
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -464,24 +479,28 @@ __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_
                 }
             }
         }
-        const int n = (sb + gg) * rows_per_strip + (L & 15);
+        const int s0 = sb + 2 * gg; // the pair's first strip (below h_hi: the group is live)
         if constexpr (DOWN) {
+            const int n = s0 * 16 + (L & 15);
+            const bool both = s0 + 1 < h_hi;
             if (a.o_bf16) {
                 dx_bf16 *ob = reinterpret_cast<dx_bf16 *>(a.o) + (size_t)orow * a.d + n;
                 ob[0] = (dx_bf16)float_to_bf16_rne(v0);
-                ob[16] = (dx_bf16)float_to_bf16_rne(v1);
+                if (both) ob[16] = (dx_bf16)float_to_bf16_rne(v1);
             } else {
                 a.o[(size_t)orow * a.d + n] = v0;
-                a.o[(size_t)orow * a.d + n + 16] = v1;
+                if (both) a.o[(size_t)orow * a.d + n + 16] = v1;
             }
         } else {
-            const float hv = v0 / (1.f + expf(-v0)) * v1;
-            a.h[(size_t)(ex.seg0 + slot) * a.fmax + n] = (dx_bf16)float_to_bf16_rne(hv);
+            if (s0 + first < h_hi) {
+                const float hv = v0 / (1.f + expf(-v0)) * v1;
+                a.h[(size_t)(ex.seg0 + slot) * a.fmax + s0 * 8 + (L & 15)] = (dx_bf16)float_to_bf16_rne(hv);
+            }
         }
     }
 }
 
-// One run: strips [s_lo, s_hi) of one expert for one block of up to 32 tokens (mb).
+// One run: strips [h_lo, h_hi) of one expert for one block of up to 32 tokens (mb).
 // All kThreads threads of the block execute this with identical arguments.
 //
 // FAST (K is one round of whole chunks: K / (4*LK) = WPS * CPW with WPS <= 8): the steady-state loop
@@ -489,7 +508,7 @@ __device__ __forceinline__ void finish_batch(const dx_fwd_args &a, const expert_
 // strip index is clamped, so the last iterations of a ragged run fetch a duplicate) -- which lets the
 // compiler wait for exactly the loads it is about to use and keep the prefetch in flight.
 template <int LK, int CPW, bool DOWN, int FMT, int MT, bool FAST>
-__device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ctx &ex, int mb, int s_lo, int s_hi,
+__device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ctx &ex, int mb, int h_lo, int h_hi,
                                            f32x4 (*red)[kWaves][4][64], int &pb)
 {
     constexpr int CHUNK = 4 * LK;
@@ -502,17 +521,18 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     const int rounds = FAST ? 1 : (per + WPS - 1) / WPS;
     const int g = wave / WPS, kw = wave % WPS;
     const bool idle = g >= SPP;
-    const int rows_per_strip = DOWN ? 32 : 16;
-    const int nbatch = (s_hi - s_lo + SPP - 1) / SPP;
+    const int npairs = (h_hi - h_lo + 1) / 2;
+    const int nbatch = (npairs + SPP - 1) / SPP;
     const int nsteps = nbatch * rounds;
 
     int fin_slot, fin_orow;
     finish_target<DOWN, MT>(a, ex, mb, fin_slot, fin_orow);
     auto finish = [&](int batch) {
         __syncthreads();
-        const int sb = s_lo + batch * SPP;
-        const int live_groups = (s_hi - sb) < SPP ? (s_hi - sb) : SPP;
-        finish_batch<DOWN, MT>(a, ex, fin_slot, fin_orow, sb, live_groups, WPS,
+        const int sb = h_lo + 2 * batch * SPP;
+        const int left = (h_hi - sb + 1) / 2; // pairs from sb on
+        const int live_groups = left < SPP ? left : SPP;
+        finish_batch<DOWN, MT>(a, ex, fin_slot, fin_orow, sb, live_groups, WPS, h_hi,
                                reinterpret_cast<const float *>(&red[pb][0][0][0]));
         pb ^= 1; // the other half of `red` is free: its readers passed the barrier above
     };
@@ -532,8 +552,8 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
         if constexpr (FMT != 0) prepare_quant_tokens<LK, CPW, MT, FMT>(x, bias, c0, ncp);
     };
 
-    // A step is one 16-row strip: step t = (batch * rounds + round) * 2 + b, b = 0 the first strip of the
-    // pair (gate rows / lower 16 down rows), b = 1 the second (up rows / upper 16 down rows).  NST
+    // A step is one strip: step t = (batch * rounds + round) * 2 + b, b = 0 the first strip of the pair,
+    // b = 1 the second; the last pair of a run may lack its second strip (no load, no multiply).  NST
     // register stages: the strip of step t + NST - 1 is fetched while step t is multiplied.  A quantized
     // strip is a quarter of the bytes or less, so it gets a deeper pipeline (four stages; with six or eight
     // the runs of a decode batch, a dozen steps each, spend most of their steps outside the steady loop,
@@ -542,18 +562,24 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     const int nhalf = 2 * nsteps;
     wstage<LK, CPW, FMT> st[NST];
     const gbytes weight_rows0 = ex.w0, weight_rows1 = ex.w1;
+    // the strip of step t (past the end of the run for the missing half of the last pair and for the pairs of
+    // wavefront groups without one in the last batch)
+    auto strip_of = [&](int t) { return h_lo + 2 * (((t >> 1) / rounds) * SPP + g) + (t & 1); };
+    // row r of a strip's tile in the weight (scale) matrices: row index and which of the two matrices
     auto issue_step = [&](int t, wstage<LK, CPW, FMT> &dst) {
-        const int b = t & 1, sr = t >> 1;
-        int s = s_lo + (sr / rounds) * SPP + g;
-        s = s < s_hi ? s : s_hi - 1; // ragged tail: fetch a duplicate rather than branch
+        const int sr = t >> 1;
+        int s = strip_of(t);
+        s = s < h_hi ? s : h_hi - 1; // ragged tail: fetch a duplicate rather than branch
+        const int c0 = ((sr % rounds) * WPS + kw) * CPW;
         if constexpr (kLines<LK, CPW, FMT, FAST>) {
-            const int n = s * rows_per_strip + (r & 7) + (DOWN ? 16 * b : 0);
-            const gbytes p = (b ? weight_rows1 : weight_rows0) + (size_t)n * ex.row_bytes;
-            issue_weight_lines<LK, CPW, FMT>(dst, p, 8 * ex.row_bytes, ((sr % rounds) * WPS + kw) * CPW, ncp, q + 4 * (r >> 3));
+            const size_t lo = (size_t)((DOWN ? 16 : 8) * s + (r & 7)) * ex.row_bytes;
+            const gbytes p_lo = weight_rows0 + lo;
+            const gbytes p_hi = DOWN ? p_lo + 8 * ex.row_bytes : weight_rows1 + lo;
+            issue_weight_lines<LK, CPW, FMT>(dst, p_lo, p_hi, c0, ncp, q + 4 * (r >> 3));
         } else {
-            const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
-            const gbytes p = (b ? weight_rows1 : weight_rows0) + (size_t)n * ex.row_bytes;
-            issue_weights<LK, CPW, FMT>(dst, p, ((sr % rounds) * WPS + kw) * CPW, ncp, q);
+            const gbytes p = DOWN ? weight_rows0 + (size_t)(16 * s + r) * ex.row_bytes
+                                  : (r < 8 ? weight_rows0 : weight_rows1) + (size_t)(8 * s + (r & 7)) * ex.row_bytes;
+            issue_weights<LK, CPW, FMT>(dst, p, c0, ncp, q);
         }
     };
     // Quantized formats: the group scales of the steps [t0, t0 + NST), one per chunk (a chunk never crosses a
@@ -568,11 +594,11 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
         if constexpr (FMT != 0) {
 #pragma unroll
             for (int u = 0; u < NST; ++u) {
-                const int b = u & 1, sr = (t0 >> 1) + (u >> 1); // step t0 + u
-                int s = s_lo + (sr / rounds) * SPP + g;
-                s = s < s_hi ? s : s_hi - 1;
-                const int n = s * rows_per_strip + r + (DOWN ? 16 * b : 0);
-                const gbf16 sp = (b ? scale_rows1 : scale_rows0) + (size_t)n * ex.G;
+                const int sr = (t0 >> 1) + (u >> 1); // step t0 + u
+                int s = strip_of(t0 + u);
+                s = s < h_hi ? s : h_hi - 1;
+                const gbf16 sp = DOWN ? scale_rows0 + (size_t)(16 * s + r) * ex.G
+                                      : (r < 8 ? scale_rows0 : scale_rows1) + (size_t)(8 * s + (r & 7)) * ex.G;
                 const int c0 = ((sr % rounds) * WPS + kw) * CPW;
                 if (CPW == 2 && a.group == CHUNK && c0 + 1 < ncp) {
                     // the two chunks' scales are neighbours (c0 is even, a scale row starts 4-byte aligned)
@@ -612,11 +638,13 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
             if (n < 256) g_steps[DOWN][blockIdx.x >> 6][n] = wall_clock64() | ((unsigned long long)FMT << 60) | ((unsigned long long)(t == 0) << 59);
         }
 #endif
-        if constexpr (kLines<LK, CPW, FMT, FAST>) multiply<LK, CPW, FMT, MT>(settle_lines<LK, CPW, FMT>(cur, c0, ncp), x, bias, sc, c0, ncp, acc[b]);
-        else multiply<LK, CPW, FMT, MT>(cur, x, bias, sc, c0, ncp, acc[b]);
+        if (strip_of(t) < h_hi) { // wavefront-uniform; a strip past the end was not fetched either, or is a duplicate
+            if constexpr (kLines<LK, CPW, FMT, FAST>) multiply<LK, CPW, FMT, MT>(settle_lines<LK, CPW, FMT>(cur, c0, ncp), x, bias, sc, c0, ncp, acc[b]);
+            else multiply<LK, CPW, FMT, MT>(cur, x, bias, sc, c0, ncp, acc[b]);
+        }
         if (b == 0 || rnd != rounds - 1) return;
-        // the strip pairs of this batch are complete: park the partial sums (a clamped duplicate is dropped)
-        const bool live = s_lo + batch * SPP + g < s_hi;
+        // the strip pairs of this batch are complete: park the partial sums (zeros for a missing second strip)
+        const bool live = strip_of(t - 1) < h_hi;
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
@@ -631,7 +659,7 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     // the routing arrays, so that they are in flight while the token rows are looked up
 #pragma unroll
     for (int i = 0; i < NST - 1; ++i)
-        if (i < nhalf) issue_step(i, st[i]);
+        if (i < nhalf && strip_of(i) < h_hi) issue_step(i, st[i]);
     issue_scales(0, sc_cur);
 
     // token rows of this run (A operand): row r of tile mt
@@ -675,7 +703,7 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
 #pragma unroll
         for (int i = 0; i < NST; ++i) {
             if (t + i < nhalf) {
-                if (t + i + NST - 1 < nhalf) issue_step(t + i + NST - 1, st[(i + NST - 1) % NST]);
+                if (t + i + NST - 1 < nhalf && strip_of(t + i + NST - 1) < h_hi) issue_step(t + i + NST - 1, st[(i + NST - 1) % NST]);
                 do_step(t + i, st[i], sc_cur[i], i & 1);
             }
         }
@@ -704,7 +732,7 @@ __device__ __forceinline__ void build_partition(const dx_fwd_args &a, partition_
         const int m = e == a.E ? a.T : a.offsets[e + 1] - a.offsets[e];
         return m <= a.m_small ? m : 0;
     };
-    auto strips_of = [&](int e) { return DOWN ? a.d / 32 : (e == a.E ? a.shared_f : a.f) / 16; };
+    auto strips_of = [&](int e) { return DOWN ? a.d / 16 : (e == a.E ? a.shared_f : a.f) / 8; };
     auto fmt_of = [&](int e) { return e == a.E ? (uint32_t)DX_FMT_BF16 : a.table[e].fmt; };
     const int R = (nE + kThreads - 1) / kThreads; // experts per thread, consecutive
     uint32_t mine[3] = {0, 0, 0}, local = 0;
@@ -756,7 +784,7 @@ __device__ __forceinline__ void build_partition(const dx_fwd_args &a, partition_
     __syncthreads();
 }
 
-// This block's share: the strip pairs whose first unit lies in [ub0, ub1), run by run.
+// This block's share: the strips whose first unit lies in [ub0, ub1), run by run.
 template <int LK, int CPW, bool DOWN, bool FAST>
 __device__ __forceinline__ void run_share(const dx_fwd_args &a, const partition_lds &pl, uint32_t ub0, uint32_t ub1,
                                           lds_ints perm_lds, f32x4 (*red)[kWaves][4][64])
@@ -782,11 +810,11 @@ __device__ __forceinline__ void run_share(const dx_fwd_args &a, const partition_
         ex.w1 = (gbytes)(DOWN ? hd.w_down : hd.w_up);
         ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
         ex.s1 = (gbf16)(DOWN ? hd.s_down : hd.s_up);
-        const int spe = DOWN ? a.d / 32 : fe / 16;
+        const int spe = DOWN ? a.d / 16 : fe / 8; // strips per token block of this expert
         const uint32_t wgt = units_of<DOWN>((uint32_t)ex.fmt, ex.m);
         const uint32_t lo = (ub0 > pl.cum[e] ? ub0 : pl.cum[e]) - pl.cum[e];
         const uint32_t hi = (ub1 < pl.cum[e + 1] ? ub1 : pl.cum[e + 1]) - pl.cum[e];
-        // strip pairs (flattened over token blocks) whose first unit lies in [lo, hi); pair i starts
+        // strips (flattened over token blocks) whose first unit lies in [lo, hi); strip i starts
         // kRunUnits + i * wgt units into the expert's range
         constexpr uint32_t kRun = kRunUnits<DOWN>;
         const uint32_t lo_p = lo > kRun ? lo - kRun : 0, hi_p = hi > kRun ? hi - kRun : 0;
@@ -944,7 +972,7 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
         if (e < a.E) cnt[i] = m[i] = __popcll(lds_mask[e]);
         else if (e == a.E && a.shared) m[i] = a.T;
         if (m[i] > 0)
-            mine[i] = ((m[i] + 31) / 32) * ((e == a.E ? a.shared_f : a.f) / 16) * (int)units_of<false>(fmt[i], m[i]) +
+            mine[i] = ((m[i] + 31) / 32) * ((e == a.E ? a.shared_f : a.f) / 8) * (int)units_of<false>(fmt[i], m[i]) +
                       (int)kRunUnits<false>;
         cnt_local += cnt[i];
         mine_local += mine[i];
