@@ -926,7 +926,7 @@ __global__ __launch_bounds__(kThreads) void k_stream_routed(dx_fwd_args a, dx_ro
         for (int p = 0; p < 2; ++p) {
             if (p == 0 || second) {
                 const int t = t0 + 32 * p;
-                dx_route_core::load_logits<NV>(r.logits + (size_t)(t < a.T ? t : a.T - 1) * a.E, c, a.E, v[p]);
+                dx_route_core::load_logits_rows16<NV>(r.logits + (size_t)(t < a.T ? t : a.T - 1) * a.E, c, a.E, v[p]);
             }
         }
         __syncthreads(); // the masks are clear

@@ -195,9 +195,41 @@ __device__ __forceinline__ float weight_rows16(int lgk, int k, int lane)
     return ex / sum;
 }
 
-// Lane c of a row owns the experts NV*c .. NV*c+NV-1 of its token (E <= 16*NV), v[s] is the logit of expert
-// NV*c+s (-inf past the last expert).  Same results as topk_rows: on return lane c < k of a row holds the
-// c-th id of its token and its weight (k <= 16).
+// Which experts lane c of a row owns (E <= 16*NV): slot s is expert 64 * (s / 4) + 4 * c + s % 4, ascending
+// in s.  Four consecutive slots are four consecutive logits, and the row's 16 lanes together read 256
+// consecutive bytes of the token's logits per 16-byte load (consecutive ownership, NV logits per lane,
+// would touch 16 different lines per load instruction and come back to each of them NV / 4 times).
+__device__ __forceinline__ int rows16_expert(int c, int s) { return 64 * (s >> 2) + 4 * c + (s & 3); }
+
+// v[s] = the logit of expert rows16_expert(c, s) of the token whose logits start at `row` (-inf past the last
+// expert E), every load unconditional: 16-byte loads when the row is a whole number of them and starts on a
+// 16-byte boundary (E % 4 == 0 and an aligned array: then every token's row does), else single loads on
+// clamped indices.
+template <int NV>
+__device__ __forceinline__ void load_logits_rows16(const float *row, int c, int E, float (&v)[NV])
+{
+    static_assert(NV % 4 == 0, "whole groups of four slots");
+    float raw[NV];
+    if ((E & 3) == 0 && (reinterpret_cast<uintptr_t>(row) & 15) == 0) {
+#pragma unroll
+        for (int s = 0; s < NV; s += 4) {
+            const int e = rows16_expert(c, s), e0 = e < E ? e : E - 4;
+            const float4 t = *reinterpret_cast<const float4 *>(row + e0);
+            raw[s] = t.x; raw[s + 1] = t.y; raw[s + 2] = t.z; raw[s + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < NV; ++s) {
+            const int e = rows16_expert(c, s);
+            raw[s] = row[e < E ? e : E - 1];
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < NV; ++s) v[s] = rows16_expert(c, s) < E ? raw[s] : -INFINITY;
+}
+
+// v[s] is the logit of expert rows16_expert(c, s) of the row's token (-inf past the last expert).  Same
+// results as topk_rows: on return lane c < k of a row holds the c-th id of its token and its weight (k <= 16).
 template <int NV>
 __device__ __forceinline__ void topk_rows16(const float (&v)[NV], int k, int lane, int &id, float &wt)
 {
@@ -206,7 +238,7 @@ __device__ __forceinline__ void topk_rows16(const float (&v)[NV], int k, int lan
 #pragma unroll
     for (int s = 0; s < NV; ++s) {
         key[s] = key_of(v[s]);
-        ix[s] = NV * c + s;
+        ix[s] = rows16_expert(c, s);
     }
     int lgk;
     select_rows16<NV>(key, ix, k, c, id, lgk);
@@ -245,7 +277,7 @@ __device__ __forceinline__ void topk_rows16_filtered(const float (&v)[NV], int k
     if (__ballot(__popc(above) > C) != 0ull) { // wavefront-uniform
         int ix[NV];
 #pragma unroll
-        for (int s = 0; s < NV; ++s) ix[s] = NV * c + s;
+        for (int s = 0; s < NV; ++s) ix[s] = rows16_expert(c, s);
         select_rows16<NV>(key, ix, k, c, id, lgk);
     } else {
 #pragma unroll
@@ -258,7 +290,7 @@ __device__ __forceinline__ void topk_rows16_filtered(const float (&v)[NV], int k
             above &= above - 1u;
             const int got = scratch[slot * 64 + lane];
             ck[j] = have ? got : kTakenKey;
-            ci[j] = have ? NV * c + slot : 0x7fffffff;
+            ci[j] = have ? rows16_expert(c, slot) : 0x7fffffff;
         }
         select_rows16<C>(ck, ci, k, c, id, lgk);
     }

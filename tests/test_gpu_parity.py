@@ -814,12 +814,13 @@ def test_route_forward_with_tied_logits(B, LY, dxo):
 
 
 @pytest.mark.parametrize("case", ["coarse grid", "all equal", "favourites are neighbours", "one lane and ties",
-                                  "few above a sea of equals", "second pass"])
+                                  "favourites 64 apart", "few above a sea of equals", "second pass"])
 def test_route_forward_wide_layer_threshold_and_its_fallback(B, LY, dxo, case):
     """Layers of more than 128 experts select through a threshold and a short list per lane, and fall back to
     the plain selection when a lane's list overflows: logits built so that both ways run (many exact ties;
-    every favourite of a token among 32 neighbouring experts; a few distinct values above a constant), all
-    of them against the oracle's ids, weights and permutation."""
+    every favourite of a token among 32 neighbouring experts, or among the 32 experts 64 * g + 4 * c + j that
+    one lane of the selection holds; a few distinct values above a constant), all of them against the oracle's
+    ids, weights and permutation."""
     import dataclasses
     T = 40 if case == "second pass" else 32
     wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=512, k=10, d=256, f=128, group=128)
@@ -838,7 +839,13 @@ def test_route_forward_wide_layer_threshold_and_its_fallback(B, LY, dxo, case):
     elif case == "one lane and ties":
         logits = g.standard_normal((T, wl.E)).astype(np.float32)
         for t in range(T):
-            logits[t, 32 * (t % 16) + np.arange(0, 32, 2)] = 5.0   # sixteen equal favourites in one lane
+            own = (64 * np.arange(8)[:, None] + 4 * (t % 16) + np.arange(4)[None, :]).ravel()
+            logits[t, own[::2]] = 5.0                               # sixteen equal favourites in one lane's set
+    elif case == "favourites 64 apart":
+        logits = g.standard_normal((T, wl.E)).astype(np.float32)
+        for t in range(T):
+            own = (64 * np.arange(8)[:, None] + 4 * (t % 16) + np.arange(4)[None, :]).ravel()
+            logits[t, own[g.permutation(32)[:12]]] += 8.0           # the ten largest inside one lane's set
     elif case == "few above a sea of equals":
         logits = np.zeros((T, wl.E), np.float32)
         for t in range(T):
