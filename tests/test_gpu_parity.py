@@ -278,6 +278,44 @@ def test_forward_c1_mixed_all_hi_all_lo(B, LY, dxo):
         ly.ctx.close()
 
 
+@pytest.mark.parametrize("shift", [16, 80, 112])
+def test_forward_weights_that_start_inside_a_line(B, LY, dxo, shift):
+    """The boundary promises 16-byte alignment only.  The decode kernels fetch weights in pieces that are whole
+    128-byte lines when a matrix starts on a line; here every matrix and scale array of every expert starts
+    `shift` bytes into one (bf16 and int4 versions, d = 2048 so that the line-shaped loads are the ones that
+    run): same bits as with the aligned copies, and the oracle's values."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=24, E=8, k=3, d=2048, f=128, group=128)
+    print(f"weights shifted by {shift} bytes", flush=True)
+    x, logits = W.layer_inputs(wl, seed=41)
+    ly = Layer(B, LY, dxo, wl, [1, 4, 6], seed=41)
+    y_gpu, y_ref = ly.run(x, logits)
+    assert rel_l2(y_gpu, y_ref) <= REL_L2_TOL
+    keep = []
+
+    def moved(t):
+        n = t.numel() * t.element_size()
+        raw = torch.zeros(n + 256, dtype=torch.uint8, device=t.device)
+        base = (-raw.data_ptr()) % 128 + shift                      # `shift` bytes past a line boundary
+        v = raw[base:base + n].view(t.dtype).view(t.shape)
+        v.copy_(t)
+        assert v.data_ptr() % 128 == shift % 128 and v.data_ptr() % 16 == 0
+        keep.append(raw)
+        return v
+
+    lw = ly.lw
+    for e in range(wl.E):
+        if lw.is_hi[e]:
+            h = B.make_handle(B.DX_FMT_BF16, *(moved(m[e]) for m in lw.hi))
+        else:
+            i = lw.lo_slot[e]
+            h = B.make_handle(B.DX_FMT_INT4G, *(moved(q[i]) for q in lw.q), *(moved(sc[i]) for sc in lw.s))
+        ly.ctx.dx_swap_handle(0, e, h)
+    y_moved, _ = ly.run(x, logits)
+    assert np.array_equal(y_moved, y_gpu)
+    ly.ctx.close()
+
+
 @pytest.mark.parametrize("T", [1, 7, 16, 17, 33, 40])
 def test_forward_ragged_token_counts(B, LY, dxo, T):
     import dataclasses
