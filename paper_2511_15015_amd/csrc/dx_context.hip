@@ -244,7 +244,9 @@ extern "C" dx_status dx_create(const dx_config *cfg, void *stream, dx_ctx **out)
         g.top_k > 64 || !group_ok || g.d % g.group || g.f % g.group || g.d % 32 || g.f % 32 ||
         g.shared_f < 0 || g.shared_f % 32 || (g.shared_f && g.shared_f % g.group) || g.max_tokens <= 0 ||
         g.alpha_q16 >= 65536u || (g.hi_fmt != DX_FMT_BF16 && g.hi_fmt != DX_FMT_INT4G) ||
-        (g.hi_fmt == DX_FMT_INT4G && g.group < 64) || (uint64_t)g.max_tokens * (uint64_t)(g.top_k + 1) > 0x7FFFFFFFull) {
+        (g.hi_fmt == DX_FMT_INT4G && g.group < 64) || (uint64_t)g.max_tokens * (uint64_t)(g.top_k + 1) > 0x7FFFFFFFull ||
+        // (the kernels address inside one expert matrix with 32-bit byte offsets)
+        (uint64_t)g.d * (uint64_t)(g.f > g.shared_f ? g.f : g.shared_f) * 2ull > 0xFFFFFFFFull) {
         g_create_err = "dx_create: invalid configuration";
         return DX_ERR_INVALID;
     }

@@ -414,7 +414,7 @@ __device__ __forceinline__ void multiply(const wstage<LK, CPW, FMT> &st, const u
 struct expert_ctx {
     gbytes w0, w1;   // gate/up: the gate and up matrices; down: the down matrix twice
     gbf16 s0, s1;    // their scales (int4)
-    size_t row_bytes;
+    uint32_t row_bytes; // of a weight row (a matrix is smaller than 4 GiB)
     int K;           // contraction length
     int G;           // scale groups per row
     int seg0, m;     // segment in the H/O scratch, tokens
@@ -512,7 +512,10 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
                                            f32x4 (*red)[kWaves][4][64], int &pb)
 {
     constexpr int CHUNK = 4 * LK;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, q = lane >> 4;
+    // (the wavefront's index through readfirstlane: everything derived from it -- its K-part, its strips, the
+    // strips' offsets in the matrices -- is then scalar arithmetic, and the loads take a scalar base plus a
+    // per-lane offset that is computed once per run)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, r = lane & 15, q = lane >> 4;
     const int nc = ex.K / CHUNK;
     // wavefronts per strip pair, strip pairs side by side, K rounds
     const int per = (nc + CPW - 1) / CPW;
@@ -562,6 +565,7 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
     const int nhalf = 2 * nsteps;
     wstage<LK, CPW, FMT> st[NST];
     const gbytes weight_rows0 = ex.w0, weight_rows1 = ex.w1;
+    const uint32_t lane_row8 = (uint32_t)(r & 7) * ex.row_bytes, lane_row16 = (uint32_t)r * ex.row_bytes; // per-lane byte offsets
     // the strip of step t (past the end of the run for the missing half of the last pair and for the pairs of
     // wavefront groups without one in the last batch)
     auto strip_of = [&](int t) { return h_lo + 2 * (((t >> 1) / rounds) * SPP + g) + (t & 1); };
@@ -571,14 +575,14 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
         int s = strip_of(t);
         s = s < h_hi ? s : h_hi - 1; // ragged tail: fetch a duplicate rather than branch
         const int c0 = ((sr % rounds) * WPS + kw) * CPW;
+        const size_t strip_at = (size_t)((DOWN ? 16 : 8) * s) * ex.row_bytes; // scalar
         if constexpr (kLines<LK, CPW, FMT, FAST>) {
-            const size_t lo = (size_t)((DOWN ? 16 : 8) * s + (r & 7)) * ex.row_bytes;
-            const gbytes p_lo = weight_rows0 + lo;
-            const gbytes p_hi = DOWN ? p_lo + 8 * ex.row_bytes : weight_rows1 + lo;
+            const gbytes p_lo = weight_rows0 + strip_at + lane_row8;
+            const gbytes p_hi = DOWN ? weight_rows0 + (strip_at + 8 * ex.row_bytes) + lane_row8 : weight_rows1 + strip_at + lane_row8;
             issue_weight_lines<LK, CPW, FMT>(dst, p_lo, p_hi, c0, ncp, q + 4 * (r >> 3));
         } else {
-            const gbytes p = DOWN ? weight_rows0 + (size_t)(16 * s + r) * ex.row_bytes
-                                  : (r < 8 ? weight_rows0 : weight_rows1) + (size_t)(8 * s + (r & 7)) * ex.row_bytes;
+            const gbytes p = DOWN ? weight_rows0 + strip_at + lane_row16
+                                  : (r < 8 ? weight_rows0 + strip_at : weight_rows1 + strip_at) + lane_row8;
             issue_weights<LK, CPW, FMT>(dst, p, c0, ncp, q);
         }
     };
@@ -597,8 +601,9 @@ __device__ __forceinline__ void run_strips(const dx_fwd_args &a, const expert_ct
                 const int sr = (t0 >> 1) + (u >> 1); // step t0 + u
                 int s = strip_of(t0 + u);
                 s = s < h_hi ? s : h_hi - 1;
-                const gbf16 sp = DOWN ? scale_rows0 + (size_t)(16 * s + r) * ex.G
-                                      : (r < 8 ? scale_rows0 : scale_rows1) + (size_t)(8 * s + (r & 7)) * ex.G;
+                const size_t strip_at = (size_t)((DOWN ? 16 : 8) * s) * ex.G; // scalar
+                const gbf16 sp = DOWN ? scale_rows0 + strip_at + (uint32_t)(r * ex.G)
+                                      : (r < 8 ? scale_rows0 + strip_at : scale_rows1 + strip_at) + (uint32_t)((r & 7) * ex.G);
                 const int c0 = ((sr % rounds) * WPS + kw) * CPW;
                 if (CPW == 2 && a.group == CHUNK && c0 + 1 < ncp) {
                     // the two chunks' scales are neighbours (c0 is even, a scale row starts 4-byte aligned)
@@ -805,7 +810,7 @@ __device__ __forceinline__ void run_share(const dx_fwd_args &a, const partition_
         const int fe = ex.shared ? a.shared_f : a.f;
         ex.K = DOWN ? fe : a.d;
         ex.G = ex.K / a.group;
-        ex.row_bytes = ex.fmt == DX_FMT_BF16 ? (size_t)ex.K * 2 : (ex.fmt == DX_FMT_INT4G ? (size_t)ex.K / 2 : (size_t)ex.K / 4);
+        ex.row_bytes = ex.fmt == DX_FMT_BF16 ? (uint32_t)ex.K * 2 : (ex.fmt == DX_FMT_INT4G ? (uint32_t)ex.K / 2 : (uint32_t)ex.K / 4);
         ex.w0 = (gbytes)(DOWN ? hd.w_down : hd.w_gate);
         ex.w1 = (gbytes)(DOWN ? hd.w_down : hd.w_up);
         ex.s0 = (gbf16)(DOWN ? hd.s_down : hd.s_gate);
