@@ -111,7 +111,10 @@ typedef struct {
  * (L*E routed + L shared entries), the window counters, the routing and
  * forward scratch for max_tokens, a migration stream and two side streams
  * (all at default priority).  A context is not thread-safe: one host thread
- * at a time. */
+ * at a time.  DX_ERR_INVALID for a configuration outside the supported
+ * range: E <= 1024, top_k <= min(E, 64), group in {32, 64, 128} dividing d, f
+ * and shared_f, d, f, shared_f multiples of 32, an expert matrix smaller than
+ * 4 GiB (d * max(f, shared_f) * 2 bytes), max_tokens * (top_k + 1) < 2^31. */
 dx_status dx_create(const dx_config *cfg, void *hip_compute_stream, dx_ctx **out);
 void dx_destroy(dx_ctx *ctx);
 const char *dx_last_error(const dx_ctx *ctx);

@@ -100,3 +100,19 @@ def test_route_static_refuses_sizes_beyond_its_scratch_without_touching_a_gpu(B)
     for T, E, k in [(8192, 1024, 8), (64, 2048, 8), (64, 0, 1), (64, 128, 0), (64, 128, 65), (-1, 128, 8)]:
         assert lib.dx_route_static(None, T, E, k, None, None, None, None, None, None) == B.DX_ERR_INVALID
         assert lib.dx_route_static_last_error().decode().startswith("dx_route_static:")
+
+
+def test_create_refuses_configurations_outside_its_range_without_touching_a_gpu(B):
+    """dx_create checks the configuration before any HIP call: experts beyond the table's range, a group size
+    the kernels do not have, a dimension that is not a multiple of 32 and an expert matrix of 4 GiB (the
+    kernels address inside a matrix with 32-bit byte offsets) are all DX_ERR_INVALID."""
+    import ctypes as C
+    lib = B.load()
+    good = dict(L=1, E=8, d=256, f=128, top_k=2, group=64, shared_f=0, max_tokens=16, window_steps=1, alpha_q16=0,
+                route_updates_hotness=0, hi_fmt=B.DX_FMT_BF16, budget_bytes=0, transient_bytes=0)
+    for change in (dict(E=2000), dict(group=48), dict(d=250), dict(top_k=9), dict(d=65536, f=32768, group=128),
+                   dict(shared_f=65536, d=32768, group=128), dict(max_tokens=0), dict(alpha_q16=65536)):
+        cfg = B.DxConfig(**{**good, **change})
+        out = C.c_void_p()
+        assert lib.dx_create(C.byref(cfg), None, C.byref(out)) == B.DX_ERR_INVALID, change
+        assert not out.value
