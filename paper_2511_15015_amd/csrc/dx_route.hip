@@ -47,8 +47,11 @@ __device__ int block_exclusive_scan(int v, int *lds_wave_tot /*[kWaves]*/, int *
     return base + inc - v;
 }
 
-// One chunk of 64 tokens per block.  NV = consecutive logits held per lane (E <= 64*NV).
-template <int NV>
+// One chunk of 64 tokens per block.
+// ROWS16 (layers of up to 512 experts): a token per 16-lane row, NV logits per lane of the row (E <= 16*NV), so
+// the 16 wavefronts take the chunk's 64 tokens in one pass (the selection code of the decode kernels' routing
+// prologue).  Otherwise a token per wavefront, NV consecutive logits per lane (E <= 64*NV), four passes.
+template <int NV, bool ROWS16>
 __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
     const float *__restrict__ logits, int T, int E, int k, int32_t *__restrict__ ids, float *__restrict__ w,
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
@@ -66,6 +69,23 @@ __global__ __launch_bounds__(kRouteThreads) void k_route_topk(
     if (fused && hotness && (int)threadIdx.x < E) hot_before = hotness[threadIdx.x];
     __syncthreads();
 
+    if constexpr (ROWS16) {
+        static_assert(kChunk == 4 * kWaves, "four tokens per wavefront cover the chunk");
+        const int tt = 4 * wave + (lane >> 4), t = chunk * kChunk + tt, c = lane & 15;
+        if (chunk * kChunk + 4 * wave < T) { // wave-uniform: some row of this wavefront has a token (T > 0)
+            float v[NV];
+            dx_route_core::load_logits_rows16<NV>(logits + (size_t)(t < T ? t : T - 1) * E, c, E, v);
+            int my_id;
+            float my_w;
+            dx_route_core::topk_rows16<NV>(v, k, lane, my_id, my_w);
+            if (t < T && c < k) {
+                ids[(size_t)t * k + c] = my_id;
+                w[(size_t)t * k + c] = my_w;
+                lds_ids[tt * k + c] = my_id;
+                atomicOr(&lds_mask[my_id], 1ull << tt);
+            }
+        }
+    } else
     for (int tt = wave; tt < kChunk; tt += kWaves) {
         const int t = chunk * kChunk + tt;
         if (t >= T) break; // wave-uniform
@@ -255,14 +275,14 @@ __global__ __launch_bounds__(256) void k_router_gemm(const dx_bf16 *__restrict__
     }
 }
 
-template <int NV>
+template <int NV, bool ROWS16>
 hipError_t launch_topk(const float *logits, int T, int E, int k, int32_t *ids, float *w, int32_t *counts,
                        int32_t *offsets, int32_t *perm, unsigned long long *mask, unsigned long long *hotness,
                        int n_chunks, hipStream_t s)
 {
     const int fused = n_chunks == 1;
     size_t lds = (size_t)E * 8 + (size_t)(kChunk * k + kWaves + E) * 4;
-    hipLaunchKernelGGL(k_route_topk<NV>, dim3(n_chunks), dim3(kRouteThreads), lds, s, logits, T, E, k, ids, w,
+    hipLaunchKernelGGL((k_route_topk<NV, ROWS16>), dim3(n_chunks), dim3(kRouteThreads), lds, s, logits, T, E, k, ids, w,
                        counts, offsets, perm, mask, hotness, fused);
     return hipGetLastError();
 }
@@ -276,11 +296,16 @@ hipError_t dxk_route(const float *logits, int T, int E, int k, int32_t *ids, flo
     // T == 0 still runs one (empty) chunk so that counts and offsets are written.
     const int n_chunks = T > 0 ? (T + kChunk - 1) / kChunk : 1;
     hipError_t e;
-    if (E <= 64) e = launch_topk<1>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
-    else if (E <= 128) e = launch_topk<2>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
-    else if (E <= 256) e = launch_topk<4>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
-    else if (E <= 512) e = launch_topk<8>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
-    else e = launch_topk<16>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    // (k <= 16: a selected id per lane of the token's row)
+    if (k <= 16 && E <= 64) e = launch_topk<4, true>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (k <= 16 && E <= 128) e = launch_topk<8, true>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (k <= 16 && E <= 256) e = launch_topk<16, true>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (k <= 16 && E <= 512) e = launch_topk<32, true>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (E <= 64) e = launch_topk<1, false>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (E <= 128) e = launch_topk<2, false>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (E <= 256) e = launch_topk<4, false>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else if (E <= 512) e = launch_topk<8, false>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
+    else e = launch_topk<16, false>(logits, T, E, k, ids, w, counts, offsets, perm, mask, hotness, n_chunks, s);
     if (e != hipSuccess || n_chunks == 1) return e;
     hipLaunchKernelGGL(k_route_scan, dim3(1), dim3(kRouteThreads), 0, s, mask, n_chunks, E, chunk_base, counts,
                        offsets, hotness);
