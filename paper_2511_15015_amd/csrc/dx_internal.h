@@ -156,6 +156,7 @@ struct dx_fwd_args {
     int m_small; // experts with at most this many tokens take the streaming kernels, the others the tiled ones
     int o_bf16;  // O rows are bf16 (prefill: halves the traffic between the down kernels and the combine), else fp32
     int m_big;   // non-zero: the leading multiple of 256 rows of a bf16 expert takes the 256 x 256 tile kernel
+    int big_int4; // non-zero (with m_big): so does the leading multiple of 256 rows of an int4 expert
 };
 // Decode batches that the gate/up kernel routes itself (dx_route_forward): what its first block reads and
 // writes on top of dx_fwd_args (whose ids, w, offsets and perm point at the same arrays for the kernels

@@ -1208,6 +1208,8 @@ hipError_t launch_all(const dx_fwd_args &a_in, int n_cu, hipStream_t s, const dx
     const bool big_fit = a.d % 256 == 0 && a.f % 128 == 0 && (!a.shared || a.shared_f % 128 == 0) &&
                          span_x < (1ull << 32) && span_h < (1ull << 32) && (uint64_t)a.d * a.fmax * 2 < (1ull << 32);
     a.m_big = mixed && big_fit ? 256 : 0;
+    // its int4 path reads a row's scales as aligned pairs: an even number of groups along both contractions
+    a.big_int4 = a.m_big && (a.d / a.group) % 2 == 0 && (a.f / a.group) % 2 == 0;
     a.o_bf16 = mixed; // d % 128 == 0 there, so rows split into 8-column pieces
     const split_choice gu = pick_split(a.d / CHUNK, a.d / CHUNK);
     const split_choice dn = pick_split(a.f / CHUNK, (a.shared ? a.shared_f : a.f) / CHUNK);

@@ -73,6 +73,24 @@ __device__ __forceinline__ u32x4 dequant8(uint32_t word, float scale)
     return u32x4{p[0], p[1], p[2], p[3]};
 }
 
+// The same with the hardware's packed fp32 -> bf16 conversion (round to nearest even, as float_to_bf16_rne
+// for finite values)
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ u32x4 dequant8_pk(uint32_t word, float scale)
+{
+    uint32_t p[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f32x2 v;
+        v.x = (float)((int)(word << (28 - 8 * i)) >> 28) * scale;
+        v.y = (float)((int)(word << (24 - 8 * i)) >> 28) * scale;
+        const bf16x2 b = __builtin_convertvector(v, bf16x2);
+        p[i] = __builtin_bit_cast(uint32_t, b);
+    }
+    return u32x4{p[0], p[1], p[2], p[3]};
+}
+
 // 8 two-bit codes (bits 16*half .. of `word`) times scale -> 8 bf16 in element order
 __device__ __forceinline__ u32x4 dequant8_crumbs(uint32_t word, int half, float scale)
 {
@@ -98,7 +116,7 @@ constexpr int kBigRows = 256; // row granularity of the big-tile kernel
 
 // Rows of expert e that belong to the calling kernel.  Segments up to m_small tokens are not tiled at
 // all.  When the big-tile kernel is on (a.m_big), it owns the leading multiple of 256 rows of every
-// bf16 expert and the 128-row kernel owns the rest (all rows of an int4 expert).
+// bf16 expert (and of every int4 expert when a.big_int4) and the 128-row kernel owns the rest.
 template <bool BIG>
 __device__ __forceinline__ void owned_rows(const dx_fwd_args &a, int e, int &row0, int &rows)
 {
@@ -108,7 +126,7 @@ __device__ __forceinline__ void owned_rows(const dx_fwd_args &a, int e, int &row
     int lead = 0;
     if (a.m_big && m >= kBigRows) {
         const int fmt = e == a.E ? a.shared->fmt : a.table[e].fmt;
-        if (fmt == DX_FMT_BF16) lead = m / kBigRows * kBigRows;
+        if (fmt == DX_FMT_BF16 || (fmt == DX_FMT_INT4G && a.big_int4)) lead = m / kBigRows * kBigRows;
     }
     if (BIG) rows = lead;
     else row0 = lead, rows = m - lead;
@@ -441,7 +459,7 @@ __global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Large bf16 segments: 256 x 256 output tiles, 8 wavefronts (2 along rows x 4 along columns, each a
+// Large segments: 256 x 256 output tiles, 8 wavefronts (2 along rows x 4 along columns, each a
 // 128 x 64 sub-tile = 4 x 2 MFMA tiles), K in steps of 32 through a four-stage LDS ring that is
 // filled by global_load_lds_dwordx4 (memory to LDS without passing through registers), up to four
 // steps ahead of the MFMA loop.  One barrier per step.
@@ -449,11 +467,23 @@ __global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
 //   1 KB contiguously (lane l -> byte 16*l).  The piece stored in slot c of row r is c ^ ((r>>2)&3):
 //   the 16 lanes that read one piece index of 16 consecutive rows then hit 16 different bank groups.
 //   The loads are inline assembly so that the compiler does not serialise them against the LDS
-//   reads; their completion is awaited with explicit vmcnt counts (4 loads per wavefront per step).
+//   reads; their completion is awaited with explicit vmcnt counts.
+// bf16 experts: tokens and weights both arrive that way (4 loads per wavefront per step).
+// int4 experts (Q4): the tokens arrive that way; the weights' nibbles and scales take the same kind of
+//   load, four bytes per lane, into a small side ring (per stage and wavefront: 2 x 16 rows x 16 bytes of
+//   nibbles, 32 rows x one pair of scales), three steps before the wavefront that loaded them expands them
+//   (nibble -> fp32 -> times the group's scale -> bf16) into the weight half of the stage that has just been
+//   freed.  Every wavefront expands only what it loaded itself, so the side ring needs no barrier, only
+//   the wavefront's own vmcnt; the expanded rows are published by the step's barrier like the loaded ones
+//   (5 loads per wavefront per step).
 constexpr int TM = 256, TN = 256, TK = 32;
 constexpr int kBigThreads = 512;
-constexpr int kStageBytes = (TM + TN) * TK * 2; // 32 KB: A rows then B rows
+constexpr int kStageBytes = (TM + TN) * TK * 2; // 32 KB: token rows then weight rows
 constexpr int kStages = 4;
+constexpr int kSideWave = 768;                        // per wavefront: 256 + 256 bytes of nibbles, 256 of scale pairs
+constexpr int kSideStage = (kBigThreads / 64) * kSideWave; // 6 KB
+constexpr int kRingBytes = kStages * (kStageBytes + kSideStage);
+static_assert(kRingBytes >= TM * (TN * 2 + 16), "the staged output tile reuses the ring");
 
 typedef __attribute__((address_space(3))) char lds_char;
 
@@ -463,28 +493,34 @@ __device__ __forceinline__ void load_to_lds(uint32_t m0, uint32_t voff, uint64_t
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(voff), "s"(sbase)
                  : "memory");
 }
-
-template <bool DOWN>
-__global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
+// the same with 4 bytes per lane: memory (sbase + voff) -> LDS (m0 + 4 * lane)
+__device__ __forceinline__ void load_to_lds4(uint32_t m0, uint32_t voff, uint64_t sbase)
 {
-    // 128 KB ring; the tail keeps room for the staged output tile (256 rows of 512 + 16 bytes)
-    __shared__ __attribute__((aligned(1024))) char ring[kStages * kStageBytes + TM * 16];
-    __shared__ uint32_t cum[kMaxExperts + 1];
-    __shared__ uint32_t wave_tot[kBigThreads / 64];
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(m0), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+// a wave-uniform pointer as a scalar pair (the halves go through unsigned 32-bit values: the builtin
+// returns int, which must not be sign-extended into the upper half)
+__device__ __forceinline__ uint64_t scalar_ptr(const void *p)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p >> 32));
+    return (uint64_t)lo | ((uint64_t)hi << 32);
+}
 
-    const int ntn_routed = DOWN ? a.d / TN : a.f / (TN / 2);
-    const int ntn_shared = DOWN ? a.d / TN : a.shared_f / (TN / 2);
-    const tile_id t = find_tile<kBigThreads, TM, true>(a, ntn_routed, ntn_shared, cum, wave_tot);
-    if (!t.valid) return; // block-uniform
+template <bool DOWN, bool Q4>
+__device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t, const dx_handle &hd, char *ring)
+{
     const bool shared = t.e == a.E;
-    const dx_handle hd = shared ? *a.shared : a.table[t.e];
     const int fe = shared ? a.shared_f : a.f;
     const int K = DOWN ? fe : a.d;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
 
-    // ---- loader role: wavefront w fills rows [32w, 32w + 32) of the A part and of the B part ----
+    // ---- loader role: wavefront w fills rows [32w, 32w + 32) of the token part and of the weight part ----
+    // weight-tile row -> matrix row: down: TN consecutive rows; gate/up: 128 gate rows, then the same up rows
+    auto wrow = [&](int row) { return DOWN ? t.nt * TN + row : t.nt * (TN / 2) + (row & 127); };
     uint32_t a_off[2], b_off[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -493,30 +529,59 @@ __global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
         const int slot = t.mt * TM + row; // big tiles are full: slot < t.m
         if constexpr (DOWN) {
             a_off[i] = (uint32_t)(t.seg0 + slot) * (uint32_t)a.fmax * 2u + piece * 16u;
-            b_off[i] = (uint32_t)(t.nt * TN + row) * (uint32_t)K * 2u + piece * 16u;
         } else {
             const int tok = shared ? t.tok0 + slot : a.perm[t.seg0 + slot] / a.k;
             a_off[i] = (uint32_t)tok * (uint32_t)K * 2u + piece * 16u;
-            b_off[i] = (uint32_t)(t.nt * (TN / 2) + (row & 127)) * (uint32_t)K * 2u + piece * 16u;
         }
+        // bf16: the lane's 16-byte piece of the row; int4: its four bytes (8 nibbles) of the row's 16 per step
+        b_off[i] = Q4 ? (uint32_t)wrow(row) * (uint32_t)(K / 2) + (uint32_t)(lane & 3) * 4u
+                      : (uint32_t)wrow(row) * (uint32_t)K * 2u + piece * 16u;
     }
     const uint64_t a_base = (uint64_t)(DOWN ? (const void *)a.h : (const void *)a.x);
-    const void *bmat = DOWN ? hd.w_down : (wave < 4 ? hd.w_gate : hd.w_up);
-    // wave-uniform matrix base as a scalar pair (the halves go through unsigned 32-bit values: the
-    // builtin returns int, which must not be sign-extended into the upper half)
-    const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)bmat);
-    const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)bmat >> 32));
-    const uint64_t b_base = (uint64_t)b_lo | ((uint64_t)b_hi << 32);
+    const uint64_t b_base = scalar_ptr(DOWN ? hd.w_down : (wave < 4 ? hd.w_gate : hd.w_up));
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char *)ring;
     const uint32_t m0_a = lds0 + wave * 2048, m0_b = lds0 + TM * TK * 2 + wave * 2048;
     const int nk = K / TK;
-    auto issue = [&](int kt, int stage) {
-        const uint64_t kb = (uint64_t)(kt < nk ? kt : nk - 1) * (TK * 2);
+    // int4: scales of the lane's row (lane & 31 of the wavefront's 32 rows), read as the aligned pair that
+    // holds the step's group (the number of groups per row is even there, so a pair never leaves its row)
+    const int lg = __builtin_ctz((unsigned)a.group);
+    const uint32_t s_off = Q4 ? (uint32_t)wrow(32 * wave + (lane & 31)) * (uint32_t)(K >> lg) * 2u : 0u;
+    const uint64_t s_base = Q4 ? scalar_ptr(DOWN ? hd.s_down : (wave < 4 ? hd.s_gate : hd.s_up)) : 0;
+    const int side_wave = kStages * kStageBytes + wave * kSideWave; // + stage * kSideStage
+    auto clamped = [&](int kt) { return kt < nk ? kt : nk - 1; };
+    auto issue_tokens = [&](int kt, int stage) {
+        const uint64_t kb = (uint64_t)clamped(kt) * (TK * 2);
         const uint32_t so = (uint32_t)stage * kStageBytes;
         load_to_lds(m0_a + so, a_off[0], a_base + kb);
         load_to_lds(m0_a + so + 1024, a_off[1], a_base + kb);
+    };
+    auto issue_weights = [&](int kt, int stage) { // bf16
+        const uint64_t kb = (uint64_t)clamped(kt) * (TK * 2);
+        const uint32_t so = (uint32_t)stage * kStageBytes;
         load_to_lds(m0_b + so, b_off[0], b_base + kb);
         load_to_lds(m0_b + so + 1024, b_off[1], b_base + kb);
+    };
+    auto issue_codes = [&](int kt, int slot) { // int4: nibbles and scale pairs of step kt -> side slot
+        const int kc = clamped(kt);
+        const uint32_t m0 = lds0 + (uint32_t)(side_wave + slot * kSideStage);
+        load_to_lds4(m0, b_off[0], b_base + (uint64_t)kc * (TK / 2));
+        load_to_lds4(m0 + 256, b_off[1], b_base + (uint64_t)kc * (TK / 2));
+        load_to_lds4(m0 + 512, s_off, s_base + (uint64_t)((((kc * TK) >> lg) * 2) & ~3));
+    };
+    // int4: the wavefront's 32 rows of step kt, from side slot `slot` into the weight half of `stage`
+    auto expand = [&](int kt, int slot, int stage) {
+        const int odd = ((clamped(kt) * TK) >> lg) & 1;
+        const char *side = ring + side_wave + slot * kSideStage;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t codes = *reinterpret_cast<const uint32_t *>(side + 256 * i + 4 * lane);
+            const uint32_t pair = *reinterpret_cast<const uint32_t *>(side + 512 + 4 * (16 * i + (lane >> 2)));
+            const float scale = __uint_as_float(odd ? pair & 0xFFFF0000u : pair << 16);
+            const int row = 32 * wave + 16 * i + (lane >> 2);
+            const int pos = (lane & 3) ^ ((row >> 2) & 3);
+            *reinterpret_cast<u32x4 *>(ring + stage * kStageBytes + TM * TK * 2 + row * (TK * 2) + pos * 16) =
+                dequant8_pk(codes, scale);
+        }
     };
 
     // ---- MFMA role ----
@@ -554,11 +619,26 @@ __global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
             for (int ns = 0; ns < 2; ++ns)
                 acc[ms][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ns].v, af[ms].v, acc[ms][ns], 0, 0, 0);
     };
-    issue(0, 0);
-    issue(1, 1);
-    issue(2, 2);
-    issue(3, 3);
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); // own loads of step 0
+    if constexpr (Q4) {
+        // The codes of step j are loaded with the tokens of step j - 3 and expanded when step j - 4 frees
+        // its stage.  Start: codes 0..3 and tokens 0, 1; expand 0..3 as soon as the codes are there; then
+        // codes 4..6 and tokens 2, 3 in the order the loop continues (tokens j + 4, codes j + 7).
+        for (int j = 0; j < 4; ++j) issue_codes(j, j);
+        issue_tokens(0, 0);
+        issue_tokens(1, 1);
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); // own codes 0..3
+        for (int j = 0; j < 4; ++j) expand(j, j, j);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the side slots have been read: refill three
+        issue_codes(4, 0);
+        issue_tokens(2, 2);
+        issue_codes(5, 1);
+        issue_tokens(3, 3);
+        issue_codes(6, 2);
+        asm volatile("s_waitcnt vmcnt(10) lgkmcnt(0)" ::: "memory"); // own tokens 0, 1 and codes 4; own expansions
+    } else {
+        for (int j = 0; j < 4; ++j) issue_tokens(j, j), issue_weights(j, j);
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); // own loads of step 0
+    }
     __builtin_amdgcn_s_barrier();
     read_frags(0, 0, fa[0], fb[0]);
     auto step = [&](int kt, auto stage_c) {
@@ -568,11 +648,19 @@ __global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
         __builtin_amdgcn_sched_barrier(0);
         mma_half(fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
-        // own loads of step kt + 1 have landed (8 younger ones may still fly) and own LDS reads of
-        // stage S have returned; after the barrier that holds for every wavefront
-        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        // own loads of step kt + 1 (int4: and the codes of step kt + 4) have landed, the loads of two later
+        // steps may still fly; own LDS reads of stage S have returned and own LDS writes are done; after
+        // the barrier that holds for every wavefront
+        if constexpr (Q4) asm volatile("s_waitcnt vmcnt(10) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        issue(kt + 4, S);
+        issue_tokens(kt + 4, S);
+        if constexpr (Q4) {
+            issue_codes(kt + 7, (S + 3) & 3);
+            expand(kt + 4, S, S);
+        } else {
+            issue_weights(kt + 4, S);
+        }
         read_frags((S + 1) & 3, 0, fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
         mma_half(fa[1], fb[1]);
@@ -638,6 +726,23 @@ __global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
         }
         *reinterpret_cast<u32x4 *>(dst) = v;
     }
+}
+
+template <bool DOWN>
+__global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
+{
+    // the ring (128 KB) and the int4 side ring (24 KB); the staged output tile (256 rows of 512 + 16 bytes) reuses them
+    __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
+    __shared__ uint32_t cum[kMaxExperts + 1];
+    __shared__ uint32_t wave_tot[kBigThreads / 64];
+
+    const int ntn_routed = DOWN ? a.d / TN : a.f / (TN / 2);
+    const int ntn_shared = DOWN ? a.d / TN : a.shared_f / (TN / 2);
+    const tile_id t = find_tile<kBigThreads, TM, true>(a, ntn_routed, ntn_shared, cum, wave_tot);
+    if (!t.valid) return; // block-uniform
+    const dx_handle hd = t.e == a.E ? *a.shared : a.table[t.e];
+    if (hd.fmt == DX_FMT_INT4G) big_tile<DOWN, true>(a, t, hd, ring); // block-uniform
+    else big_tile<DOWN, false>(a, t, hd, ring);
 }
 
 } // namespace

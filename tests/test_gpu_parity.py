@@ -519,6 +519,35 @@ def test_forward_prefill_tiles_small_shapes(B, LY, dxo, T, E, k, resident):
     ly.ctx.close()
 
 
+@pytest.mark.parametrize("T,E,k,d,f,group,resident", [
+    (600, 2, 2, 256, 128, 32, []),          # both experts int4 with 600 rows: two 256-row tiles and a remainder each
+    (1100, 2, 2, 256, 128, 64, []),         # four tiles each; the down contraction is four steps (one trip of the loop)
+    (520, 2, 1, 512, 256, 128, []),         # about 260 rows each: one tile and a few rows
+    (700, 4, 2, 512, 256, 128, [0]),        # bf16 and int4 tiles in one launch
+    (768, 1, 1, 256, 384, 128, []),         # three groups per row of W_down: the int4 experts stay with the 128-row tiles
+    (300, 1, 1, 2048, 768, 128, []),        # the 30B layer's K extents: 64 and 24 steps
+])
+def test_forward_prefill_int4_segments_of_256_rows_and_more(B, LY, dxo, T, E, k, d, f, group, resident):
+    """int4 experts with 256 rows and more: the leading multiple of 256 rows takes the 256 x 256 tile kernel, which
+    expands the codes into its LDS ring (when the number of groups per row is even); every token, and the same
+    bits on a second run."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["C1"], T=T, E=E, k=k, d=d, f=f, group=group)
+    print(f"prefill int4 tiles T={T} E={E} k={k} d={d} f={f} g={group} resident={resident}", flush=True)
+    x, logits = W.layer_inputs(wl, seed=31)
+    ly = Layer(B, LY, dxo, wl, resident, seed=31)
+    y_gpu, y_ref = ly.run(x, logits)
+    err = rel_l2(y_gpu, y_ref)
+    print("  rel-L2", err, flush=True)
+    assert err <= REL_L2_TOL
+    yg = bf16_bits_to_f32(y_gpu).astype(np.float64)
+    tok = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
+    assert tok.max() <= 2 * REL_L2_TOL
+    again, _ = ly.run(x, logits)
+    assert np.array_equal(again, y_gpu)
+    ly.ctx.close()
+
+
 @pytest.mark.parametrize("T", [150, 600])
 def test_forward_prefill_with_shared_expert(B, LY, dxo, T):
     import dataclasses
@@ -533,19 +562,21 @@ def test_forward_prefill_with_shared_expert(B, LY, dxo, T):
     ly.ctx.close()
 
 
-@pytest.mark.parametrize("T", [4096, 8192])
-def test_forward_c3_prefill_sampled_tokens(B, LY, dxo, T):
+@pytest.mark.parametrize("T,n_hi", [(4096, None), (8192, None), (4096, 0)])
+def test_forward_c3_prefill_sampled_tokens(B, LY, dxo, T, n_hi):
     """The 30B-shaped prefill layer at full size (T=4096) and at twice that (the largest batch the
-    benchmarks use): routing bit-exact on all tokens, layer output checked on sampled tokens the oracle
-    computes one by one."""
+    benchmarks use), and with no resident expert (every expert int4, the large segments in 256-row tiles):
+    routing bit-exact on all tokens, layer output checked on sampled tokens the oracle computes one by one."""
     import dataclasses
     wl = dataclasses.replace(WORKLOADS["C3"], T=T)
+    if n_hi is not None:
+        wl = dataclasses.replace(wl, n_hi=n_hi)
     print("forward C3: drawing masters", flush=True)
     masters = W.layer_masters(wl, 0, 0)
     x, logits = W.layer_inputs(wl, seed=0)
     ids, w, counts, offsets, perm = dxo.route(logits, wl.k)
     S = counts.astype(np.uint64) << np.uint64(16)
-    resident = set(int(e) for e in dxo.select_topn(S, wl.n_hi))
+    resident = set(int(e) for e in dxo.select_topn(S, wl.n_hi)) if wl.n_hi else set()
     ctx = B.Context(L=1, E=wl.E, d=wl.d, f=wl.f, top_k=wl.k, group=wl.group, max_tokens=wl.T)
     dev = [LY.bits_to_device(m) for m in masters]
     lw = LY.LayerWeights(ctx, 0, *dev, resident, wl.group)
@@ -671,6 +702,7 @@ def _quant_pair_layer(B, LY, dxo, wl, hi_ids, seed, T):
     (33, 16, 4, 2048, 768, 128, [2, 3, 5]),    # the 30B layer's K extents
     (300, 4, 2, 256, 128, 64, [0, 2]),         # prefill-sized: 128-row tiles expand int2 on the way to LDS
     (700, 4, 2, 256, 128, 128, [1]),
+    (700, 4, 2, 512, 256, 128, [1, 2]),        # int4 segments of 256 rows and more: 256-row tiles
 ])
 def test_forward_int4_int2_pair(B, LY, dxo, T, E, k, d, f, group, hi_ids):
     import dataclasses
