@@ -209,7 +209,23 @@ def run_sweep(args):
                 step_fn(i)
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / steps
-            rows.append({"T": T, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3)})
+            row = {"T": T, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3)}
+            if T <= 256:
+                # the same L calls recorded once into a HIP graph and replayed: the device's own time per
+                # call, where the host's three launches per call are the longer part (the smallest batches)
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in range(L):
+                        step_fn(i)
+                g.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps // L):
+                    g.replay()
+                torch.cuda.synchronize()
+                row["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / (steps // L * L)
+                del g
+            rows.append(row)
             T *= 2
     ctx.close()
     at32 = next(r for r in rows if r["T"] == 32)

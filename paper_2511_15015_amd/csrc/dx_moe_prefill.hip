@@ -60,34 +60,25 @@ __device__ __forceinline__ float swiglu_fast(float g, float u)
     return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
 }
 
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// two fp32 -> two bf16 in one word (the hardware's packed conversion: round to nearest even, the same
+// bits as float_to_bf16_rne for finite values)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const f32x2 v{lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // 8 nibbles of `word` times scale -> 8 bf16 in element order
 __device__ __forceinline__ u32x4 dequant8(uint32_t word, float scale)
 {
     uint32_t p[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float lo = (float)((int)(word << (28 - 8 * i)) >> 28) * scale;
-        const float hi = (float)((int)(word << (24 - 8 * i)) >> 28) * scale;
-        p[i] = float_to_bf16_rne(lo) | (float_to_bf16_rne(hi) << 16);
-    }
-    return u32x4{p[0], p[1], p[2], p[3]};
-}
-
-// The same with the hardware's packed fp32 -> bf16 conversion (round to nearest even, as float_to_bf16_rne
-// for finite values)
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-__device__ __forceinline__ u32x4 dequant8_pk(uint32_t word, float scale)
-{
-    uint32_t p[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        f32x2 v;
-        v.x = (float)((int)(word << (28 - 8 * i)) >> 28) * scale;
-        v.y = (float)((int)(word << (24 - 8 * i)) >> 28) * scale;
-        const bf16x2 b = __builtin_convertvector(v, bf16x2);
-        p[i] = __builtin_bit_cast(uint32_t, b);
-    }
+    for (int i = 0; i < 4; ++i)
+        p[i] = pack_bf16((float)((int)(word << (28 - 8 * i)) >> 28) * scale,
+                         (float)((int)(word << (24 - 8 * i)) >> 28) * scale);
     return u32x4{p[0], p[1], p[2], p[3]};
 }
 
@@ -97,11 +88,8 @@ __device__ __forceinline__ u32x4 dequant8_crumbs(uint32_t word, int half, float 
     const uint32_t h = word >> (16 * half);
     uint32_t p[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float lo = (float)((int)(h << (30 - 4 * i)) >> 30) * scale;
-        const float hi = (float)((int)(h << (28 - 4 * i)) >> 30) * scale;
-        p[i] = float_to_bf16_rne(lo) | (float_to_bf16_rne(hi) << 16);
-    }
+    for (int i = 0; i < 4; ++i)
+        p[i] = pack_bf16((float)((int)(h << (30 - 4 * i)) >> 30) * scale, (float)((int)(h << (28 - 4 * i)) >> 30) * scale);
     return u32x4{p[0], p[1], p[2], p[3]};
 }
 
@@ -580,7 +568,7 @@ __device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t,
             const int row = 32 * wave + 16 * i + (lane >> 2);
             const int pos = (lane & 3) ^ ((row >> 2) & 3);
             *reinterpret_cast<u32x4 *>(ring + stage * kStageBytes + TM * TK * 2 + row * (TK * 2) + pos * 16) =
-                dequant8_pk(codes, scale);
+                dequant8(codes, scale);
         }
     };
 
