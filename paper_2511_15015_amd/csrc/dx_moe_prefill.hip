@@ -448,28 +448,31 @@ __global__ __launch_bounds__(kThreads) void k_tiled(dx_fwd_args a)
 
 // ---------------------------------------------------------------------------------------------
 // Large segments: 256 x 256 output tiles, 8 wavefronts (2 along rows x 4 along columns, each a
-// 128 x 64 sub-tile = 4 x 2 MFMA tiles), K in steps of 32 through a four-stage LDS ring that is
-// filled by global_load_lds_dwordx4 (memory to LDS without passing through registers), up to four
+// 128 x 64 sub-tile = 4 x 2 MFMA tiles), K in steps of 64 through a two-stage LDS ring that is
+// filled by global_load_lds_dwordx4 (memory to LDS without passing through registers), up to two
 // steps ahead of the MFMA loop.  One barrier per step.
-//   LDS rows are 64 bytes (4 pieces of 16 bytes), unpadded because a wavefront-wide LDS load writes
-//   1 KB contiguously (lane l -> byte 16*l).  The piece stored in slot c of row r is c ^ ((r>>2)&3):
-//   the 16 lanes that read one piece index of 16 consecutive rows then hit 16 different bank groups.
+//   LDS rows are 128 bytes, one whole line of a token or weight row per step (a load instruction then
+//   asks for 8 whole lines; with 64-byte rows and 16 half lines per instruction the same fill runs a
+//   quarter slower), unpadded because a wavefront-wide LDS load writes 1 KB contiguously (lane l ->
+//   byte 16*l).  The piece stored in slot c of row r is c ^ ((r>>1)&7): the 16 lanes that read one piece
+//   index of 16 consecutive rows then hit 16 different bank groups.
 //   The loads are inline assembly so that the compiler does not serialise them against the LDS
 //   reads; their completion is awaited with explicit vmcnt counts.
-// bf16 experts: tokens and weights both arrive that way (4 loads per wavefront per step).
+// bf16 experts: tokens and weights both arrive that way (8 loads per wavefront per step).
 // int4 experts (Q4): the tokens arrive that way; the weights' nibbles and scales take the same kind of
-//   load, four bytes per lane, into a small side ring (per stage and wavefront: 2 x 16 rows x 16 bytes of
-//   nibbles, 32 rows x one pair of scales), three steps before the wavefront that loaded them expands them
+//   load, four bytes per lane, into a small side ring (per slot and wavefront: 4 x 8 rows x 32 bytes of
+//   nibbles, 32 rows x one pair of scales), one step before the wavefront that loaded them expands them
 //   (nibble -> fp32 -> times the group's scale -> bf16) into the weight half of the stage that has just been
 //   freed.  Every wavefront expands only what it loaded itself, so the side ring needs no barrier, only
 //   the wavefront's own vmcnt; the expanded rows are published by the step's barrier like the loaded ones
-//   (5 loads per wavefront per step).
-constexpr int TM = 256, TN = 256, TK = 32;
+//   (9 loads per wavefront per step).
+constexpr int TM = 256, TN = 256, TK = 64;
 constexpr int kBigThreads = 512;
-constexpr int kStageBytes = (TM + TN) * TK * 2; // 32 KB: token rows then weight rows
-constexpr int kStages = 4;
-constexpr int kSideWave = 768;                        // per wavefront: 256 + 256 bytes of nibbles, 256 of scale pairs
-constexpr int kSideStage = (kBigThreads / 64) * kSideWave; // 6 KB
+constexpr int kRowBytes64 = TK * 2;                      // 128: one line of a row per step
+constexpr int kStageBytes = (TM + TN) * kRowBytes64;     // 64 KB: token rows then weight rows
+constexpr int kStages = 2;
+constexpr int kSideWave = 1280;                          // per wavefront: 4 x 256 bytes of nibbles, 256 of scale pairs
+constexpr int kSideStage = (kBigThreads / 64) * kSideWave; // 10 KB
 constexpr int kRingBytes = kStages * (kStageBytes + kSideStage);
 static_assert(kRingBytes >= TM * (TN * 2 + 16), "the staged output tile reuses the ring");
 
@@ -507,13 +510,15 @@ __device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t,
     const int wm = wave >> 2, wn = wave & 3;
 
     // ---- loader role: wavefront w fills rows [32w, 32w + 32) of the token part and of the weight part ----
+    // A load instruction covers 8 rows x one 128-byte line; lane l writes LDS piece l % 8 of row l / 8 and
+    // fetches the memory piece that belongs there: piece p of row r sits in slot p ^ ((r >> 1) & 7).
     // weight-tile row -> matrix row: down: TN consecutive rows; gate/up: 128 gate rows, then the same up rows
     auto wrow = [&](int row) { return DOWN ? t.nt * TN + row : t.nt * (TN / 2) + (row & 127); };
-    uint32_t a_off[2], b_off[2];
+    uint32_t a_off[4], b_off[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = 32 * wave + 16 * i + (lane >> 2);
-        const uint32_t piece = (uint32_t)((lane & 3) ^ ((row >> 2) & 3));
+    for (int i = 0; i < 4; ++i) {
+        const int row = 32 * wave + 8 * i + (lane >> 3);
+        const uint32_t piece = (uint32_t)((lane & 7) ^ ((row >> 1) & 7));
         const int slot = t.mt * TM + row; // big tiles are full: slot < t.m
         if constexpr (DOWN) {
             a_off[i] = (uint32_t)(t.seg0 + slot) * (uint32_t)a.fmax * 2u + piece * 16u;
@@ -521,63 +526,63 @@ __device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t,
             const int tok = shared ? t.tok0 + slot : a.perm[t.seg0 + slot] / a.k;
             a_off[i] = (uint32_t)tok * (uint32_t)K * 2u + piece * 16u;
         }
-        // bf16: the lane's 16-byte piece of the row; int4: its four bytes (8 nibbles) of the row's 16 per step
-        b_off[i] = Q4 ? (uint32_t)wrow(row) * (uint32_t)(K / 2) + (uint32_t)(lane & 3) * 4u
+        // bf16: the lane's 16-byte piece of the row; int4: its four bytes (8 nibbles) of the row's 32 per step
+        b_off[i] = Q4 ? (uint32_t)wrow(row) * (uint32_t)(K / 2) + (uint32_t)(lane & 7) * 4u
                       : (uint32_t)wrow(row) * (uint32_t)K * 2u + piece * 16u;
     }
     const uint64_t a_base = (uint64_t)(DOWN ? (const void *)a.h : (const void *)a.x);
     const uint64_t b_base = scalar_ptr(DOWN ? hd.w_down : (wave < 4 ? hd.w_gate : hd.w_up));
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char *)ring;
-    const uint32_t m0_a = lds0 + wave * 2048, m0_b = lds0 + TM * TK * 2 + wave * 2048;
+    const uint32_t m0_a = lds0 + wave * 32 * kRowBytes64, m0_b = lds0 + TM * kRowBytes64 + wave * 32 * kRowBytes64;
     const int nk = K / TK;
     // int4: scales of the lane's row (lane & 31 of the wavefront's 32 rows), read as the aligned pair that
-    // holds the step's group (the number of groups per row is even there, so a pair never leaves its row)
+    // holds the step's groups (the number of groups per row is even there, so a pair never leaves its row;
+    // with groups of 32 a step spans exactly the two groups of its pair)
     const int lg = __builtin_ctz((unsigned)a.group);
     const uint32_t s_off = Q4 ? (uint32_t)wrow(32 * wave + (lane & 31)) * (uint32_t)(K >> lg) * 2u : 0u;
     const uint64_t s_base = Q4 ? scalar_ptr(DOWN ? hd.s_down : (wave < 4 ? hd.s_gate : hd.s_up)) : 0;
-    const int side_wave = kStages * kStageBytes + wave * kSideWave; // + stage * kSideStage
+    const int side_wave = kStages * kStageBytes + wave * kSideWave; // + slot * kSideStage
     auto clamped = [&](int kt) { return kt < nk ? kt : nk - 1; };
     auto issue_tokens = [&](int kt, int stage) {
-        const uint64_t kb = (uint64_t)clamped(kt) * (TK * 2);
+        const uint64_t kb = (uint64_t)clamped(kt) * kRowBytes64;
         const uint32_t so = (uint32_t)stage * kStageBytes;
-        load_to_lds(m0_a + so, a_off[0], a_base + kb);
-        load_to_lds(m0_a + so + 1024, a_off[1], a_base + kb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_to_lds(m0_a + so + 1024 * i, a_off[i], a_base + kb);
     };
     auto issue_weights = [&](int kt, int stage) { // bf16
-        const uint64_t kb = (uint64_t)clamped(kt) * (TK * 2);
+        const uint64_t kb = (uint64_t)clamped(kt) * kRowBytes64;
         const uint32_t so = (uint32_t)stage * kStageBytes;
-        load_to_lds(m0_b + so, b_off[0], b_base + kb);
-        load_to_lds(m0_b + so + 1024, b_off[1], b_base + kb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_to_lds(m0_b + so + 1024 * i, b_off[i], b_base + kb);
     };
     auto issue_codes = [&](int kt, int slot) { // int4: nibbles and scale pairs of step kt -> side slot
         const int kc = clamped(kt);
         const uint32_t m0 = lds0 + (uint32_t)(side_wave + slot * kSideStage);
-        load_to_lds4(m0, b_off[0], b_base + (uint64_t)kc * (TK / 2));
-        load_to_lds4(m0 + 256, b_off[1], b_base + (uint64_t)kc * (TK / 2));
-        load_to_lds4(m0 + 512, s_off, s_base + (uint64_t)((((kc * TK) >> lg) * 2) & ~3));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_to_lds4(m0 + 256 * i, b_off[i], b_base + (uint64_t)kc * (TK / 2));
+        load_to_lds4(m0 + 1024, s_off, s_base + (uint64_t)((((kc * TK) >> lg) * 2) & ~3));
     };
     // int4: the wavefront's 32 rows of step kt, from side slot `slot` into the weight half of `stage`
     auto expand = [&](int kt, int slot, int stage) {
-        const int odd = ((clamped(kt) * TK) >> lg) & 1;
+        const int odd = ((clamped(kt) * TK + 8 * (lane & 7)) >> lg) & 1; // per lane when a group is 32 wide
         const char *side = ring + side_wave + slot * kSideStage;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const uint32_t codes = *reinterpret_cast<const uint32_t *>(side + 256 * i + 4 * lane);
-            const uint32_t pair = *reinterpret_cast<const uint32_t *>(side + 512 + 4 * (16 * i + (lane >> 2)));
+            const uint32_t pair = *reinterpret_cast<const uint32_t *>(side + 1024 + 4 * (8 * i + (lane >> 3)));
             const float scale = __uint_as_float(odd ? pair & 0xFFFF0000u : pair << 16);
-            const int row = 32 * wave + 16 * i + (lane >> 2);
-            const int pos = (lane & 3) ^ ((row >> 2) & 3);
-            *reinterpret_cast<u32x4 *>(ring + stage * kStageBytes + TM * TK * 2 + row * (TK * 2) + pos * 16) =
+            const int row = 32 * wave + 8 * i + (lane >> 3);
+            const int pos = (lane & 7) ^ ((row >> 1) & 7);
+            *reinterpret_cast<u32x4 *>(ring + stage * kStageBytes + TM * kRowBytes64 + row * kRowBytes64 + pos * 16) =
                 dequant8(codes, scale);
         }
     };
 
     // ---- MFMA role ----
-    const int r = lane & 31, kq = lane >> 5, swz = (r >> 2) & 3;
-    const int a_lane = (wm * 128 + r) * (TK * 2);
-    const int b_lane0 = TM * TK * 2 + (DOWN ? wn * 64 + r : wn * 32 + r) * (TK * 2);
-    const int b_lane1 = TM * TK * 2 + (DOWN ? wn * 64 + 32 + r : 128 + wn * 32 + r) * (TK * 2);
-    const int slot0 = (kq ^ swz) * 16, slot1 = ((2 + kq) ^ swz) * 16;
+    const int r = lane & 31, kq = lane >> 5, swz = (r >> 1) & 7;
+    const int a_lane = (wm * 128 + r) * kRowBytes64;
+    const int b_lane0 = TM * kRowBytes64 + (DOWN ? wn * 64 + r : wn * 32 + r) * kRowBytes64;
+    const int b_lane1 = TM * kRowBytes64 + (DOWN ? wn * 64 + 32 + r : 128 + wn * 32 + r) * kRowBytes64;
 
     f32x16 acc[4][2];
 #pragma unroll
@@ -587,20 +592,20 @@ __device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[ms][ns][v] = 0.f;
 
-    // Software pipeline.  Each K-step has two halves (16 k-values each); the fragments of a half sit
-    // in registers before its MFMAs start.  The barrier is in the middle of a step, in the shadow of
-    // the first half's MFMAs: past it every wavefront holds all of stage S in registers, so S is
-    // refilled at once with step kt + 4, and the landed stage of step kt + 1 may be read.
+    // Software pipeline.  Each K-step has four quarters (16 k-values each); the fragments of a quarter sit
+    // in registers before its MFMAs start.  The barrier comes once the last quarter's fragments have been
+    // read, in the shadow of the third quarter's MFMAs: past it every wavefront holds what it needs of
+    // stage S, so S is refilled at once with step kt + 2, and the landed stage of step kt + 1 may be read.
     frag8 fa[2][4], fb[2][2];
-    auto read_frags = [&](int stage, int half, frag8 (&af)[4], frag8 (&bf)[2]) {
+    auto read_frags = [&](int stage, int quarter, frag8 (&af)[4], frag8 (&bf)[2]) {
         const char *st = ring + stage * kStageBytes;
-        const int so = half ? slot1 : slot0;
+        const int so = ((2 * quarter + kq) ^ swz) * 16;
 #pragma unroll
-        for (int ms = 0; ms < 4; ++ms) af[ms].u = *reinterpret_cast<const u32x4 *>(st + a_lane + ms * 2048 + so);
+        for (int ms = 0; ms < 4; ++ms) af[ms].u = *reinterpret_cast<const u32x4 *>(st + a_lane + ms * 32 * kRowBytes64 + so);
         bf[0].u = *reinterpret_cast<const u32x4 *>(st + b_lane0 + so);
         bf[1].u = *reinterpret_cast<const u32x4 *>(st + b_lane1 + so);
     };
-    auto mma_half = [&](const frag8 (&af)[4], const frag8 (&bf)[2]) {
+    auto mma_quarter = [&](const frag8 (&af)[4], const frag8 (&bf)[2]) {
 #pragma unroll
         for (int ms = 0; ms < 4; ++ms)
 #pragma unroll
@@ -608,24 +613,23 @@ __device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t,
                 acc[ms][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ns].v, af[ms].v, acc[ms][ns], 0, 0, 0);
     };
     if constexpr (Q4) {
-        // The codes of step j are loaded with the tokens of step j - 3 and expanded when step j - 4 frees
-        // its stage.  Start: codes 0..3 and tokens 0, 1; expand 0..3 as soon as the codes are there; then
-        // codes 4..6 and tokens 2, 3 in the order the loop continues (tokens j + 4, codes j + 7).
-        for (int j = 0; j < 4; ++j) issue_codes(j, j);
+        // The codes of step j are loaded with the tokens of step j - 1 and expanded when step j - 2 frees
+        // its stage.  Start: codes 0, 1 and tokens 0, 1; expand 0, 1 as soon as the codes are there; then
+        // the codes of step 2.
+        issue_codes(0, 0);
+        issue_codes(1, 1);
         issue_tokens(0, 0);
         issue_tokens(1, 1);
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); // own codes 0..3
-        for (int j = 0; j < 4; ++j) expand(j, j, j);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the side slots have been read: refill three
-        issue_codes(4, 0);
-        issue_tokens(2, 2);
-        issue_codes(5, 1);
-        issue_tokens(3, 3);
-        issue_codes(6, 2);
-        asm volatile("s_waitcnt vmcnt(10) lgkmcnt(0)" ::: "memory"); // own tokens 0, 1 and codes 4; own expansions
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); // own codes 0, 1
+        expand(0, 0, 0);
+        expand(1, 1, 1);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // side slot 0 has been read: refill it
+        issue_codes(2, 0);
+        asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory"); // own tokens of step 0; own expansions
     } else {
-        for (int j = 0; j < 4; ++j) issue_tokens(j, j), issue_weights(j, j);
-        asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); // own loads of step 0
+        issue_tokens(0, 0), issue_weights(0, 0);
+        issue_tokens(1, 1), issue_weights(1, 1);
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); // own loads of step 0
     }
     __builtin_amdgcn_s_barrier();
     read_frags(0, 0, fa[0], fb[0]);
@@ -634,31 +638,35 @@ __device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t,
         // (the scheduling fences keep the LDS reads ahead of the MFMAs they overlap with)
         read_frags(S, 1, fa[1], fb[1]);
         __builtin_amdgcn_sched_barrier(0);
-        mma_half(fa[0], fb[0]);
+        mma_quarter(fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
-        // own loads of step kt + 1 (int4: and the codes of step kt + 4) have landed, the loads of two later
-        // steps may still fly; own LDS reads of stage S have returned and own LDS writes are done; after
-        // the barrier that holds for every wavefront
-        if constexpr (Q4) asm volatile("s_waitcnt vmcnt(10) lgkmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        read_frags(S, 2, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_quarter(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(S, 3, fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_quarter(fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // own loads of step kt + 1 (int4: and the codes of step kt + 2) have landed; own LDS reads of stage S
+        // have returned and own LDS writes are done; after the barrier that holds for every wavefront
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        issue_tokens(kt + 4, S);
+        issue_tokens(kt + 2, S);
         if constexpr (Q4) {
-            issue_codes(kt + 7, (S + 3) & 3);
-            expand(kt + 4, S, S);
+            issue_codes(kt + 3, S ^ 1);
+            expand(kt + 2, S, S);
         } else {
-            issue_weights(kt + 4, S);
+            issue_weights(kt + 2, S);
         }
-        read_frags((S + 1) & 3, 0, fa[0], fb[0]);
+        read_frags(S ^ 1, 0, fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
-        mma_half(fa[1], fb[1]);
+        mma_quarter(fa[1], fb[1]);
         __builtin_amdgcn_sched_barrier(0);
     };
-    for (int kt = 0; kt < nk; kt += 4) { // nk is a multiple of 4 (K a multiple of 128)
+    for (int kt = 0; kt < nk; kt += 2) { // nk is even (K a multiple of 128)
         step(kt, std::integral_constant<int, 0>{});
         step(kt + 1, std::integral_constant<int, 1>{});
-        step(kt + 2, std::integral_constant<int, 2>{});
-        step(kt + 3, std::integral_constant<int, 3>{});
     }
     // the redundant loads issued past the end still target this block's LDS: drain them
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -719,7 +727,7 @@ __device__ __forceinline__ void big_tile(const dx_fwd_args &a, const tile_id &t,
 template <bool DOWN>
 __global__ __launch_bounds__(kBigThreads) void k_big(dx_fwd_args a)
 {
-    // the ring (128 KB) and the int4 side ring (24 KB); the staged output tile (256 rows of 512 + 16 bytes) reuses them
+    // the ring (128 KB) and the int4 side ring (20 KB); the staged output tile (256 rows of 512 + 16 bytes) reuses them
     __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
     __shared__ uint32_t cum[kMaxExperts + 1];
     __shared__ uint32_t wave_tot[kBigThreads / 64];
