@@ -384,10 +384,10 @@ def main():
             # decode, whole layer call: all three matrices of every activated expert (+ the shared expert) once,
             # x and the logits in, y and the routing arrays out
             step_bytes += n_hi_act * b_hi + n_lo_act * b_lo + b_sh + 2 * T * d * 2 + T * E * 4 + T * k * 12 + E * 8
-            # prefill: the 256-row tile kernel multiplies the leading multiple of 256 rows of every bf16
-            # segment: 2 * rows * d * 2f each
-            # (no bf16 experts in the int4 / int2 pair: there the 128-row tile kernel takes every segment above 32)
-            rows = (counts[hi] // 256 * 256).sum() if not quant_pair else counts[counts > 32].sum()
+            # prefill: the 256-row tile kernel multiplies the leading multiple of 256 rows of every bf16 and
+            # every int4 segment (not of int2 segments): 2 * rows * d * 2f each
+            big = hi if quant_pair else np.ones_like(hi)
+            rows = (counts[big] // 256 * 256).sum()
             alg_flops += float(rows) * 2.0 * d * 2 * f
         alg_per_launch, flops_per_launch, step_bytes_per_call = alg_bytes / L, alg_flops / L, step_bytes / L
 
@@ -448,7 +448,7 @@ def main():
         routed = False
         achieved = flops_per_launch / (gate_up_us * 1e-6) / 1e12
         step_flops = float(T * k) * 2.0 * d * 3 * f      # all routed pairs through gate, up and down
-        roofline = {"bound": "mfma", "kernel": "k_tiled<gate/up>" if quant_pair else "k_big<gate/up>", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+        roofline = {"bound": "mfma", "kernel": "k_big<gate/up>", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                     "algorithmic_flops_per_launch": flops_per_launch, "avg_launch_us": gate_up_us,
                     "note": "timed while the 128-row tile and streaming kernels of the same pass run beside it "
