@@ -548,13 +548,15 @@ def test_forward_prefill_int4_segments_of_256_rows_and_more(B, LY, dxo, T, E, k,
     ly.ctx.close()
 
 
-@pytest.mark.parametrize("T", [150, 600])
-def test_forward_prefill_with_shared_expert(B, LY, dxo, T):
+@pytest.mark.parametrize("T,E,group,resident", [(150, 16, 128, [0, 5, 9]), (600, 16, 128, [0, 5, 9]),
+                                               # 256-row tiles of the shared expert, of a bf16 and of int4 experts in one launch
+                                               (1100, 4, 64, [1])])
+def test_forward_prefill_with_shared_expert(B, LY, dxo, T, E, group, resident):
     import dataclasses
-    wl = dataclasses.replace(WORKLOADS["C4"], L=1, E=16, k=4, T=T, d=256, f=128, shared_f=256, group=128)
+    wl = dataclasses.replace(WORKLOADS["C4"], L=1, E=E, k=min(4, E), T=T, d=256, f=128, shared_f=256, group=group)
     x, logits = W.layer_inputs(wl, seed=8)
     shared = W.shared_master(wl, 8, 0)
-    ly = Layer(B, LY, dxo, wl, [0, 5, 9], seed=8, shared=shared)
+    ly = Layer(B, LY, dxo, wl, resident, seed=8, shared=shared)
     y_gpu, y_ref = ly.run(x, logits)
     err = rel_l2(y_gpu, y_ref)
     print("  prefill shared rel-L2", err, flush=True)
